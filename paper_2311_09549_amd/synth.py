@@ -1,0 +1,180 @@
+"""Seeded synthetic inputs for the sparse-times-dense contraction kernels.
+
+This module only draws random coordinates, values and dense factors.  It holds
+none of the contraction arithmetic and imports neither the HIP library nor the
+CPU oracle, so that both sides can be fed exactly the same inputs.
+
+The paper evaluates on SuiteSparse / Network Repository / FROSTT / DARPA
+tensors (Section 6, Table 1) that are not redistributable here; the generators
+below stand in for them: Zipf-skewed mode coordinates imitate the power-law
+mode-degree distributions of the web / FROSTT tensors, and the uniform 200^3
+tensor imitates the uniform-sparsity motivating cases of Section 3.1.
+
+Recipe (all draws from numpy ``default_rng([1000 + config_id, stream])``):
+
+* ``Zipf(s)`` over a domain of size ``n``: ``P(rank r) ~ r**-s`` for
+  ``r = 1..n``; a rank is mapped to a coordinate through a seeded random
+  permutation of ``0..n-1`` (stream 10 + mode).
+* coordinates are drawn in rounds (stream 0), de-duplicated, and the first
+  ``nnz`` distinct coordinates in draw order are kept ("top-up" reading of
+  "drawn ... then deduplicated"), so the realised ``nnz`` equals the target;
+* the kept coordinates are sorted lexicographically (mode 0 slowest);
+* values ~ U[-1, 1] (stream 1), assigned in sorted order;
+* dense factors (stream 2 + factor index) ~ U[-1, 1] or N(0, 1).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# kind -> (expression string, sparse order, number of factors)
+KINDS = {
+    "ttmc3": ("A(i,l,m)=B(i,j,k)*C(j,l)*D(k,m)", 3, 2),
+    "mttkrp3": ("A(i,r)=B(i,j,k)*C(j,r)*D(k,r)", 3, 2),
+    "sddmm_spmm": ("A(i,l)=S(i,j)*X(i,k)*Y(j,k)*Z(j,l)", 2, 3),
+    "ttmc4": ("A(i,l,m,n)=B(i,j,k,p)*C(j,l)*D(k,m)*E(p,n)", 4, 3),
+}
+
+CONFIGS = {
+    1: dict(kind="ttmc3", dtype="f64", dims=(200, 200, 200), nnz=8_000,
+            coord=("uniform",) * 3, ranks=(8, 8), factor_dist="uniform"),
+    2: dict(kind="mttkrp3", dtype="f32", dims=(50_000, 20_000, 10_000), nnz=20_000_000,
+            coord=(("zipf", 1.2),) * 3, ranks=(32,), factor_dist="normal"),
+    3: dict(kind="ttmc3", dtype="f32", dims=(100_000, 50_000, 20_000), nnz=30_000_000,
+            coord=(("zipf", 1.1),) * 3, ranks=(16, 16), factor_dist="normal"),
+    4: dict(kind="sddmm_spmm", dtype="f32", dims=(1_000_000, 1_000_000), nnz=16_000_000,
+            coord=(("zipf", 1.3), "uniform"), ranks=(64, 64), factor_dist="normal"),
+    5: dict(kind="ttmc4", dtype="f32", dims=(10_000,) * 4, nnz=50_000_000,
+            coord=(("zipf", 1.1),) * 4, ranks=(8, 8, 8), factor_dist="normal"),
+}
+
+
+def config(config_id: int, scale: float = 1.0) -> dict:
+    """Return a copy of config ``config_id``; ``scale < 1`` shrinks every sparse
+    dimension by ``scale`` and nnz by ``scale`` (ranks and distributions kept)."""
+    c = dict(CONFIGS[config_id])
+    c["id"] = config_id
+    if scale != 1.0:
+        c["dims"] = tuple(max(4, int(round(d * scale))) for d in c["dims"])
+        space = float(np.prod([float(d) for d in c["dims"]]))
+        c["nnz"] = int(max(1, min(round(c["nnz"] * scale), space // 4)))
+    c["expr"] = KINDS[c["kind"]][0]
+    return c
+
+
+def _zipf_cdf(n: int, s: float) -> np.ndarray:
+    w = np.arange(1, n + 1, dtype=np.float64) ** (-s)
+    cdf = np.cumsum(w)
+    cdf /= cdf[-1]
+    return cdf
+
+
+class _ModeSampler:
+    def __init__(self, spec, n: int, seed_key):
+        self.n = n
+        if spec == "uniform" or spec == ("uniform",):
+            self.cdf = None
+            self.perm = None
+        else:
+            name, s = spec
+            assert name == "zipf"
+            self.cdf = _zipf_cdf(n, float(s))
+            self.perm = np.random.default_rng(seed_key).permutation(n).astype(np.int64)
+
+    def draw(self, rng, count: int) -> np.ndarray:
+        if self.cdf is None:
+            return rng.integers(0, self.n, size=count, dtype=np.int64)
+        r = np.searchsorted(self.cdf, rng.random(count), side="right")
+        np.minimum(r, self.n - 1, out=r)
+        return self.perm[r]
+
+
+def draw_coords(dims, nnz: int, coord_specs, seed: int) -> np.ndarray:
+    """First ``nnz`` distinct coordinates in draw order, returned sorted
+    lexicographically as an int32 array of shape [order, nnz]."""
+    order = len(dims)
+    space = 1
+    for d in dims:
+        space *= int(d)
+    if nnz > space:
+        raise ValueError("nnz exceeds the coordinate space")
+    samplers = [_ModeSampler(coord_specs[m], int(dims[m]), [seed, 10 + m]) for m in range(order)]
+    rng = np.random.default_rng([seed, 0])
+    have = np.empty(0, dtype=np.int64)  # sorted distinct linearised keys
+    while have.size < nnz:
+        need = nnz - have.size
+        count = int(min(max(need * 1.3, 4096), 40_000_000))
+        key = np.zeros(count, dtype=np.int64)
+        for m in range(order):
+            key *= int(dims[m])
+            key += samplers[m].draw(rng, count)
+        uniq, first = np.unique(key, return_index=True)
+        del key
+        if have.size:
+            loc = np.searchsorted(have, uniq)
+            loc[loc == have.size] = have.size - 1
+            fresh = have[loc] != uniq
+            uniq, first = uniq[fresh], first[fresh]
+        if uniq.size > need:  # keep the earliest-drawn ones
+            keep = np.argpartition(first, need - 1)[:need]
+            uniq = np.sort(uniq[keep])
+        have = uniq if have.size == 0 else np.union1d(have, uniq)
+    coords = np.empty((order, nnz), dtype=np.int32)
+    rem = have
+    for m in range(order - 1, -1, -1):
+        rem, c = np.divmod(rem, int(dims[m]))
+        coords[m] = c.astype(np.int32)
+    return coords
+
+
+def draw_values(nnz: int, dtype, seed: int) -> np.ndarray:
+    rng = np.random.default_rng([seed, 1])
+    return rng.uniform(-1.0, 1.0, size=nnz).astype(dtype)
+
+
+def draw_factor(rows: int, cols: int, dist: str, dtype, seed: int, index: int) -> np.ndarray:
+    rng = np.random.default_rng([seed, 2 + index])
+    if dist == "uniform":
+        a = rng.uniform(-1.0, 1.0, size=(rows, cols))
+    elif dist == "normal":
+        a = rng.standard_normal(size=(rows, cols))
+    else:
+        raise ValueError(dist)
+    return np.ascontiguousarray(a.astype(dtype))
+
+
+def factor_shapes(cfg: dict):
+    """(rows, cols) of each dense factor, in expression order."""
+    kind, dims, ranks = cfg["kind"], cfg["dims"], cfg["ranks"]
+    if kind == "ttmc3":
+        return [(dims[1], ranks[0]), (dims[2], ranks[1])]
+    if kind == "mttkrp3":
+        return [(dims[1], ranks[0]), (dims[2], ranks[0])]
+    if kind == "sddmm_spmm":
+        return [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1])]
+    if kind == "ttmc4":
+        return [(dims[1], ranks[0]), (dims[2], ranks[1]), (dims[3], ranks[2])]
+    raise ValueError(kind)
+
+
+def output_shape(cfg: dict):
+    kind, dims, ranks = cfg["kind"], cfg["dims"], cfg["ranks"]
+    if kind == "ttmc3":
+        return (dims[0], ranks[0], ranks[1])
+    if kind == "mttkrp3":
+        return (dims[0], ranks[0])
+    if kind == "sddmm_spmm":
+        return (dims[0], ranks[1])
+    if kind == "ttmc4":
+        return (dims[0], ranks[0], ranks[1], ranks[2])
+    raise ValueError(kind)
+
+
+def generate(cfg: dict) -> dict:
+    """Draw the sparse operand (sorted, distinct COO) and the dense factors."""
+    seed = 1000 + int(cfg.get("id", 0)) + int(cfg.get("seed_offset", 0)) * 100
+    dt = np.float64 if cfg["dtype"] == "f64" else np.float32
+    coords = draw_coords(cfg["dims"], cfg["nnz"], cfg["coord"], seed)
+    vals = draw_values(coords.shape[1], dt, seed)
+    factors = [draw_factor(r, c, cfg["factor_dist"], dt, seed, n)
+               for n, (r, c) in enumerate(factor_shapes(cfg))]
+    return dict(cfg=cfg, coords=coords, vals=vals, factors=factors)
