@@ -1,0 +1,217 @@
+/*
+ * libsparsecontract -- sparse-times-dense tensor contractions on one AMD MI355X (gfx950),
+ * executed under the fused / fissioned loop nests of "SparseAuto: An Auto-Scheduler for
+ * Sparse Tensor Computations Using Recursive Loop Nest Restructuring" (arXiv 2311.09549).
+ *
+ * The library executes a schedule; it does not search for one (the auto-scheduler of
+ * Section 5 is not part of it).  The caller names the expression and the schedule:
+ *
+ *   kernel 6 of Table 2   A(i,l,m)   = B(i,j,k) * C(j,l) * D(k,m)             ("ttmc3")
+ *   MTTKRP (Section 6)    A(i,r)     = B(i,j,k) * C(j,r) * D(k,r)             ("mttkrp3")
+ *   kernel 1 of Table 2   A(i,l)     = S(i,j) * X(i,k) * Y(j,k) * Z(j,l)      ("sddmm_spmm")
+ *   order-4 TTM chain     A(i,l,m,n) = B(i,j,k,p) * C(j,l) * D(k,m) * E(p,n)  ("ttmc4")
+ *
+ * Index names are free; the FIRST operand on the right-hand side is the sparse one, its
+ * first index must be the first output index, and the remaining operands are dense
+ * row-major matrices passed in expression order.  Anything outside this family is
+ * rejected with SC_ERR_EXPR_UNSUPPORTED.
+ *
+ * Conventions
+ *   - Every function returns an sc_status (0 = SC_OK), never throws, never aborts,
+ *     never prints.
+ *   - All views are BORROWED: the caller owns every buffer and keeps it alive for the
+ *     duration of the call (sc_execute: until the work queued on the stream has run).
+ *   - Coordinates and positions are int32 (as in the generated code of Figure 1b);
+ *     values are fp32 or fp64; dense operands are row-major with leading dimension `ld`
+ *     (in elements), the rank index contiguous; the output is dense, row-major, last
+ *     index fastest, and is fully overwritten (rows of empty slices become +0).
+ *   - `on_device` says whether the pointers of a view are host (0) or device (1) memory.
+ *   - sc_execute allocates nothing, never synchronises and launches only on the stream
+ *     it is given.  sc_plan_create may allocate a few small plan-owned device tables.
+ */
+#ifndef SPARSECONTRACT_H
+#define SPARSECONTRACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SC_OK = 0,
+    SC_ERR_NULL,              /* a required pointer argument is NULL */
+    SC_ERR_BAD_ORDER,         /* sparse order outside 2..4, or it disagrees with the expression */
+    SC_ERR_BAD_DTYPE,         /* unknown dtype, or operands of different dtypes */
+    SC_ERR_BAD_DIMS,          /* a dimension, nnz or node count is negative / inconsistent / overflows int32 */
+    SC_ERR_BAD_POS,           /* a pos array is not monotone, has an empty node, or has wrong end points */
+    SC_ERR_CRD_RANGE,         /* a coordinate is outside [0, dim) */
+    SC_ERR_UNSORTED,          /* coordinates are not in lexicographic order */
+    SC_ERR_DUPLICATE,         /* the same coordinate is stored twice */
+    SC_ERR_EXPR_PARSE,        /* the expression string is not well-formed index notation */
+    SC_ERR_EXPR_UNSUPPORTED,  /* well-formed, but not a member of the supported family */
+    SC_ERR_SCHED_UNSUPPORTED, /* schedule kind / fuse depth / intermediate name not available */
+    SC_ERR_SHAPE_MISMATCH,    /* operand shapes disagree with the expression or with the plan */
+    SC_ERR_WORKSPACE_SMALL,   /* workspace_bytes < sc_plan_workspace_bytes() */
+    SC_ERR_DEVICE,            /* no usable GPU, a HIP call failed, or a host view was given where a device view is needed */
+    SC_ERR_ALLOC              /* host allocation failed */
+} sc_status;
+
+typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
+
+/* Schedule classes of Section 4.2: LINEAR = the perfectly nested default nest;
+ * FISSIONED = producer and consumer split, the temporary fully materialised (in the
+ * workspace, in HBM); FUSED = producer and consumer fused under their common outer
+ * loops, the live temporary kept on chip (registers / LDS). */
+typedef enum { SC_SCHED_LINEAR = 0, SC_SCHED_FUSED = 1, SC_SCHED_FISSIONED = 2 } sc_sched_kind;
+
+typedef struct sc_plan sc_plan;
+
+/* Sorted coordinate list (Section 2.1): crd[m][z] is the mode-m coordinate of stored
+ * entry z; entries are in strictly increasing lexicographic order (mode 0 slowest). */
+typedef struct {
+    int32_t order;            /* 2..4 */
+    int64_t dims[4];
+    int64_t nnz;
+    sc_dtype dtype;
+    const int32_t *crd[4];
+    const void *vals;         /* nnz values of `dtype` */
+    int32_t on_device;
+} sc_coo_view;
+
+/* Compressed sparse fiber tree (Section 2.1), every level compressed:
+ *   level 0:  crd[0][s], s < nfib[0]          -- the non-empty top-level slices
+ *   level m:  pos[m][p] .. pos[m][p+1]        -- children of node p of level m-1  (nfib[m-1]+1 entries)
+ *             crd[m][c], c < nfib[m]          -- coordinate of node c
+ *   leaves:   nfib[order-1] == nnz; vals[z] belongs to leaf z.
+ * pos[0] is unused (may be NULL).  No node is empty. */
+typedef struct {
+    int32_t order;
+    int64_t dims[4];
+    int64_t nnz;
+    sc_dtype dtype;
+    int64_t nfib[4];
+    const int32_t *pos[4];
+    const int32_t *crd[4];
+    const void *vals;
+    int32_t on_device;
+} sc_csf_view;
+
+/* Row-major dense matrix: element (r, c) at data[r * ld + c]. */
+typedef struct {
+    const void *data;
+    int64_t rows, cols, ld;
+    sc_dtype dtype;
+} sc_dense_view;
+
+/* A schedule in closed form (the loopfuse directive of Section 4.4 with the split
+ * positions fixed by the expression family): its class, and for each temporary its name
+ * and the number of leading common loops fused.
+ *   n_intermediates  0 (LINEAR), 1 (orders 2, 3) or 2 (order 4); 0 is also accepted for
+ *                    FUSED / FISSIONED and means "the derived ones".
+ *   intermediate[t]  optional text such as "T(i,j,m)" or "T1(i,j,k,n)"; when given, its
+ *                    index set must equal the one Section 4.2 derives (indices of the
+ *                    producer that also occur in the consumer or the output).
+ *   fuse_depth[t]    FISSIONED: must be 0.  FUSED: 0 = library's choice, otherwise
+ *                    1..(order-1): how many sparse loops producer and consumer share.
+ *                    All FUSED depths compute the same result; sc_plan_describe reports
+ *                    the on-chip granularity actually used.
+ *   deterministic    0: partial sums of rows that span work tiles are combined with
+ *                    floating-point atomics (order may vary from run to run).
+ *                    1: not available yet (SC_ERR_SCHED_UNSUPPORTED). */
+typedef struct {
+    sc_sched_kind kind;
+    int32_t n_intermediates;
+    const char *intermediate[2];
+    int32_t fuse_depth[2];
+    int32_t deterministic;
+} sc_schedule;
+
+/* Library version. */
+sc_status sc_version(int *major, int *minor);
+
+/* Static English text for a status code (never NULL). */
+const char *sc_status_string(sc_status s);
+
+/* Host helper, off the hot path.  Counts the nodes of every CSF level of a sorted,
+ * duplicate-free HOST coordinate list (Section 2.1).  Validates order, dims, coordinate
+ * ranges, ordering and uniqueness.  nfib_out[m] receives the node count of level m. */
+sc_status sc_coo_to_csf_sizes(const sc_coo_view *coo, int64_t nfib_out[4]);
+
+/* Host helper, off the hot path.  Fills a caller-allocated HOST CSF view: the caller sets
+ * out->pos[m] (nfib[m-1]+1 int32, m >= 1) and out->crd[m] (nfib[m] int32) to writable host
+ * arrays sized from sc_coo_to_csf_sizes, and out->vals either to NULL (the leaf order of a
+ * sorted coordinate list IS the CSF leaf order, so the COO value array can be reused) or to
+ * a writable array of nnz values, which is then filled.  order, dims, nnz, dtype, nfib and
+ * on_device(=0) are written by the call. */
+sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out);
+
+/* Validates everything and prepares execution (Section 4.2 for the derivation of the
+ * temporaries; Table 2 for the nests).  `expr` is index notation such as
+ * "A(i,l,m)=B(i,j,k)*C(j,l)*D(k,m)".  `sparse` may be a host or a device view: its pos
+ * arrays (and, for host views, its crd arrays) are checked and the equal-work tile tables
+ * are built from them.  Of `factors` only rows / cols / dtype are read.  If a GPU is
+ * present the tile tables are uploaded into plan-owned device memory; without one the plan
+ * is still created (for validation, sizing and description) but cannot execute. */
+sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
+                         const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched);
+
+/* Bytes of device workspace sc_execute needs (FISSIONED temporaries; 0 is possible). */
+sc_status sc_plan_workspace_bytes(const sc_plan *plan, size_t *bytes);
+
+/* Human-readable description: the forall/where text of the nest (Section 4.2 notation),
+ * the temporaries with their shapes, the flop and compulsory-byte model, tile counts.
+ * Always NUL-terminates; truncates to n-1 characters. */
+sc_status sc_plan_describe(const sc_plan *plan, char *buf, size_t n);
+
+/* Model figures of the planned schedule: flops (multiply = 1, add = 1) and compulsory HBM
+ * bytes (every input array and the output touched once; temporaries of a FISSIONED
+ * schedule written once and read once).  Either pointer may be NULL. */
+sc_status sc_plan_model(const sc_plan *plan, double *flops, double *bytes);
+
+/* Where FISSIONED temporary `index` lives inside the workspace: byte offset, rows (one per
+ * node of the sparse prefix level it is attached to) and columns.  For FUSED plans returns
+ * SC_ERR_SCHED_UNSUPPORTED (the temporary never exists in memory). */
+sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, size_t *offset_bytes,
+                               int64_t *rows, int64_t *cols);
+
+/* Runs the planned contraction on `hip_stream` (a hipStream_t; NULL = the default
+ * stream).  `sparse` and every factor must be DEVICE views with the structure sizes and
+ * shapes the plan was made for; `out` is device memory for the whole dense result;
+ * `workspace` is device memory of at least sc_plan_workspace_bytes() bytes, 256-byte
+ * aligned (may be NULL when that is 0).  Asynchronous: returns after queueing. */
+sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors,
+                     int32_t nfactors, void *out, void *workspace, size_t workspace_bytes,
+                     void *hip_stream);
+
+/* Optional per-kernel timing.  With profiling on, sc_execute brackets each kernel it
+ * launches with plan-owned HIP events on the caller's stream; after the caller has
+ * synchronised the stream, sc_plan_kernel_time reports the elapsed milliseconds of launch
+ * `index` of the most recent sc_execute and its name (name may be NULL). */
+sc_status sc_plan_set_profiling(sc_plan *plan, int32_t on);
+sc_status sc_plan_kernel_count(const sc_plan *plan, int32_t *count);
+sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, char *name, size_t name_len, float *ms);
+
+/* Work-tile introspection (for tests and reports).  A plan cuts the stored nonzeros into
+ * contiguous tiles of roughly equal work; rec receives {n0, n1, a0, na, b0, nb, c0, nc, flags}:
+ * the leaf range [n0, n1) and, for each CSF level above the leaves (a = parents of the
+ * leaves, b = the level above, c = the one above that), the first node and the node count
+ * the tile touches; flag bit 2*lvl is set when the first node of that level also has leaves
+ * in an earlier tile, bit 2*lvl+1 when the last node also has leaves in a later tile. */
+sc_status sc_plan_tile_count(const sc_plan *plan, int64_t *count);
+sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9]);
+
+/* Process-global tuning knobs; they affect plans created afterwards.  Names:
+ * "tile_leaves", "tile_nodes_a", "tile_nodes_b" (upper bounds on the leaves / level-a /
+ * level-b nodes of one work tile; 0 restores the built-in choice).  Unknown names give
+ * SC_ERR_EXPR_PARSE; sc_plan_create rejects caps whose on-chip buffers do not fit. */
+sc_status sc_tuning_set(const char *name, int64_t value);
+
+/* Frees the plan and its device tables.  NULL is accepted. */
+sc_status sc_plan_destroy(sc_plan *plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPARSECONTRACT_H */

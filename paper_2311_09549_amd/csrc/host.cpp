@@ -1,0 +1,859 @@
+// Host side of libsparsecontract: status text, COO -> CSF conversion, expression parsing,
+// validation, derivation of the temporaries (Section 4.2), equal-work tile tables, the
+// flop / byte model and the C entry points.  All device work is in kernels.hip.
+#include <algorithm>
+#include <cctype>
+#include <cstdarg>
+#include <climits>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <set>
+#include <string>
+#include <vector>
+
+#include "plan.h"
+
+using namespace sck;
+
+// ------------------------------------------------------------------------------------------
+// small helpers
+// ------------------------------------------------------------------------------------------
+namespace {
+
+const char *kStatusText[] = {
+    "ok",
+    "a required pointer argument is NULL",
+    "sparse order must be 2, 3 or 4 and agree with the expression",
+    "unknown dtype or operands of different dtypes",
+    "a dimension, nnz or node count is negative, inconsistent or exceeds int32",
+    "a pos array is not strictly increasing from 0 to the child count",
+    "a coordinate is outside its dimension",
+    "coordinates are not in lexicographic order",
+    "a coordinate is stored twice",
+    "the expression is not well-formed index notation",
+    "the expression is not in the supported family",
+    "the schedule (kind, fuse depth, intermediate name, determinism or rank) is not available",
+    "operand shapes or alignment disagree with the expression or the plan",
+    "the workspace is smaller than sc_plan_workspace_bytes()",
+    "no usable GPU, a HIP call failed, or a host view was given where a device view is required",
+    "host allocation failed",
+};
+
+size_t esize(sc_dtype d) { return d == SC_F64 ? 8 : 4; }
+bool dtype_ok(sc_dtype d) { return d == SC_F32 || d == SC_F64; }
+
+struct Term {
+    std::string name;
+    std::vector<std::string> idx;
+};
+
+// term := ident '(' ident (',' ident)* ')'
+bool parse_term(const char *&p, Term &t)
+{
+    auto skip = [&]() { while (*p && isspace((unsigned char)*p)) ++p; };
+    auto ident = [&](std::string &s) {
+        skip();
+        if (!(isalpha((unsigned char)*p) || *p == '_')) return false;
+        const char *b = p;
+        while (isalnum((unsigned char)*p) || *p == '_' || *p == '\'') ++p;
+        s.assign(b, p);
+        return true;
+    };
+    t.idx.clear();
+    if (!ident(t.name)) return false;
+    skip();
+    if (*p != '(') return false;
+    ++p;
+    for (;;) {
+        std::string s;
+        if (!ident(s)) return false;
+        t.idx.push_back(s);
+        skip();
+        if (*p == ',') { ++p; continue; }
+        if (*p == ')') { ++p; break; }
+        return false;
+    }
+    return true;
+}
+
+// expr := term ('=' | '+=') term ('*' term)*
+bool parse_expr(const char *s, Term &lhs, std::vector<Term> &rhs)
+{
+    const char *p = s;
+    auto skip = [&]() { while (*p && isspace((unsigned char)*p)) ++p; };
+    if (!parse_term(p, lhs)) return false;
+    skip();
+    if (*p == '+') ++p;
+    if (*p != '=') return false;
+    ++p;
+    rhs.clear();
+    for (;;) {
+        Term t;
+        if (!parse_term(p, t)) return false;
+        rhs.push_back(t);
+        skip();
+        if (*p == '*') { ++p; continue; }
+        if (*p == '\0') break;
+        return false;
+    }
+    return true;
+}
+
+bool contains(const std::vector<std::string> &v, const std::string &s)
+{
+    return std::find(v.begin(), v.end(), s) != v.end();
+}
+
+std::string join(const std::string &name, const std::vector<std::string> &idx)
+{
+    std::string r = name + "(";
+    for (size_t i = 0; i < idx.size(); ++i) r += (i ? "," : "") + idx[i];
+    return r + ")";
+}
+
+struct Family {
+    Kind kind;
+    int slot_of_factor[3];  // canonical slot -> position among the dense factors (0-based after the sparse operand)
+    std::vector<std::vector<std::string>> temp_idx;  // derived temporaries, deepest producer first
+    std::vector<std::string> temp_name;
+};
+
+// Classify a parsed expression into the supported family and derive the index sets of the
+// temporaries: indices of the producer that also occur in the consumer or in the output
+// (worked example of Section 4.2).  The producer always starts at the sparse operand and
+// absorbs the factors from the LAST sparse mode backwards, so that each temporary is
+// attached to a prefix of the CSF tree.
+sc_status classify(const Term &lhs, const std::vector<Term> &rhs, Family &fam)
+{
+    if (rhs.size() < 2) return SC_ERR_EXPR_UNSUPPORTED;
+    const Term &sp = rhs[0];
+    const size_t d = sp.idx.size();
+    if (d < 2 || d > 4) return SC_ERR_EXPR_UNSUPPORTED;
+    {
+        std::set<std::string> u(sp.idx.begin(), sp.idx.end());
+        if (u.size() != d) return SC_ERR_EXPR_UNSUPPORTED;
+    }
+    if (lhs.idx.empty() || lhs.idx[0] != sp.idx[0]) return SC_ERR_EXPR_UNSUPPORTED;
+    const size_t nf = rhs.size() - 1;
+    for (size_t f = 1; f <= nf; ++f)
+        if (rhs[f].idx.size() != 2 || rhs[f].idx[0] == rhs[f].idx[1]) return SC_ERR_EXPR_UNSUPPORTED;
+
+    auto find_on = [&](const std::string &first, int skip_pos) -> int {
+        for (size_t f = 1; f <= nf; ++f)
+            if ((int)f != skip_pos && rhs[f].idx[0] == first) return (int)f;
+        return -1;
+    };
+
+    if (d == 2 && nf == 3) {
+        // S(i,j) * X(i,k) * Y(j,k) * Z(j,l) -> A(i,l)
+        int x = find_on(sp.idx[0], -1);
+        if (x < 0) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &k = rhs[x].idx[1];
+        int y = -1, z = -1;
+        for (size_t f = 1; f <= nf; ++f) {
+            if ((int)f == x) continue;
+            if (rhs[f].idx[0] != sp.idx[1]) return SC_ERR_EXPR_UNSUPPORTED;
+            if (rhs[f].idx[1] == k) y = (int)f; else z = (int)f;
+        }
+        if (y < 0 || z < 0) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &l = rhs[z].idx[1];
+        if (contains(sp.idx, k) || contains(sp.idx, l)) return SC_ERR_EXPR_UNSUPPORTED;
+        if (lhs.idx.size() != 2 || lhs.idx[1] != l) return SC_ERR_EXPR_UNSUPPORTED;
+        fam.kind = K_SDDMM_SPMM;
+        fam.slot_of_factor[0] = x - 1; fam.slot_of_factor[1] = y - 1; fam.slot_of_factor[2] = z - 1;
+        fam.temp_idx = {{sp.idx[0], sp.idx[1]}};
+        fam.temp_name = {"T"};
+        return SC_OK;
+    }
+    if ((d == 3 && nf == 2) || (d == 4 && nf == 3)) {
+        int on[4] = {-1, -1, -1, -1};
+        for (size_t m = 1; m < d; ++m) {
+            on[m] = find_on(sp.idx[m], -1);
+            if (on[m] < 0) return SC_ERR_EXPR_UNSUPPORTED;
+            for (size_t q = 1; q < m; ++q) if (on[q] == on[m]) return SC_ERR_EXPR_UNSUPPORTED;
+        }
+        std::vector<std::string> x;
+        for (size_t m = 1; m < d; ++m) {
+            const std::string &xi = rhs[on[m]].idx[1];
+            if (contains(sp.idx, xi)) return SC_ERR_EXPR_UNSUPPORTED;
+            x.push_back(xi);
+        }
+        for (size_t m = 1; m < d; ++m) fam.slot_of_factor[m - 1] = on[m] - 1;
+        const bool all_same = (x[0] == x[1]) && (d == 3);
+        std::set<std::string> ux(x.begin(), x.end());
+        if (d == 3 && all_same) {
+            if (lhs.idx.size() != 2 || lhs.idx[1] != x[0]) return SC_ERR_EXPR_UNSUPPORTED;
+            fam.kind = K_MTTKRP3;
+            fam.temp_idx = {{sp.idx[0], sp.idx[1], x[0]}};
+            fam.temp_name = {"T"};
+            return SC_OK;
+        }
+        if (ux.size() != x.size()) return SC_ERR_EXPR_UNSUPPORTED;
+        if (lhs.idx.size() != d) return SC_ERR_EXPR_UNSUPPORTED;
+        for (size_t m = 1; m < d; ++m) if (lhs.idx[m] != x[m - 1]) return SC_ERR_EXPR_UNSUPPORTED;
+        if (d == 3) {
+            fam.kind = K_TTMC3;
+            fam.temp_idx = {{sp.idx[0], sp.idx[1], x[1]}};
+            fam.temp_name = {"T"};
+        } else {
+            fam.kind = K_TTMC4;
+            fam.temp_idx = {{sp.idx[0], sp.idx[1], sp.idx[2], x[2]}, {sp.idx[0], sp.idx[1], x[1], x[2]}};
+            fam.temp_name = {"T1", "T2"};
+        }
+        return SC_OK;
+    }
+    return SC_ERR_EXPR_UNSUPPORTED;
+}
+
+// ------------------------------------------------------------------------------------------
+// structure validation
+// ------------------------------------------------------------------------------------------
+sc_status check_header(int32_t order, const int64_t *dims, int64_t nnz, sc_dtype dtype)
+{
+    if (order < 2 || order > 4) return SC_ERR_BAD_ORDER;
+    if (!dtype_ok(dtype)) return SC_ERR_BAD_DTYPE;
+    for (int m = 0; m < order; ++m)
+        if (dims[m] <= 0 || dims[m] > INT32_MAX) return SC_ERR_BAD_DIMS;
+    if (nnz < 0 || nnz > INT32_MAX - 4096) return SC_ERR_BAD_DIMS;
+    return SC_OK;
+}
+
+// Host arrays of a CSF view (copied from the device when needed).
+struct HostCsf {
+    std::vector<int32_t> pos_store[4], crd_store[4];
+    const int32_t *pos[4] = {nullptr, nullptr, nullptr, nullptr};
+    const int32_t *crd[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool have_crd = false;
+};
+
+sc_status fetch_csf(const sc_csf_view *v, HostCsf &h, bool want_crd)
+{
+    for (int m = 0; m < v->order; ++m) {
+        const int64_t npos = m ? v->nfib[m - 1] + 1 : 0;
+        const int64_t ncrd = v->nfib[m];
+        if (m && !v->pos[m]) return SC_ERR_NULL;
+        if (ncrd > 0 && !v->crd[m]) return SC_ERR_NULL;
+        if (!v->on_device) {
+            h.pos[m] = v->pos[m];
+            h.crd[m] = v->crd[m];
+            continue;
+        }
+        try {
+            if (m) h.pos_store[m].resize((size_t)npos);
+            if (want_crd) h.crd_store[m].resize((size_t)ncrd);
+        } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
+        if (m && hipMemcpy(h.pos_store[m].data(), v->pos[m], sizeof(int32_t) * (size_t)npos, hipMemcpyDeviceToHost) != hipSuccess)
+            return SC_ERR_DEVICE;
+        if (want_crd && ncrd &&
+            hipMemcpy(h.crd_store[m].data(), v->crd[m], sizeof(int32_t) * (size_t)ncrd, hipMemcpyDeviceToHost) != hipSuccess)
+            return SC_ERR_DEVICE;
+        h.pos[m] = m ? h.pos_store[m].data() : nullptr;
+        h.crd[m] = want_crd ? h.crd_store[m].data() : nullptr;
+    }
+    h.have_crd = want_crd || !v->on_device;
+    return SC_OK;
+}
+
+sc_status validate_csf(const sc_csf_view *v, const HostCsf &h)
+{
+    sc_status st = check_header(v->order, v->dims, v->nnz, v->dtype);
+    if (st != SC_OK) return st;
+    const int d = v->order;
+    if (v->nfib[d - 1] != v->nnz) return SC_ERR_BAD_DIMS;
+    for (int m = 0; m < d; ++m) {
+        if (v->nfib[m] < 0) return SC_ERR_BAD_DIMS;
+        if (m && v->nfib[m] < v->nfib[m - 1]) return SC_ERR_BAD_DIMS;
+        if ((v->nfib[m] == 0) != (v->nnz == 0)) return SC_ERR_BAD_DIMS;
+    }
+    if (v->nfib[0] > v->dims[0]) return SC_ERR_BAD_DIMS;
+    if (v->nnz > 0 && !v->vals) return SC_ERR_NULL;
+    for (int m = 1; m < d; ++m) {
+        const int32_t *pos = h.pos[m];
+        const int64_t np = v->nfib[m - 1];
+        if (pos[0] != 0 || pos[np] != v->nfib[m]) return SC_ERR_BAD_POS;
+        for (int64_t p = 0; p < np; ++p)
+            if (pos[p + 1] <= pos[p]) return SC_ERR_BAD_POS;
+    }
+    if (!h.have_crd) return SC_OK;
+    for (int m = 0; m < d; ++m) {
+        const int32_t *crd = h.crd[m];
+        const int64_t n = v->nfib[m];
+        for (int64_t c = 0; c < n; ++c)
+            if (crd[c] < 0 || crd[c] >= v->dims[m]) return SC_ERR_CRD_RANGE;
+        if (m == 0) {
+            for (int64_t c = 1; c < n; ++c) {
+                if (crd[c] == crd[c - 1]) return SC_ERR_DUPLICATE;
+                if (crd[c] < crd[c - 1]) return SC_ERR_UNSORTED;
+            }
+        } else {
+            const int32_t *pos = h.pos[m];
+            for (int64_t p = 0; p < v->nfib[m - 1]; ++p)
+                for (int64_t c = pos[p] + 1; c < pos[p + 1]; ++c) {
+                    if (crd[c] == crd[c - 1]) return SC_ERR_DUPLICATE;
+                    if (crd[c] < crd[c - 1]) return SC_ERR_UNSORTED;
+                }
+        }
+    }
+    return SC_OK;
+}
+
+sc_status validate_coo(const sc_coo_view *c)
+{
+    if (!c) return SC_ERR_NULL;
+    sc_status st = check_header(c->order, c->dims, c->nnz, c->dtype);
+    if (st != SC_OK) return st;
+    if (c->on_device) return SC_ERR_DEVICE;
+    if (c->nnz == 0) return SC_OK;
+    for (int m = 0; m < c->order; ++m)
+        if (!c->crd[m]) return SC_ERR_NULL;
+    for (int64_t z = 0; z < c->nnz; ++z) {
+        for (int m = 0; m < c->order; ++m)
+            if (c->crd[m][z] < 0 || c->crd[m][z] >= c->dims[m]) return SC_ERR_CRD_RANGE;
+        if (z) {
+            int cmp = 0;
+            for (int m = 0; m < c->order && cmp == 0; ++m)
+                cmp = (c->crd[m][z] > c->crd[m][z - 1]) - (c->crd[m][z] < c->crd[m][z - 1]);
+            if (cmp == 0) return SC_ERR_DUPLICATE;
+            if (cmp < 0) return SC_ERR_UNSORTED;
+        }
+    }
+    return SC_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// tiles
+// ------------------------------------------------------------------------------------------
+
+// Node of level `lvl` that contains node `x` of level `lvl + 1` (pos = pos[lvl + 1]).
+inline int32_t parent_of(const int32_t *pos, int64_t nparent, int32_t x)
+{
+    return (int32_t)(std::upper_bound(pos, pos + nparent + 1, x) - pos) - 1;
+}
+
+// Builds the tile table: leaves are cut into runs of at most caps.tn, shortened so that no
+// tile touches more than caps.ta level-a nodes (and caps.tb level-b nodes for order 4).
+void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, std::vector<TileRec> &tiles)
+{
+    const int d = v->order;
+    const int64_t nnz = v->nnz;
+    tiles.clear();
+    // level indices: leaves = d-1, a = d-2, b = d-3, c = d-4
+    const int la = d - 2, lb = d - 3, lc = d - 4;
+    int64_t n0 = 0;
+    while (n0 < nnz) {
+        TileRec t;
+        memset(&t, 0, sizeof(t));
+        int64_t n1 = std::min<int64_t>(n0 + caps.tn, nnz);
+        const int32_t a0 = parent_of(h.pos[la + 1], v->nfib[la], (int32_t)n0);
+        if ((int64_t)a0 + caps.ta < v->nfib[la]) n1 = std::min<int64_t>(n1, h.pos[la + 1][a0 + caps.ta]);
+        int32_t b0 = 0, c0 = 0;
+        if (lb >= 0) {
+            b0 = parent_of(h.pos[lb + 1], v->nfib[lb], a0);
+            if (d == 4 && (int64_t)b0 + caps.tb < v->nfib[lb])
+                n1 = std::min<int64_t>(n1, h.pos[la + 1][h.pos[lb + 1][b0 + caps.tb]]);
+        }
+        if (lc >= 0) c0 = parent_of(h.pos[lc + 1], v->nfib[lc], b0);
+        const int32_t a1 = parent_of(h.pos[la + 1], v->nfib[la], (int32_t)(n1 - 1));
+        t.n0 = (int32_t)n0; t.n1 = (int32_t)n1;
+        t.a0 = a0; t.na = a1 - a0 + 1;
+        int32_t flags = 0;
+        if (h.pos[la + 1][a0] < n0) flags |= 1;
+        if (h.pos[la + 1][a1 + 1] > n1) flags |= 2;
+        if (lb >= 0) {
+            const int32_t b1 = parent_of(h.pos[lb + 1], v->nfib[lb], a1);
+            t.b0 = b0; t.nb = b1 - b0 + 1;
+            if (h.pos[la + 1][h.pos[lb + 1][b0]] < n0) flags |= 4;
+            if (h.pos[la + 1][h.pos[lb + 1][b1 + 1]] > n1) flags |= 8;
+            if (lc >= 0) {
+                const int32_t c1 = parent_of(h.pos[lc + 1], v->nfib[lc], b1);
+                t.c0 = c0; t.nc = c1 - c0 + 1;
+                if (h.pos[la + 1][h.pos[lb + 1][h.pos[lc + 1][c0]]] < n0) flags |= 16;
+                if (h.pos[la + 1][h.pos[lb + 1][h.pos[lc + 1][c1 + 1]]] > n1) flags |= 32;
+            }
+        }
+        t.flags = flags;
+        tiles.push_back(t);
+        n0 = n1;
+    }
+}
+
+void appendf(std::string &s, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void appendf(std::string &s, const char *fmt, ...)
+{
+    char buf[1024];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    s += buf;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------
+// tuning knobs
+// ------------------------------------------------------------------------------------------
+sck::Tuning &sck::tuning()
+{
+    static Tuning t;
+    return t;
+}
+
+extern "C" sc_status sc_tuning_set(const char *name, int64_t value)
+{
+    if (!name) return SC_ERR_NULL;
+    if (value < 0 || value > (1 << 20)) return SC_ERR_BAD_DIMS;
+    Tuning &t = tuning();
+    if (!strcmp(name, "tile_leaves")) t.tn = (int32_t)value;
+    else if (!strcmp(name, "tile_nodes_a")) t.ta = (int32_t)value;
+    else if (!strcmp(name, "tile_nodes_b")) t.tb = (int32_t)value;
+    else return SC_ERR_EXPR_PARSE;
+    return SC_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// C entry points
+// ------------------------------------------------------------------------------------------
+extern "C" sc_status sc_version(int *major, int *minor)
+{
+    if (!major || !minor) return SC_ERR_NULL;
+    *major = 0;
+    *minor = 1;
+    return SC_OK;
+}
+
+extern "C" const char *sc_status_string(sc_status s)
+{
+    const int n = (int)(sizeof(kStatusText) / sizeof(kStatusText[0]));
+    if ((int)s < 0 || (int)s >= n) return "unknown status";
+    return kStatusText[(int)s];
+}
+
+extern "C" sc_status sc_coo_to_csf_sizes(const sc_coo_view *coo, int64_t nfib_out[4])
+{
+    if (!coo || !nfib_out) return SC_ERR_NULL;
+    sc_status st = validate_coo(coo);
+    if (st != SC_OK) return st;
+    for (int m = 0; m < 4; ++m) nfib_out[m] = 0;
+    const int d = coo->order;
+    for (int64_t z = 0; z < coo->nnz; ++z) {
+        // first level at which entry z differs from entry z-1: a new node starts there and below
+        int first = 0;
+        if (z) {
+            while (first < d && coo->crd[first][z] == coo->crd[first][z - 1]) ++first;
+        }
+        for (int m = first; m < d; ++m) nfib_out[m]++;
+    }
+    return SC_OK;
+}
+
+extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
+{
+    if (!coo || !out) return SC_ERR_NULL;
+    int64_t nfib[4];
+    sc_status st = sc_coo_to_csf_sizes(coo, nfib);
+    if (st != SC_OK) return st;
+    const int d = coo->order;
+    for (int m = 0; m < d; ++m) {
+        if (m && !out->pos[m]) return SC_ERR_NULL;
+        if (nfib[m] && !out->crd[m]) return SC_ERR_NULL;
+    }
+    int32_t *pos[4], *crd[4];
+    for (int m = 0; m < d; ++m) {
+        pos[m] = const_cast<int32_t *>(out->pos[m]);
+        crd[m] = const_cast<int32_t *>(out->crd[m]);
+    }
+    int64_t cnt[4] = {0, 0, 0, 0};
+    for (int64_t z = 0; z < coo->nnz; ++z) {
+        int first = 0;
+        if (z) {
+            while (first < d && coo->crd[first][z] == coo->crd[first][z - 1]) ++first;
+        }
+        for (int m = first; m < d; ++m) {
+            // a new node of level m; if its parent (level m-1) is new too, the parent's
+            // child range starts here
+            if (m > 0 && m - 1 >= first) pos[m][cnt[m - 1] - 1] = (int32_t)cnt[m];
+            crd[m][cnt[m]] = coo->crd[m][z];
+            cnt[m]++;
+        }
+    }
+    for (int m = 1; m < d; ++m) pos[m][nfib[m - 1]] = (int32_t)nfib[m];
+    if (out->vals && coo->nnz) {
+        if (!coo->vals) return SC_ERR_NULL;
+        memcpy(const_cast<void *>(out->vals), coo->vals, esize(coo->dtype) * (size_t)coo->nnz);
+    }
+    out->order = coo->order;
+    out->nnz = coo->nnz;
+    out->dtype = coo->dtype;
+    out->on_device = 0;
+    for (int m = 0; m < 4; ++m) {
+        out->dims[m] = m < d ? coo->dims[m] : 0;
+        out->nfib[m] = m < d ? nfib[m] : 0;
+    }
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
+                                    const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
+{
+    if (!out) return SC_ERR_NULL;
+    *out = nullptr;
+    if (!expr || !sparse || !factors || !sched) return SC_ERR_NULL;
+
+    Term lhs;
+    std::vector<Term> rhs;
+    if (!parse_expr(expr, lhs, rhs)) return SC_ERR_EXPR_PARSE;
+    Family fam;
+    sc_status st = classify(lhs, rhs, fam);
+    if (st != SC_OK) return st;
+    if ((int)rhs[0].idx.size() != sparse->order) return SC_ERR_BAD_ORDER;
+    if (nfactors != (int32_t)rhs.size() - 1) return SC_ERR_SHAPE_MISMATCH;
+
+    st = check_header(sparse->order, sparse->dims, sparse->nnz, sparse->dtype);
+    if (st != SC_OK) return st;
+    HostCsf h;
+    st = fetch_csf(sparse, h, /*want_crd=*/true);
+    if (st != SC_OK) return st;
+    st = validate_csf(sparse, h);
+    if (st != SC_OK) return st;
+
+    sc_plan *p = new (std::nothrow) sc_plan();
+    if (!p) return SC_ERR_ALLOC;
+    struct Guard {
+        sc_plan *p;
+        ~Guard() { if (p) sc_plan_destroy(p); }
+    } guard{p};
+
+    p->kind = fam.kind;
+    p->dtype = sparse->dtype;
+    p->order = sparse->order;
+    p->nnz = sparse->nnz;
+    for (int m = 0; m < 4; ++m) { p->dims[m] = sparse->dims[m]; p->nfib[m] = sparse->nfib[m]; }
+    p->nfactors = nfactors;
+    for (int s = 0; s < nfactors; ++s) {
+        p->slot_of_factor[s] = fam.slot_of_factor[s];
+        const sc_dense_view &f = factors[fam.slot_of_factor[s]];
+        if (f.dtype != p->dtype) return dtype_ok(f.dtype) ? SC_ERR_BAD_DTYPE : SC_ERR_BAD_DTYPE;
+        if (f.rows <= 0 || f.cols <= 0 || f.cols > 4096) return SC_ERR_SHAPE_MISMATCH;
+        p->frows[s] = f.rows;
+        p->fcols[s] = f.cols;
+    }
+    // factor rows must equal the sparse dimension they index
+    switch (p->kind) {
+    case K_TTMC3:
+        if (p->frows[0] != p->dims[1] || p->frows[1] != p->dims[2]) return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[0] * p->fcols[1];
+        break;
+    case K_MTTKRP3:
+        if (p->frows[0] != p->dims[1] || p->frows[1] != p->dims[2] || p->fcols[0] != p->fcols[1]) return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[0];
+        break;
+    case K_SDDMM_SPMM:
+        if (p->frows[0] != p->dims[0] || p->frows[1] != p->dims[1] || p->frows[2] != p->dims[1] || p->fcols[0] != p->fcols[1])
+            return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[2];
+        break;
+    case K_TTMC4:
+        if (p->frows[0] != p->dims[1] || p->frows[1] != p->dims[2] || p->frows[2] != p->dims[3]) return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[0] * p->fcols[1] * p->fcols[2];
+        break;
+    }
+    p->out_elems = p->dims[0] * p->out_row_elems;
+
+    // ---- schedule ----
+    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    if (sched->deterministic != 0) return SC_ERR_SCHED_UNSUPPORTED;
+    p->sched = sched->kind;
+    p->n_inter = (int32_t)fam.temp_idx.size();
+    if (sched->n_intermediates != 0 && sched->n_intermediates != p->n_inter) return SC_ERR_SCHED_UNSUPPORTED;
+    for (int t = 0; t < p->n_inter; ++t) {
+        p->inter[t].name = join(fam.temp_name[t], fam.temp_idx[t]);
+        const int fd = sched->n_intermediates ? sched->fuse_depth[t] : 0;
+        if (sched->kind == SC_SCHED_FISSIONED && fd != 0) return SC_ERR_SCHED_UNSUPPORTED;
+        if (sched->kind == SC_SCHED_FUSED && (fd < 0 || fd > p->order - 1)) return SC_ERR_SCHED_UNSUPPORTED;
+        p->fuse_depth[t] = fd;
+    }
+    if (sched->n_intermediates) {
+        // each named temporary must match one of the derived index sets, each derived set at most once
+        bool used[2] = {false, false};
+        for (int t = 0; t < sched->n_intermediates; ++t) {
+            if (!sched->intermediate[t]) continue;
+            Term tt;
+            const char *q = sched->intermediate[t];
+            if (!parse_term(q, tt)) return SC_ERR_SCHED_UNSUPPORTED;
+            while (*q && isspace((unsigned char)*q)) ++q;
+            if (*q) return SC_ERR_SCHED_UNSUPPORTED;
+            std::set<std::string> got(tt.idx.begin(), tt.idx.end());
+            if (got.size() != tt.idx.size()) return SC_ERR_SCHED_UNSUPPORTED;
+            int match = -1;
+            for (int u = 0; u < p->n_inter; ++u) {
+                std::set<std::string> want(fam.temp_idx[u].begin(), fam.temp_idx[u].end());
+                if (!used[u] && want == got) { match = u; break; }
+            }
+            if (match < 0) return SC_ERR_SCHED_UNSUPPORTED;
+            used[match] = true;
+        }
+    }
+
+    // ---- tiles ----
+    p->caps = default_caps(p->kind, p->dtype, p->fcols);
+    if (p->caps.tn <= 0) return SC_ERR_SCHED_UNSUPPORTED;  // no kernel instantiated for these ranks
+    const Tuning &tu = tuning();
+    if (tu.tn) p->caps.tn = tu.tn;
+    if (tu.ta) p->caps.ta = tu.ta;
+    if (tu.tb) p->caps.tb = tu.tb;
+    if (lds_bytes_needed(p) > 64 * 1024) return SC_ERR_SCHED_UNSUPPORTED;
+    try {
+        build_tiles(sparse, h, p->caps, p->tiles);
+    } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
+
+    // ---- workspace, model, text ----
+    const double e = (double)esize(p->dtype);
+    const double nnz = (double)p->nnz;
+    const int d = p->order;
+    const double S = (double)p->nfib[0];
+    double flops = 0, bytes = 0, extra = 0;
+    size_t off = 0;
+    auto place = [&](int t, int64_t rows, int64_t cols) {
+        p->inter[t].rows = rows;
+        p->inter[t].cols = cols;
+        p->inter[t].offset = off;
+        off += ((size_t)rows * (size_t)cols * esize(p->dtype) + 255) & ~(size_t)255;
+    };
+    double fac_bytes = 0;
+    for (int s = 0; s < nfactors; ++s) fac_bytes += (double)p->frows[s] * (double)p->fcols[s] * e;
+    switch (p->kind) {
+    case K_TTMC3: {
+        const double F = (double)p->nfib[1], L = (double)p->fcols[0], M = (double)p->fcols[1];
+        flops = 2 * M * nnz + 2 * L * M * F;
+        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F * M * e;
+        place(0, p->nfib[1], p->fcols[1]);
+        break;
+    }
+    case K_MTTKRP3: {
+        const double F = (double)p->nfib[1], R = (double)p->fcols[0];
+        flops = 2 * R * (nnz + F);
+        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F * R * e;
+        place(0, p->nfib[1], p->fcols[0]);
+        break;
+    }
+    case K_SDDMM_SPMM: {
+        const double K = (double)p->fcols[0], L = (double)p->fcols[2];
+        flops = nnz * (2 * K + 1 + 2 * L);
+        // every array touched once (perfect reuse of the gathered rows)
+        bytes = nnz * (4 + e) + S * 8 + S * K * e + (double)p->frows[1] * (K + L) * e + (double)p->out_elems * e;
+        extra = 2 * nnz * e;
+        place(0, p->nnz, 1);
+        break;
+    }
+    case K_TTMC4: {
+        const double F2 = (double)p->nfib[1], F3 = (double)p->nfib[2];
+        const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
+        flops = 2 * N * nnz + 2 * M * N * F3 + 2 * L * M * N * F2;
+        bytes = nnz * (4 + e) + F3 * 8 + F2 * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F3 * N * e + 2 * F2 * M * N * e;
+        place(0, p->nfib[2], p->fcols[2]);
+        place(1, p->nfib[1], p->fcols[1] * p->fcols[2]);
+        break;
+    }
+    }
+    if (p->sched == SC_SCHED_FISSIONED) {
+        bytes += extra;
+        p->ws_bytes = off;
+    } else {
+        p->ws_bytes = 0;
+        for (int t = 0; t < p->n_inter; ++t) p->inter[t].offset = 0;
+    }
+    p->model_flops = flops;
+    p->model_bytes = bytes;
+
+    std::string &tx = p->text;
+    appendf(tx, "expression: %s\n", expr);
+    appendf(tx, "schedule: %s\n", p->sched == SC_SCHED_FUSED ? "FUSED (temporaries on chip)" : "FISSIONED (temporaries in the workspace)");
+    const std::vector<std::string> &si = rhs[0].idx;
+    switch (p->kind) {
+    case K_TTMC3:
+    case K_MTTKRP3: {
+        const std::string x = fam.temp_idx[0][2];
+        const std::string l = lhs.idx[1];
+        if (p->sched == SC_SCHED_FUSED)
+            appendf(tx, "nest: forall(tile of %s,%s', where(forall(%s', forall(%s, %s += T(%s',%s) * %s)), forall(%s',%s', forall(%s, T(%s',%s) += %s * %s))))\n",
+                    si[0].c_str(), si[1].c_str(), si[1].c_str(), l.c_str(), join(lhs.name, lhs.idx).c_str(), si[1].c_str(), x.c_str(),
+                    rhs[p->slot_of_factor[0] + 1].name.c_str(), si[1].c_str(), si[2].c_str(), x.c_str(), si[1].c_str(), x.c_str(),
+                    rhs[0].name.c_str(), rhs[p->slot_of_factor[1] + 1].name.c_str());
+        else
+            appendf(tx, "nest: where(forall(%s,%s', forall(%s.., %s += %s * %s)), forall(%s,%s',%s', forall(%s, %s += %s * %s)))\n",
+                    si[0].c_str(), si[1].c_str(), l.c_str(), join(lhs.name, lhs.idx).c_str(), p->inter[0].name.c_str(),
+                    rhs[p->slot_of_factor[0] + 1].name.c_str(), si[0].c_str(), si[1].c_str(), si[2].c_str(), x.c_str(),
+                    p->inter[0].name.c_str(), rhs[0].name.c_str(), rhs[p->slot_of_factor[1] + 1].name.c_str());
+        break;
+    }
+    case K_SDDMM_SPMM:
+        appendf(tx, "nest: forall(%s, forall(%s', where(forall(l, A += t * Z), forall(k, t += S * X * Y))))%s\n", si[0].c_str(), si[1].c_str(),
+                p->sched == SC_SCHED_FUSED ? " with scalar t in registers" : " split into SDDMM and SpMM over the sampled values");
+        break;
+    case K_TTMC4:
+        appendf(tx, "nest: two-level where: %s from leaves, %s from %s, output from %s (%s)\n", p->inter[0].name.c_str(),
+                p->inter[1].name.c_str(), p->inter[0].name.c_str(), p->inter[1].name.c_str(),
+                p->sched == SC_SCHED_FUSED ? "both per tile in LDS" : "both in the workspace");
+        break;
+    }
+    for (int t = 0; t < p->n_inter; ++t)
+        appendf(tx, "temporary %d: %s, %lld x %lld, position-compressed along the sparse prefix%s\n", t, p->inter[t].name.c_str(),
+                (long long)p->inter[t].rows, (long long)p->inter[t].cols,
+                p->sched == SC_SCHED_FUSED ? ", live per tile only" : "");
+    appendf(tx, "structure: nnz=%lld", (long long)p->nnz);
+    for (int m = 0; m < d - 1; ++m) appendf(tx, " nodes[%d]=%lld", m, (long long)p->nfib[m]);
+    appendf(tx, "\ntiles: %zu (<= %d leaves, <= %d level-a nodes", p->tiles.size(), p->caps.tn, p->caps.ta);
+    if (d == 4) appendf(tx, ", <= %d level-b nodes", p->caps.tb);
+    appendf(tx, ")\nmodel: %.6g flops, %.6g compulsory HBM bytes, workspace %zu bytes\n", flops, bytes, p->ws_bytes);
+
+    // ---- device tables ----
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
+        if (!p->tiles.empty()) {
+            if (hipMalloc((void **)&p->d_tiles, sizeof(TileRec) * p->tiles.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(p->d_tiles, p->tiles.data(), sizeof(TileRec) * p->tiles.size(), hipMemcpyHostToDevice) != hipSuccess)
+                return SC_ERR_DEVICE;
+        }
+        p->has_device = true;
+    } else {
+        (void)hipGetLastError();
+    }
+    guard.p = nullptr;
+    *out = p;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_workspace_bytes(const sc_plan *plan, size_t *bytes)
+{
+    if (!plan || !bytes) return SC_ERR_NULL;
+    *bytes = plan->ws_bytes;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_describe(const sc_plan *plan, char *buf, size_t n)
+{
+    if (!plan || !buf) return SC_ERR_NULL;
+    if (n == 0) return SC_ERR_BAD_DIMS;
+    const size_t k = std::min(n - 1, plan->text.size());
+    memcpy(buf, plan->text.data(), k);
+    buf[k] = '\0';
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_model(const sc_plan *plan, double *flops, double *bytes)
+{
+    if (!plan) return SC_ERR_NULL;
+    if (flops) *flops = plan->model_flops;
+    if (bytes) *bytes = plan->model_bytes;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, size_t *offset_bytes, int64_t *rows, int64_t *cols)
+{
+    if (!plan) return SC_ERR_NULL;
+    if (plan->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
+    if (offset_bytes) *offset_bytes = plan->inter[index].offset;
+    if (rows) *rows = plan->inter[index].rows;
+    if (cols) *cols = plan->inter[index].cols;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_tile_count(const sc_plan *plan, int64_t *count)
+{
+    if (!plan || !count) return SC_ERR_NULL;
+    *count = (int64_t)plan->tiles.size();
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9])
+{
+    if (!plan || !rec) return SC_ERR_NULL;
+    if (index < 0 || index >= (int64_t)plan->tiles.size()) return SC_ERR_BAD_DIMS;
+    memcpy(rec, &plan->tiles[(size_t)index], 9 * sizeof(int32_t));
+    return SC_OK;
+}
+
+extern "C" sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors,
+                                void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!plan || !sparse || !factors || !out) return SC_ERR_NULL;
+    if (!plan->has_device) return SC_ERR_DEVICE;
+    if (!sparse->on_device) return SC_ERR_DEVICE;
+    if (nfactors != plan->nfactors) return SC_ERR_SHAPE_MISMATCH;
+    if (sparse->order != plan->order) return SC_ERR_BAD_ORDER;
+    if (sparse->dtype != plan->dtype) return SC_ERR_BAD_DTYPE;
+    if (sparse->nnz != plan->nnz) return SC_ERR_SHAPE_MISMATCH;
+    for (int m = 0; m < plan->order; ++m) {
+        if (sparse->dims[m] != plan->dims[m] || sparse->nfib[m] != plan->nfib[m]) return SC_ERR_SHAPE_MISMATCH;
+        if (plan->nnz > 0 && (!sparse->crd[m] || (m && !sparse->pos[m]))) return SC_ERR_NULL;
+    }
+    if (plan->nnz > 0 && !sparse->vals) return SC_ERR_NULL;
+    if ((uintptr_t)out % 16) return SC_ERR_SHAPE_MISMATCH;
+    sc_dense_view canon[3];
+    for (int s = 0; s < plan->nfactors; ++s) {
+        const sc_dense_view &f = factors[plan->slot_of_factor[s]];
+        if (!f.data) return SC_ERR_NULL;
+        if (f.dtype != plan->dtype) return SC_ERR_BAD_DTYPE;
+        if (f.rows != plan->frows[s] || f.cols != plan->fcols[s] || f.ld < f.cols) return SC_ERR_SHAPE_MISMATCH;
+        // rows are read with 16-byte vector loads
+        if ((uintptr_t)f.data % 16 || (f.ld * (int64_t)esize(f.dtype)) % 16) return SC_ERR_SHAPE_MISMATCH;
+        canon[s] = f;
+    }
+    if (workspace_bytes < plan->ws_bytes) return SC_ERR_WORKSPACE_SMALL;
+    if (plan->ws_bytes && (!workspace || (uintptr_t)workspace % 256)) return plan->ws_bytes && !workspace ? SC_ERR_NULL : SC_ERR_SHAPE_MISMATCH;
+    return launch_plan(plan, sparse, canon, out, workspace, (hipStream_t)hip_stream);
+}
+
+extern "C" sc_status sc_plan_set_profiling(sc_plan *plan, int32_t on)
+{
+    if (!plan) return SC_ERR_NULL;
+    if (on && !plan->events_made) {
+        if (!plan->has_device) return SC_ERR_DEVICE;
+        for (int i = 0; i < kMaxLaunches; ++i) {
+            if (hipEventCreate(&plan->ev_begin[i]) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipEventCreate(&plan->ev_end[i]) != hipSuccess) return SC_ERR_DEVICE;
+        }
+        plan->events_made = true;
+    }
+    plan->profiling = on != 0;
+    plan->n_launch = 0;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_kernel_count(const sc_plan *plan, int32_t *count)
+{
+    if (!plan || !count) return SC_ERR_NULL;
+    *count = plan->n_launch;
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, char *name, size_t name_len, float *ms)
+{
+    if (!plan || !ms) return SC_ERR_NULL;
+    if (!plan->profiling || !plan->events_made) return SC_ERR_SCHED_UNSUPPORTED;
+    if (index < 0 || index >= plan->n_launch) return SC_ERR_BAD_DIMS;
+    if (hipEventElapsedTime(ms, plan->ev_begin[index], plan->ev_end[index]) != hipSuccess) return SC_ERR_DEVICE;
+    if (name && name_len) {
+        snprintf(name, name_len, "%s", plan->launch_name[index]);
+    }
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_destroy(sc_plan *plan)
+{
+    if (!plan) return SC_OK;
+    if (plan->d_tiles) (void)hipFree(plan->d_tiles);
+    if (plan->events_made)
+        for (int i = 0; i < kMaxLaunches; ++i) {
+            (void)hipEventDestroy(plan->ev_begin[i]);
+            (void)hipEventDestroy(plan->ev_end[i]);
+        }
+    delete plan;
+    return SC_OK;
+}

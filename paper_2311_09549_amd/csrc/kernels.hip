@@ -1,0 +1,550 @@
+// HIP kernels of libsparsecontract for gfx950 (CDNA4, 64-wide wavefronts).
+//
+// Every kernel works on one "tile": a contiguous run of stored nonzeros (CSF leaves)
+// together with the CSF nodes above them (plan.h, TileRec).  Tiles are cut at plan time so
+// that each holds about the same number of nonzeros whatever the slice / fiber lengths;
+// heavy slices and fibers are therefore split across workgroups, and the pieces are
+// recombined at the end (LDS atomics inside a workgroup, global atomics on pre-zeroed
+// output rows between workgroups).
+//
+// Inside a tile the nests of Table 2 run as a chain of segmented reductions, one per CSF
+// level, each of the form
+//     out(parent, :) = sum over children c of parent:  f( in(c, :), Factor(crd[c], :) )
+// A "lane group" of LG = W / VEC adjacent lanes owns VEC consecutive elements of the
+// W-wide row; a workgroup holds G = 256 / LG lane groups and each walks a contiguous chunk
+// of the tile's children, keeping the running sum of the current parent in registers and
+// flushing it when the walk crosses a parent boundary.  Coordinates, values and boundary
+// positions are staged into LDS with coalesced loads first.
+#include <hip/hip_runtime.h>
+
+#include <climits>
+
+#include "plan.h"
+
+namespace sck {
+
+constexpr int NT = 256;  // threads per workgroup
+
+template <typename T, int N>
+struct alignas(sizeof(T) * N) Pack {
+    T v[N];
+};
+
+template <typename T>
+struct VecWidth {
+    static constexpr int value = 16 / (int)sizeof(T);
+};
+
+// Padded LDS index: spreads chunk starts that are a multiple of 32 words apart over banks.
+__device__ __forceinline__ int pidx(int i) { return i + (i >> 5); }
+__host__ __device__ constexpr int padded(int n) { return n + (n >> 5) + 1; }
+
+template <typename T>
+__device__ __forceinline__ void atomic_add(T *p, T v)
+{
+    atomicAdd(p, v);
+}
+
+// ------------------------------------------------------------------------------------------
+// fill
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(NT) fill_zero_kernel(T *__restrict__ p, int64_t n)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    const int64_t nvec = n / VEC;
+    Pack<T, VEC> z;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * NT)
+        reinterpret_cast<Pack<T, VEC> *>(p)[i] = z;
+    for (int64_t i = nvec * VEC + (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) p[i] = T(0);
+}
+
+// Zeroes the rows of a W-wide temporary that are shared between tiles (the first level-a
+// node of a tile that continues from the previous tile), so that the tiles can add their
+// pieces atomically.  `level` selects which node level the rows belong to (0 = a, 1 = b).
+template <typename T>
+__global__ void __launch_bounds__(NT) zero_shared_rows_kernel(const TileRec *__restrict__ tiles, int ntiles, int level,
+                                                              T *__restrict__ rows, int W)
+{
+    const int per = NT / 64;
+    const int t = blockIdx.x * per + threadIdx.x / 64;
+    if (t >= ntiles) return;
+    const TileRec tr = tiles[t];
+    const bool shared = (tr.flags >> (2 * level)) & 1;
+    if (!shared) return;
+    const int64_t row = level == 0 ? tr.a0 : tr.b0;
+    for (int x = threadIdx.x % 64; x < W; x += 64) rows[row * W + x] = T(0);
+}
+
+// ------------------------------------------------------------------------------------------
+// segmented walk of one lane group over children [gs, ge) of a tile
+//   bnd[lp] = first child (tile-local) of local parent lp; bnd[np] = child count; bnd[np+1] = INT_MAX
+//   load(c)            -> Item   (issues the memory reads for child c)
+//   apply(acc, item)             (adds child contribution into acc)
+//   emit(lp, acc, whole)         (parent lp finished or chunk ended; `whole` = the parent lies
+//                                 entirely inside this lane group's chunk)
+// ------------------------------------------------------------------------------------------
+template <int U, typename Acc, typename Item, typename Load, typename Apply, typename Emit>
+__device__ __forceinline__ void seg_walk(int gs, int ge, const int *bnd, int np, Load load, Apply apply, Emit emit)
+{
+    if (gs >= ge) return;
+    int lo = 0, hi = np;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (bnd[mid] <= gs) lo = mid; else hi = mid;
+    }
+    int lp = lo;
+    int pend = bnd[lp + 1];
+    bool whole = bnd[lp] >= gs;
+    Acc acc;
+    acc.clear();
+    for (int c = gs; c < ge; c += U) {
+        Item it[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (c + u < ge) it[u] = load(c + u);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (c + u < ge) {
+                apply(acc, it[u]);
+                if (c + u + 1 == pend) {
+                    emit(lp, acc, whole);
+                    acc.clear();
+                    whole = true;
+                    ++lp;
+                    pend = bnd[lp + 1];
+                }
+            }
+    }
+    if (bnd[lp] < ge) emit(lp, acc, false);
+}
+
+template <typename T, int VEC>
+struct AccVec {
+    T v[VEC];
+    __device__ __forceinline__ void clear()
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) v[i] = T(0);
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// Order-3 kernels:  T(f, x) = sum_{k' in fiber f} B * D(k, x)   then
+//   hadamard:  A(i, r)    += C(j, r) * T(f, r)                      (MTTKRP)
+//   outer:     A(i, l, m) += C(j, l) * T(f, m)                      (kernel 6 of Table 2)
+// MODE 0: fused (T lives in LDS for the tile)      -- FUSED schedule
+// MODE 1: producer only, T written to HBM          -- FISSIONED, first kernel
+// MODE 2: consumer only, T read back from HBM      -- FISSIONED, second kernel
+// CONS 0: hadamard; 1: outer product on the vector ALU (any L); 2: outer product on MFMA
+//         (fp32, L = W = 16)
+// ------------------------------------------------------------------------------------------
+struct Order3Args {
+    const TileRec *tiles;
+    const int32_t *crd1, *pos2, *crd2, *pos3, *crd3;
+    const void *vals;
+    const void *C;  // factor on mode 1 (rows = J)
+    const void *D;  // factor on mode 2 (rows = K)
+    int64_t ldC, ldD;
+    int32_t L;      // columns of C (outer only)
+    void *T;        // temporary rows (MODE 1 writes, MODE 2 reads)
+    void *A;
+    int32_t ta, tn; // caps used to carve LDS
+};
+
+template <typename T, int W>
+__host__ __device__ constexpr size_t order3_lds_bytes(int tn, int ta)
+{
+    return (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + (size_t)ta * W * sizeof(T) + 64;
+}
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int W, int MODE, int CONS>
+__global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int LG = W / VEC;   // lanes per row
+    constexpr int G = NT / LG;    // lane groups per workgroup
+    static_assert(W % VEC == 0 && (LG & (LG - 1)) == 0 && LG <= 64, "row width");
+    using P = Pack<T, VEC>;
+    using Acc = AccVec<T, VEC>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    // carve LDS (T_s first: it needs 16-byte alignment)
+    T *T_s = reinterpret_cast<T *>(smem);
+    T *val_s = T_s + (size_t)a.ta * W;
+    int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
+    int *ba_s = crd_s + padded(a.tn);    // ta + 2
+    int *crda_s = ba_s + a.ta + 2;       // ta
+    int *bb_s = crda_s + a.ta;           // ta + 2
+    int *crdb_s = bb_s + a.ta + 2;       // ta
+
+    const TileRec t = a.tiles[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int nchild = t.n1 - t.n0;
+    const int na = t.na, nb = t.nb;
+
+    // ---- stage ----
+    if (MODE != 2) {
+        const T *vals = static_cast<const T *>(a.vals);
+        for (int i = tid; i < nchild; i += NT) {
+            crd_s[pidx(i)] = a.crd3[t.n0 + i];
+            val_s[pidx(i)] = vals[t.n0 + i];
+        }
+        for (int i = tid; i <= na; i += NT) {
+            const int b = a.pos3[t.a0 + i];
+            ba_s[i] = min(max(b, t.n0), t.n1) - t.n0;
+        }
+        if (tid == 0) ba_s[na + 1] = INT_MAX;
+    }
+    if (MODE != 1) {
+        for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
+        for (int i = tid; i <= nb; i += NT) {
+            const int b = a.pos2[t.b0 + i];
+            bb_s[i] = min(max(b, t.a0), t.a0 + na) - t.a0;
+        }
+        if (tid == 0) bb_s[nb + 1] = INT_MAX;
+        for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
+    }
+    if (MODE == 2) {
+        const P *Tg = reinterpret_cast<const P *>(static_cast<const T *>(a.T) + (int64_t)t.a0 * W);
+        for (int i = tid; i < na * LG; i += NT) reinterpret_cast<P *>(T_s)[i] = Tg[i];
+    } else {
+        P z;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
+        for (int i = tid; i < na * LG; i += NT) reinterpret_cast<P *>(T_s)[i] = z;
+    }
+    __syncthreads();
+
+    const int g = tid / LG, li = tid % LG;
+
+    // ---- producer: leaves -> T_s ----
+    if (MODE != 2) {
+        const T *D = static_cast<const T *>(a.D);
+        const int q = (nchild + G - 1) / G;
+        const int gs = g * q, ge = min(gs + q, nchild);
+        struct Item { T v; P d; };
+        seg_walk<4, Acc, Item>(
+            gs, ge, ba_s, na,
+            [&](int c) {
+                Item it;
+                const int k = crd_s[pidx(c)];
+                it.v = val_s[pidx(c)];
+                it.d = *reinterpret_cast<const P *>(D + (int64_t)k * a.ldD + li * VEC);
+                return it;
+            },
+            [&](Acc &acc, const Item &it) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc.v[i] += it.v * it.d.v[i];
+            },
+            [&](int lp, const Acc &acc, bool whole) {
+                T *dst = T_s + lp * W + li * VEC;
+                if (whole) {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) dst[i] = acc.v[i];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) atomic_add(dst + i, acc.v[i]);
+                }
+            });
+        __syncthreads();
+    }
+
+    if (MODE == 1) {
+        // write the tile's rows of T; rows shared with a neighbouring tile are added atomically
+        T *Tg = static_cast<T *>(a.T) + (int64_t)t.a0 * W;
+        for (int i = tid; i < na * LG; i += NT) {
+            const int lf = i / LG;
+            const bool shared = (lf == 0 && (t.flags & 1)) || (lf == na - 1 && (t.flags & 2));
+            const P v = reinterpret_cast<const P *>(T_s)[i];
+            if (!shared) {
+                reinterpret_cast<P *>(Tg)[i] = v;
+            } else {
+#pragma unroll
+                for (int x = 0; x < VEC; ++x) atomic_add(Tg + (int64_t)i * VEC + x, v.v[x]);
+            }
+        }
+        return;
+    }
+
+    // ---- consumer: T_s -> A ----
+    // In the consumer-only kernel a fiber that continues from the previous tile belongs to
+    // the tile it starts in; skip it here.
+    const int cf0 = (MODE == 2 && (t.flags & 1)) ? 1 : 0;
+    const T *C = static_cast<const T *>(a.C);
+    T *A = static_cast<T *>(a.A);
+    auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
+
+    if (CONS == 0) {
+        const int nfib = na - cf0;
+        const int q = (nfib + G - 1) / G;
+        const int gs = cf0 + g * q, ge = min(gs + q, na);
+        struct Item { P c; P tt; };
+        seg_walk<4, Acc, Item>(
+            gs, ge, bb_s, nb,
+            [&](int lf) {
+                Item it;
+                it.c = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf] * a.ldC + li * VEC);
+                it.tt = *reinterpret_cast<const P *>(T_s + lf * W + li * VEC);
+                return it;
+            },
+            [&](Acc &acc, const Item &it) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc.v[i] += it.c.v[i] * it.tt.v[i];
+            },
+            [&](int ls, const Acc &acc, bool whole) {
+                T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
+                if (whole && !slice_shared(ls)) {
+                    P o;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) o.v[i] = acc.v[i];
+                    *reinterpret_cast<P *>(dst) = o;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) atomic_add(dst + i, acc.v[i]);
+                }
+            });
+    } else if (CONS == 1) {
+        // generic outer product on the vector ALU: every thread owns output elements (l, m)
+        // and runs over the tile's slices and fibers in order
+        const int L = a.L;
+        for (int e = tid; e < L * W; e += NT) {
+            const int l = e / W, m = e % W;
+            for (int ls = 0; ls < nb; ++ls) {
+                const int f0 = max(bb_s[ls], cf0), f1 = bb_s[ls + 1];
+                if (f0 >= f1) continue;
+                T acc = T(0);
+                for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crda_s[lf] * a.ldC + l] * T_s[lf * W + m];
+                T *dst = A + (int64_t)crdb_s[ls] * L * W + e;
+                if (!slice_shared(ls)) *dst = acc; else atomic_add(dst, acc);
+            }
+        }
+    } else {
+        // MFMA outer product, fp32, L = W = 16:  A(i, 16x16) += Csel^T (16 x Kf) * T (Kf x 16),
+        // Kf = fibers of the slice, four fibers per v_mfma_f32_16x16x4_f32.
+        if constexpr (sizeof(T) == 4 && W == 16) {
+            const int wave = tid / 64, lane = tid % 64;
+            const int nfib = na - cf0;
+            const int qf = (((nfib + 3) / 4) + 3) / 4 * 4;  // fibers per wave, multiple of 4
+            const int ws = cf0 + wave * qf, we = min(ws + qf, na);
+            if (ws < we) {
+                const int kk = lane / 16, col = lane % 16;
+                int lo = 0, hi = nb;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (bb_s[mid] <= ws) lo = mid; else hi = mid;
+                }
+                int ls = lo;
+                int send = bb_s[ls + 1];
+                bool whole = bb_s[ls] >= ws;
+                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                auto emit = [&](int s, bool wh) {
+                    float *dst = reinterpret_cast<float *>(A) + (int64_t)crdb_s[s] * 256 + col;
+                    if (wh && !slice_shared(s)) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) dst[(4 * kk + r) * 16] = acc[r];
+                    } else {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) atomic_add(dst + (4 * kk + r) * 16, acc[r]);
+                    }
+                };
+                for (int fb = ws; fb < we; fb += 4) {
+                    const int bend = min(fb + 4, we);
+                    const int lf = fb + kk;
+                    float cv = 0.f, tv = 0.f;
+                    if (lf < bend) {
+                        cv = reinterpret_cast<const float *>(C)[(int64_t)crda_s[lf] * a.ldC + col];
+                        tv = reinterpret_cast<const float *>(T_s)[lf * 16 + col];
+                    }
+                    int from = fb;  // fibers of this block in [from, bend) are not yet consumed
+                    for (;;) {
+                        const int upto = min(send, bend);
+                        const bool mine = lf >= from && lf < upto;
+                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv : 0.f, acc, 0, 0, 0);
+                        if (send <= bend) {
+                            emit(ls, whole);
+                            acc = floatx4{0.f, 0.f, 0.f, 0.f};
+                            whole = true;
+                            from = send;
+                            ++ls;
+                            send = bb_s[ls + 1];
+                            if (from >= bend) break;
+                        } else {
+                            break;
+                        }
+                    }
+                }
+                if (bb_s[ls] < we) emit(ls, false);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side: caps, LDS sizing, dispatch
+// ------------------------------------------------------------------------------------------
+namespace {
+
+bool rank_ok(int64_t w, sc_dtype dt)
+{
+    const int vec = dt == SC_F64 ? 2 : 4;
+    if (w % vec) return false;
+    const int64_t lg = w / vec;
+    return lg >= 1 && lg <= 64 && (lg & (lg - 1)) == 0;
+}
+
+int64_t producer_width(const sc_plan *p)
+{
+    switch (p->kind) {
+    case K_TTMC3: return p->fcols[1];
+    case K_MTTKRP3: return p->fcols[0];
+    default: return 0;
+    }
+}
+
+struct Launcher {
+    const sc_plan *plan;
+    hipStream_t stream;
+    sc_status status = SC_OK;
+    void begin(const char *name)
+    {
+        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
+        plan->launch_name[plan->n_launch] = name;
+        if (hipEventRecord(plan->ev_begin[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
+    }
+    void end()
+    {
+        if (hipGetLastError() != hipSuccess) status = SC_ERR_DEVICE;
+        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
+        if (hipEventRecord(plan->ev_end[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
+        plan->n_launch++;
+    }
+};
+
+template <typename T>
+void launch_fill(Launcher &ln, T *p, int64_t n, const char *name)
+{
+    if (n <= 0) return;
+    const int64_t nvec = (n + VecWidth<T>::value - 1) / VecWidth<T>::value;
+    const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, 256 * 16);
+    ln.begin(name);
+    fill_zero_kernel<T><<<blocks, NT, 0, ln.stream>>>(p, n);
+    ln.end();
+}
+
+template <typename T, int W>
+sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
+{
+    Launcher ln{p, stream};
+    launch_fill<T>(ln, static_cast<T *>(out), p->out_elems, "fill_output");
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0) return ln.status;
+    Order3Args a;
+    a.tiles = p->d_tiles;
+    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1]; a.pos3 = sp->pos[2]; a.crd3 = sp->crd[2];
+    a.vals = sp->vals;
+    a.C = fac[0].data; a.ldC = fac[0].ld;
+    a.D = fac[1].data; a.ldD = fac[1].ld;
+    a.L = (int32_t)p->fcols[0];
+    a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
+    a.A = out;
+    a.ta = p->caps.ta; a.tn = p->caps.tn;
+    const size_t lds = order3_lds_bytes<T, W>(a.tn, a.ta);
+    const bool had = p->kind == K_MTTKRP3;
+    const bool mfma = !had && sizeof(T) == 4 && W == 16 && a.L == 16;
+    if (p->sched == SC_SCHED_FUSED) {
+        if (had) {
+            ln.begin("mttkrp3_fused");
+            order3_kernel<T, W, 0, 0><<<ntiles, NT, lds, stream>>>(a);
+        } else if (mfma) {
+            ln.begin("ttmc3_fused_mfma");
+            order3_kernel<T, W, 0, 2><<<ntiles, NT, lds, stream>>>(a);
+        } else {
+            ln.begin("ttmc3_fused_valu");
+            order3_kernel<T, W, 0, 1><<<ntiles, NT, lds, stream>>>(a);
+        }
+        ln.end();
+    } else {
+        ln.begin("zero_shared_rows");
+        zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(a.T), W);
+        ln.end();
+        ln.begin("order3_traverse");
+        order3_kernel<T, W, 1, 0><<<ntiles, NT, lds, stream>>>(a);
+        ln.end();
+        if (had) {
+            ln.begin("mttkrp3_consume");
+            order3_kernel<T, W, 2, 0><<<ntiles, NT, lds, stream>>>(a);
+        } else if (mfma) {
+            ln.begin("ttmc3_consume_mfma");
+            order3_kernel<T, W, 2, 2><<<ntiles, NT, lds, stream>>>(a);
+        } else {
+            ln.begin("ttmc3_consume_valu");
+            order3_kernel<T, W, 2, 1><<<ntiles, NT, lds, stream>>>(a);
+        }
+        ln.end();
+    }
+    return ln.status;
+}
+
+template <typename T>
+sc_status dispatch_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
+{
+    switch (producer_width(p)) {
+    case 8: return run_order3<T, 8>(p, sp, fac, out, ws, stream);
+    case 16: return run_order3<T, 16>(p, sp, fac, out, ws, stream);
+    case 32: return run_order3<T, 32>(p, sp, fac, out, ws, stream);
+    case 64: return run_order3<T, 64>(p, sp, fac, out, ws, stream);
+    default: return SC_ERR_SCHED_UNSUPPORTED;
+    }
+}
+
+}  // namespace
+
+TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols)
+{
+    TileCaps c{0, 0, 0};
+    const int e = dtype == SC_F64 ? 8 : 4;
+    switch (kind) {
+    case K_TTMC3:
+    case K_MTTKRP3: {
+        const int64_t w = kind == K_TTMC3 ? fcols[1] : fcols[0];
+        if (!(w == 8 || w == 16 || w == 32 || w == 64) || !rank_ok(w, dtype)) return c;
+        c.tn = 1024;
+        // keep the T rows of a tile within 32 KB of LDS
+        c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(1024, (32 * 1024) / (w * e)));
+        break;
+    }
+    default: break;
+    }
+    return c;
+}
+
+size_t lds_bytes_needed(const sc_plan *p)
+{
+    const size_t e = p->dtype == SC_F64 ? 8 : 4;
+    switch (p->kind) {
+    case K_TTMC3:
+    case K_MTTKRP3:
+        return (size_t)padded(p->caps.tn) * (4 + e) + (size_t)(4 * p->caps.ta + 8) * 4 + (size_t)p->caps.ta * producer_width(p) * e + 64;
+    default: return 0;
+    }
+}
+
+sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
+{
+    p->n_launch = 0;
+    switch (p->kind) {
+    case K_TTMC3:
+    case K_MTTKRP3:
+        return p->dtype == SC_F64 ? dispatch_order3<double>(p, sp, fac, out, ws, stream)
+                                  : dispatch_order3<float>(p, sp, fac, out, ws, stream);
+    default:
+        return SC_ERR_SCHED_UNSUPPORTED;
+    }
+}
+
+}  // namespace sck

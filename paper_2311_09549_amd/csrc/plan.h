@@ -1,0 +1,107 @@
+// Internal definitions shared by the host planner and the HIP launchers of
+// libsparsecontract.  Not part of the public C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/sparsecontract.h"
+
+namespace sck {
+
+enum Kind { K_TTMC3 = 0, K_MTTKRP3 = 1, K_SDDMM_SPMM = 2, K_TTMC4 = 3 };
+
+// One work tile: a contiguous range of leaves (stored nonzeros) together with the range
+// of CSF nodes that contain them at every level above.  Level "a" is the parent level of
+// the leaves, "b" the level above it, "c" the one above that (unused levels are zero).
+//   order 2: a = rows
+//   order 3: a = (i,j) fibers, b = slices
+//   order 4: a = (i,j,k) fibers, b = (i,j) fibers, c = slices
+// A node that also has leaves outside [n0, n1) is "partial"; flag bit 2*lvl says the first
+// node of that level continues from the previous tile, bit 2*lvl+1 that the last node
+// continues into the next tile (lvl: a = 0, b = 1, c = 2).
+struct TileRec {
+    int32_t n0, n1;
+    int32_t a0, na;
+    int32_t b0, nb;
+    int32_t c0, nc;
+    int32_t flags;
+    int32_t pad[3];
+};
+static_assert(sizeof(TileRec) == 48, "TileRec layout");
+
+// Per-level caps of a tile (upper bounds on leaves / nodes it may hold); they size the LDS
+// arrays of the kernels.
+struct TileCaps {
+    int32_t tn;  // leaves
+    int32_t ta;  // level-a nodes
+    int32_t tb;  // level-b nodes (order 4 only; for order 3 the slice count is bounded by ta)
+};
+
+constexpr int kMaxLaunches = 8;
+
+struct Intermediate {
+    std::string name;   // e.g. "T(i,j,m)"
+    size_t offset = 0;  // byte offset inside the workspace (FISSIONED only)
+    int64_t rows = 0, cols = 0;
+};
+
+}  // namespace sck
+
+struct sc_plan {
+    sck::Kind kind;
+    sc_dtype dtype;
+    int32_t order;
+    int64_t dims[4];
+    int64_t nnz;
+    int64_t nfib[4];
+    int32_t nfactors;
+    int32_t slot_of_factor[3];   // canonical slot -> position in the caller's factor array
+    int64_t frows[3], fcols[3];  // canonical slots
+    int64_t out_elems;
+    int64_t out_row_elems;       // elements of one output row (per top-level slice)
+
+    sc_sched_kind sched;
+    int32_t fuse_depth[2];
+    int32_t n_inter;
+    sck::Intermediate inter[2];
+
+    sck::TileCaps caps;
+    std::vector<sck::TileRec> tiles;  // host copy
+    sck::TileRec *d_tiles = nullptr;  // plan-owned device copy
+    bool has_device = false;
+
+    size_t ws_bytes = 0;
+    double model_flops = 0, model_bytes = 0;
+    std::string text;  // description
+
+    // profiling
+    bool profiling = false;
+    mutable int32_t n_launch = 0;
+    mutable const char *launch_name[sck::kMaxLaunches];
+    hipEvent_t ev_begin[sck::kMaxLaunches];
+    hipEvent_t ev_end[sck::kMaxLaunches];
+    bool events_made = false;
+};
+
+namespace sck {
+
+// Process-global tuning overrides (0 = use the built-in choice).
+struct Tuning {
+    int32_t tn = 0, ta = 0, tb = 0;
+};
+Tuning &tuning();
+
+// Built-in tile caps for a contraction (host side; the kernels size their LDS from them).
+TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols);
+
+// Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
+size_t lds_bytes_needed(const sc_plan *plan);
+
+sc_status launch_plan(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac /*canonical order*/,
+                      void *out, void *workspace, hipStream_t stream);
+
+}  // namespace sck
