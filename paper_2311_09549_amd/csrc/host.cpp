@@ -350,7 +350,7 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
         int32_t b0 = 0, c0 = 0;
         if (lb >= 0) {
             b0 = parent_of(h.pos[lb + 1], v->nfib[lb], a0);
-            if (d == 4 && (int64_t)b0 + caps.tb < v->nfib[lb])
+            if (caps.tb > 0 && (int64_t)b0 + caps.tb < v->nfib[lb])
                 n1 = std::min<int64_t>(n1, h.pos[la + 1][h.pos[lb + 1][b0 + caps.tb]]);
         }
         if (lc >= 0) c0 = parent_of(h.pos[lc + 1], v->nfib[lc], b0);
@@ -597,7 +597,7 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     }
 
     // ---- tiles ----
-    p->caps = default_caps(p->kind, p->dtype, p->fcols);
+    p->caps = default_caps(p->kind, p->dtype, p->sched, p->fcols);
     if (p->caps.tn <= 0) return SC_ERR_SCHED_UNSUPPORTED;  // no kernel instantiated for these ranks
     const Tuning &tu = tuning();
     if (tu.tn) p->caps.tn = tu.tn;

@@ -4,8 +4,8 @@
 // together with the CSF nodes above them (plan.h, TileRec).  Tiles are cut at plan time so
 // that each holds about the same number of nonzeros whatever the slice / fiber lengths;
 // heavy slices and fibers are therefore split across workgroups, and the pieces are
-// recombined at the end (LDS atomics inside a workgroup, global atomics on pre-zeroed
-// output rows between workgroups).
+// recombined at the end (LDS atomics inside a workgroup, one global atomic per tile on
+// pre-zeroed output rows between workgroups).
 //
 // Inside a tile the nests of Table 2 run as a chain of segmented reductions, one per CSF
 // level, each of the form
@@ -15,8 +15,13 @@
 // of the tile's children, keeping the running sum of the current parent in registers and
 // flushing it when the walk crosses a parent boundary.  Coordinates, values and boundary
 // positions are staged into LDS with coalesced loads first.
+//
+// Because every stage is linear in its input, a node that is cut by a chunk or tile
+// boundary is simply treated as two nodes: each piece is pushed through the consumer
+// separately and only the final output rows need recombining.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <climits>
 
 #include "plan.h"
@@ -45,6 +50,17 @@ __device__ __forceinline__ void atomic_add(T *p, T v)
     atomicAdd(p, v);
 }
 
+// Largest lp in [0, np) with bnd[lp] <= x  (bnd[0] <= x < bnd[np] assumed).
+__device__ __forceinline__ int find_segment(const int *bnd, int np, int x)
+{
+    int lo = 0, hi = np;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (bnd[mid] <= x) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 // ------------------------------------------------------------------------------------------
 // fill
 // ------------------------------------------------------------------------------------------
@@ -61,9 +77,9 @@ __global__ void __launch_bounds__(NT) fill_zero_kernel(T *__restrict__ p, int64_
     for (int64_t i = nvec * VEC + (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) p[i] = T(0);
 }
 
-// Zeroes the rows of a W-wide temporary that are shared between tiles (the first level-a
-// node of a tile that continues from the previous tile), so that the tiles can add their
-// pieces atomically.  `level` selects which node level the rows belong to (0 = a, 1 = b).
+// Zeroes the rows of a W-wide temporary that are shared between tiles (the first node of a
+// tile that continues from the previous tile), so that the tiles can add their pieces
+// atomically.  `level` selects which node level the rows belong to (0 = a, 1 = b).
 template <typename T>
 __global__ void __launch_bounds__(NT) zero_shared_rows_kernel(const TileRec *__restrict__ tiles, int ntiles, int level,
                                                               T *__restrict__ rows, int W)
@@ -90,12 +106,7 @@ template <int U, typename Acc, typename Item, typename Load, typename Apply, typ
 __device__ __forceinline__ void seg_walk(int gs, int ge, const int *bnd, int np, Load load, Apply apply, Emit emit)
 {
     if (gs >= ge) return;
-    int lo = 0, hi = np;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (bnd[mid] <= gs) lo = mid; else hi = mid;
-    }
-    int lp = lo;
+    int lp = find_segment(bnd, np, gs);
     int pend = bnd[lp + 1];
     bool whole = bnd[lp] >= gs;
     Acc acc;
@@ -140,6 +151,12 @@ struct AccVec {
 // MODE 2: consumer only, T read back from HBM      -- FISSIONED, second kernel
 // CONS 0: hadamard; 1: outer product on the vector ALU (any L); 2: outer product on MFMA
 //         (fp32, L = W = 16)
+//
+// Output rows: a slice that lies entirely inside one lane group's chunk (or wave's chunk
+// for MFMA) and inside the tile is written with plain stores.  Pieces of a slice that is
+// split between lane groups are first summed in an LDS "slot" (one per lane group, keyed
+// by the group in which the slice starts), so that a tile issues at most one global
+// update per slice; that update is an atomic add if the slice is shared with another tile.
 // ------------------------------------------------------------------------------------------
 struct Order3Args {
     const TileRec *tiles;
@@ -151,13 +168,13 @@ struct Order3Args {
     int32_t L;      // columns of C (outer only)
     void *T;        // temporary rows (MODE 1 writes, MODE 2 reads)
     void *A;
-    int32_t ta, tn; // caps used to carve LDS
+    int32_t tn, ta, tb;  // caps used to carve LDS
 };
 
-template <typename T, int W>
-__host__ __device__ constexpr size_t order3_lds_bytes(int tn, int ta)
+template <typename T>
+__host__ __device__ constexpr size_t order3_lds_bytes(int W, int tn, int ta)
 {
-    return (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + (size_t)ta * W * sizeof(T) + 64;
+    return (size_t)ta * W * sizeof(T) + (size_t)NT * 16 + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + NT * 4 + 64;
 }
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
@@ -173,14 +190,15 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     using Acc = AccVec<T, VEC>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // carve LDS (T_s first: it needs 16-byte alignment)
-    T *T_s = reinterpret_cast<T *>(smem);
-    T *val_s = T_s + (size_t)a.ta * W;
+    T *T_s = reinterpret_cast<T *>(smem);                   // ta * W
+    T *slot_s = T_s + (size_t)a.ta * W;                     // NT * VEC  (16 bytes per thread)
+    T *val_s = slot_s + NT * VEC;                           // padded(tn)
     int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
     int *ba_s = crd_s + padded(a.tn);    // ta + 2
     int *crda_s = ba_s + a.ta + 2;       // ta
     int *bb_s = crda_s + a.ta;           // ta + 2
     int *crdb_s = bb_s + a.ta + 2;       // ta
+    int *slot_id = crdb_s + a.ta;        // up to NT
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
@@ -206,8 +224,18 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
             const int b = a.pos2[t.b0 + i];
             bb_s[i] = min(max(b, t.a0), t.a0 + na) - t.a0;
         }
-        if (tid == 0) bb_s[nb + 1] = INT_MAX;
+        if (tid == 0) {
+            bb_s[nb + 1] = INT_MAX;
+            // consumer-only kernel: the first fiber is skipped when it continues from the
+            // previous tile, so the first slice starts at fiber 1 as far as this tile goes
+            if (MODE == 2 && (t.flags & 1)) bb_s[0] = 1;
+        }
         for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
+        P z;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
+        reinterpret_cast<P *>(slot_s)[tid] = z;
+        slot_id[tid] = -1;
     }
     if (MODE == 2) {
         const P *Tg = reinterpret_cast<const P *>(static_cast<const T *>(a.T) + (int64_t)t.a0 * W);
@@ -228,7 +256,7 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
         const int q = (nchild + G - 1) / G;
         const int gs = g * q, ge = min(gs + q, nchild);
         struct Item { T v; P d; };
-        seg_walk<4, Acc, Item>(
+        seg_walk<8, Acc, Item>(
             gs, ge, ba_s, na,
             [&](int c) {
                 Item it;
@@ -281,8 +309,17 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 
     if (CONS == 0) {
         const int nfib = na - cf0;
-        const int q = (nfib + G - 1) / G;
+        const int q = max((nfib + G - 1) / G, 1);
         const int gs = cf0 + g * q, ge = min(gs + q, na);
+        auto direct = [&](int ls, const P &row) {
+            T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
+            if (!slice_shared(ls)) {
+                *reinterpret_cast<P *>(dst) = row;
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+            }
+        };
         struct Item { P c; P tt; };
         seg_walk<4, Acc, Item>(
             gs, ge, bb_s, nb,
@@ -297,17 +334,22 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
                 for (int i = 0; i < VEC; ++i) acc.v[i] += it.c.v[i] * it.tt.v[i];
             },
             [&](int ls, const Acc &acc, bool whole) {
-                T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
-                if (whole && !slice_shared(ls)) {
+                if (whole) {
                     P o;
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) o.v[i] = acc.v[i];
-                    *reinterpret_cast<P *>(dst) = o;
+                    direct(ls, o);
                 } else {
+                    const int slot = (max(bb_s[ls], cf0) - cf0) / q;
+                    T *dst = slot_s + slot * W + li * VEC;
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) atomic_add(dst + i, acc.v[i]);
+                    if (li == 0) slot_id[slot] = ls;
                 }
             });
+        __syncthreads();
+        const int ls = slot_id[g];
+        if (ls >= 0) direct(ls, *reinterpret_cast<const P *>(slot_s + g * W + li * VEC));
     } else if (CONS == 1) {
         // generic outer product on the vector ALU: every thread owns output elements (l, m)
         // and runs over the tile's slices and fibers in order
@@ -329,27 +371,32 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
         if constexpr (sizeof(T) == 4 && W == 16) {
             const int wave = tid / 64, lane = tid % 64;
             const int nfib = na - cf0;
-            const int qf = (((nfib + 3) / 4) + 3) / 4 * 4;  // fibers per wave, multiple of 4
+            const int qf = max((((nfib + 3) / 4) + 3) / 4 * 4, 4);  // fibers per wave, multiple of 4
             const int ws = cf0 + wave * qf, we = min(ws + qf, na);
+            float *Af = reinterpret_cast<float *>(A);
+            float *slotf = reinterpret_cast<float *>(slot_s);
             if (ws < we) {
                 const int kk = lane / 16, col = lane % 16;
-                int lo = 0, hi = nb;
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (bb_s[mid] <= ws) lo = mid; else hi = mid;
-                }
-                int ls = lo;
+                int ls = find_segment(bb_s, nb, ws);
                 int send = bb_s[ls + 1];
                 bool whole = bb_s[ls] >= ws;
                 floatx4 acc = {0.f, 0.f, 0.f, 0.f};
                 auto emit = [&](int s, bool wh) {
-                    float *dst = reinterpret_cast<float *>(A) + (int64_t)crdb_s[s] * 256 + col;
-                    if (wh && !slice_shared(s)) {
+                    if (wh) {
+                        float *dst = Af + (int64_t)crdb_s[s] * 256 + col;
+                        if (!slice_shared(s)) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) dst[(4 * kk + r) * 16] = acc[r];
+                            for (int r = 0; r < 4; ++r) dst[(4 * kk + r) * 16] = acc[r];
+                        } else {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) atomic_add(dst + (4 * kk + r) * 16, acc[r]);
+                        }
                     } else {
+                        const int slot = (max(bb_s[s], cf0) - cf0) / qf;
+                        float *dst = slotf + slot * 256 + col;
 #pragma unroll
                         for (int r = 0; r < 4; ++r) atomic_add(dst + (4 * kk + r) * 16, acc[r]);
+                        if (lane == 0) slot_id[slot] = s;
                     }
                 };
                 for (int fb = ws; fb < we; fb += 4) {
@@ -380,8 +427,171 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
                 }
                 if (bb_s[ls] < we) emit(ls, false);
             }
+            __syncthreads();
+            const int s = slot_id[wave];
+            if (s >= 0) {
+                float *dst = Af + (int64_t)crdb_s[s] * 256;
+                const bool sh = slice_shared(s);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int e = lane + 64 * r;
+                    const float v = slotf[wave * 256 + e];
+                    if (!sh) dst[e] = v; else atomic_add(dst + e, v);
+                }
+            }
         }
     }
+}
+
+// ------------------------------------------------------------------------------------------
+// MTTKRP, FUSED at fiber granularity: one walk over the nonzeros keeps the fiber sum T(r)
+// and the slice sum A(i, r) in registers (Table 2, kernel 8 producer: t += B * D, then
+// A += t * C at the end of each fiber).  C rows are requested together with the D rows of
+// the batch in which their fiber ends, so the two gathers overlap.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__host__ __device__ constexpr size_t mttkrp_lds_bytes(int tn, int ta, int tb)
+{
+    return (size_t)NT * 16 + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(2 * ta + 2 * tb + 8) * 4 + NT * 4 + 64;
+}
+
+template <typename T, int W>
+__global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int LG = W / VEC;
+    constexpr int G = NT / LG;
+    constexpr int U = 8;
+    using P = Pack<T, VEC>;
+    using Acc = AccVec<T, VEC>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T *slot_s = reinterpret_cast<T *>(smem);    // NT * VEC
+    T *val_s = slot_s + NT * VEC;               // padded(tn)
+    int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
+    int *ba_s = crd_s + padded(a.tn);   // ta + 2
+    int *crda_s = ba_s + a.ta + 2;      // ta
+    int *bb_s = crda_s + a.ta;          // tb + 2
+    int *crdb_s = bb_s + a.tb + 2;      // tb
+    int *slot_id = crdb_s + a.tb;       // NT
+
+    const TileRec t = a.tiles[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int nchild = t.n1 - t.n0;
+    const int na = t.na, nb = t.nb;
+    {
+        const T *vals = static_cast<const T *>(a.vals);
+        for (int i = tid; i < nchild; i += NT) {
+            crd_s[pidx(i)] = a.crd3[t.n0 + i];
+            val_s[pidx(i)] = vals[t.n0 + i];
+        }
+        for (int i = tid; i <= na; i += NT) {
+            const int b = a.pos3[t.a0 + i];
+            ba_s[i] = min(max(b, t.n0), t.n1) - t.n0;
+        }
+        if (tid == 0) ba_s[na + 1] = INT_MAX;
+        for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
+        for (int i = tid; i <= nb; i += NT) {
+            const int b = a.pos2[t.b0 + i];
+            bb_s[i] = min(max(b, t.a0), t.a0 + na) - t.a0;
+        }
+        if (tid == 0) bb_s[nb + 1] = INT_MAX;
+        for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
+        P z;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
+        reinterpret_cast<P *>(slot_s)[tid] = z;
+        slot_id[tid] = -1;
+    }
+    __syncthreads();
+
+    const int g = tid / LG, li = tid % LG;
+    const T *C = static_cast<const T *>(a.C);
+    const T *D = static_cast<const T *>(a.D);
+    T *A = static_cast<T *>(a.A);
+    auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
+    auto direct = [&](int ls, const P &row) {
+        T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
+        if (!slice_shared(ls)) {
+            *reinterpret_cast<P *>(dst) = row;
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+        }
+    };
+
+    const int q = max((nchild + G - 1) / G, 1);
+    const int gs = g * q, ge = min(gs + q, nchild);
+    if (gs < ge) {
+        int lf = find_segment(ba_s, na, gs);        // fiber of the apply cursor
+        int ls = find_segment(bb_s, nb, lf);        // its slice
+        int send = bb_s[ls + 1];                    // first fiber after slice ls
+        bool whole = ba_s[bb_s[ls]] >= gs;          // slice ls starts inside this chunk
+        int lf_l = lf, fend_l = ba_s[lf + 1];       // load cursor
+        Acc tsum, asum;
+        tsum.clear();
+        asum.clear();
+        auto emit = [&](int s, bool wh) {
+            if (wh) {
+                P o;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+                direct(s, o);
+            } else {
+                const int slot = ba_s[bb_s[s]] / q;
+                T *dst = slot_s + slot * W + li * VEC;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, asum.v[i]);
+                if (li == 0) slot_id[slot] = s;
+            }
+        };
+        for (int c = gs; c < ge; c += U) {
+            T v[U];
+            P d[U], cc[U];
+            bool fe[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (c + u < ge) {
+                    const int k = crd_s[pidx(c + u)];
+                    v[u] = val_s[pidx(c + u)];
+                    d[u] = *reinterpret_cast<const P *>(D + (int64_t)k * a.ldD + li * VEC);
+                    fe[u] = (c + u + 1 == fend_l);
+                    if (fe[u]) {
+                        cc[u] = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf_l] * a.ldC + li * VEC);
+                        ++lf_l;
+                        fend_l = ba_s[lf_l + 1];
+                    }
+                }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (c + u < ge) {
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) tsum.v[i] += v[u] * d[u].v[i];
+                    if (fe[u]) {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cc[u].v[i];
+                        tsum.clear();
+                        ++lf;
+                        if (lf == send) {
+                            emit(ls, whole);
+                            asum.clear();
+                            whole = true;
+                            ++ls;
+                            send = bb_s[ls + 1];
+                        }
+                    }
+                }
+        }
+        if (ba_s[lf] < ge) {  // the chunk ends inside fiber lf: push its piece through the consumer
+            const P cl = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf] * a.ldC + li * VEC);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cl.v[i];
+        }
+        if (ls < nb && ba_s[bb_s[ls]] < ge) emit(ls, false);
+    }
+    __syncthreads();
+    const int s = slot_id[g];
+    if (s >= 0) direct(s, *reinterpret_cast<const P *>(slot_s + g * W + li * VEC));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -452,14 +662,14 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.L = (int32_t)p->fcols[0];
     a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
     a.A = out;
-    a.ta = p->caps.ta; a.tn = p->caps.tn;
-    const size_t lds = order3_lds_bytes<T, W>(a.tn, a.ta);
+    a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
+    const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
     const bool had = p->kind == K_MTTKRP3;
     const bool mfma = !had && sizeof(T) == 4 && W == 16 && a.L == 16;
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
             ln.begin("mttkrp3_fused");
-            order3_kernel<T, W, 0, 0><<<ntiles, NT, lds, stream>>>(a);
+            mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
             ln.begin("ttmc3_fused_mfma");
             order3_kernel<T, W, 0, 2><<<ntiles, NT, lds, stream>>>(a);
@@ -502,9 +712,11 @@ sc_status dispatch_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dens
     }
 }
 
+bool uses_register_fused_mttkrp(const sc_plan *p) { return p->kind == K_MTTKRP3 && p->sched == SC_SCHED_FUSED; }
+
 }  // namespace
 
-TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols)
+TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols)
 {
     TileCaps c{0, 0, 0};
     const int e = dtype == SC_F64 ? 8 : 4;
@@ -514,8 +726,15 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols)
         const int64_t w = kind == K_TTMC3 ? fcols[1] : fcols[0];
         if (!(w == 8 || w == 16 || w == 32 || w == 64) || !rank_ok(w, dtype)) return c;
         c.tn = 1024;
-        // keep the T rows of a tile within 32 KB of LDS
-        c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(1024, (32 * 1024) / (w * e)));
+        if (kind == K_MTTKRP3 && sched == SC_SCHED_FUSED) {
+            // fiber sums live in registers: only boundary tables limit the node counts
+            c.ta = 512;
+            c.tb = 128;
+        } else {
+            // keep the T rows of a tile within 32 KB of LDS
+            c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(1024, (32 * 1024) / (w * e)));
+            c.tb = c.ta;
+        }
         break;
     }
     default: break;
@@ -525,11 +744,14 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols)
 
 size_t lds_bytes_needed(const sc_plan *p)
 {
-    const size_t e = p->dtype == SC_F64 ? 8 : 4;
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:
-        return (size_t)padded(p->caps.tn) * (4 + e) + (size_t)(4 * p->caps.ta + 8) * 4 + (size_t)p->caps.ta * producer_width(p) * e + 64;
+        if (uses_register_fused_mttkrp(p))
+            return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
+                                      : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
+        return p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
+                                  : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
     default: return 0;
     }
 }

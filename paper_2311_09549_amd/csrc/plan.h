@@ -96,7 +96,7 @@ struct Tuning {
 Tuning &tuning();
 
 // Built-in tile caps for a contraction (host side; the kernels size their LDS from them).
-TileCaps default_caps(Kind kind, sc_dtype dtype, const int64_t *fcols);
+TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols);
 
 // Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
 size_t lds_bytes_needed(const sc_plan *plan);

@@ -169,11 +169,30 @@ def output_shape(cfg: dict):
     raise ValueError(kind)
 
 
-def generate(cfg: dict) -> dict:
-    """Draw the sparse operand (sorted, distinct COO) and the dense factors."""
+def generate(cfg: dict, cache_dir: str | None = None) -> dict:
+    """Draw the sparse operand (sorted, distinct COO) and the dense factors.
+
+    ``cache_dir`` (optional) keeps the drawn coordinates of large workloads on disk so that
+    several processes of one session do not redraw them; the cache is keyed by every field
+    the draw depends on."""
+    import os
     seed = 1000 + int(cfg.get("id", 0)) + int(cfg.get("seed_offset", 0)) * 100
     dt = np.float64 if cfg["dtype"] == "f64" else np.float32
-    coords = draw_coords(cfg["dims"], cfg["nnz"], cfg["coord"], seed)
+    coords = None
+    path = None
+    if cache_dir is not None and cfg["nnz"] >= 1_000_000:
+        tag = "_".join(str(d) for d in cfg["dims"]) + f"_{cfg['nnz']}_{seed}_" + "_".join(
+            "u" if c in ("uniform", ("uniform",)) else f"z{c[1]}" for c in cfg["coord"])
+        path = os.path.join(cache_dir, f"coords_{tag}.npy")
+        if os.path.exists(path):
+            coords = np.load(path)
+    if coords is None:
+        coords = draw_coords(cfg["dims"], cfg["nnz"], cfg["coord"], seed)
+        if path is not None:
+            os.makedirs(cache_dir, exist_ok=True)
+            tmp = path + f".{os.getpid()}.tmp.npy"
+            np.save(tmp, coords)
+            os.replace(tmp, path)
     vals = draw_values(coords.shape[1], dt, seed)
     factors = [draw_factor(r, c, cfg["factor_dist"], dt, seed, n)
                for n, (r, c) in enumerate(factor_shapes(cfg))]
