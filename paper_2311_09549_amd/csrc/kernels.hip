@@ -446,13 +446,30 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 // ------------------------------------------------------------------------------------------
 // MTTKRP, FUSED at fiber granularity: one walk over the nonzeros keeps the fiber sum T(r)
 // and the slice sum A(i, r) in registers (Table 2, kernel 8 producer: t += B * D, then
-// A += t * C at the end of each fiber).  C rows are requested together with the D rows of
-// the batch in which their fiber ends, so the two gathers overlap.
+// A += t * C at the end of each fiber).
+//
+// Staging turns the tile's CSF arrays into one 16-byte LDS record per nonzero:
+//   koff  byte offset of the D row to gather
+//   v     the stored value
+//   e     byte offset of the C row if this nonzero is the last of its fiber (in the tile), else -1
+//   s     tile-local slice number if this nonzero is the last of its slice (in the tile), else -1
+// so the walk needs no boundary cursors or searches: a lane group reads one record per
+// nonzero, gathers D (and C when e >= 0, in the same batch of loads) and updates two
+// register accumulators.  Fibers / slices cut by a chunk boundary are described by two
+// small per-group tables (chunk_coff, chunk_ls) filled during staging.
 // ------------------------------------------------------------------------------------------
+template <typename T>
+struct alignas(sizeof(T) == 4 ? 16 : 8) NzRec {
+    uint32_t koff;
+    int32_t e;
+    int32_t s;
+    T v;
+};
+
 template <typename T>
 __host__ __device__ constexpr size_t mttkrp_lds_bytes(int tn, int ta, int tb)
 {
-    return (size_t)NT * 16 + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(2 * ta + 2 * tb + 8) * 4 + NT * 4 + 64;
+    return (size_t)NT * 16 + (size_t)padded(tn + 8) * sizeof(NzRec<T>) + (size_t)(2 * tb + 3 * NT) * 4 + 64;
 }
 
 template <typename T, int W>
@@ -461,53 +478,95 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
     constexpr int VEC = VecWidth<T>::value;
     constexpr int LG = W / VEC;
     constexpr int G = NT / LG;
-    constexpr int U = 8;
     using P = Pack<T, VEC>;
     using Acc = AccVec<T, VEC>;
+    using Rec = NzRec<T>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T *slot_s = reinterpret_cast<T *>(smem);    // NT * VEC
-    T *val_s = slot_s + NT * VEC;               // padded(tn)
-    int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
-    int *ba_s = crd_s + padded(a.tn);   // ta + 2
-    int *crda_s = ba_s + a.ta + 2;      // ta
-    int *bb_s = crda_s + a.ta;          // tb + 2
-    int *crdb_s = bb_s + a.tb + 2;      // tb
-    int *slot_id = crdb_s + a.tb;       // NT
+    T *slot_s = reinterpret_cast<T *>(smem);                       // NT * VEC
+    Rec *rec_s = reinterpret_cast<Rec *>(slot_s + NT * VEC);       // tn
+    int *slo_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // tb: first nonzero of each slice
+    int *crdb_s = slo_s + a.tb;                                    // tb: output row of each slice
+    int *chunk_coff = crdb_s + a.tb;                               // NT (G used)
+    int *chunk_ls = chunk_coff + NT;                               // NT (G used)
+    int *slot_id = chunk_ls + NT;                                  // NT (G used)
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
     const int nchild = t.n1 - t.n0;
     const int na = t.na, nb = t.nb;
+    constexpr int U = 4;                          // gathers kept in flight per lane
+    const int q = max(((nchild + G - 1) / G + U - 1) / U * U, U);   // nonzeros per lane group, multiple of U
+    const uint32_t rowD = (uint32_t)(a.ldD * sizeof(T)), rowC = (uint32_t)(a.ldC * sizeof(T));
+
+    // ---- stage 1: records, per-fiber and per-slice ranges (kept in registers) ----
     {
         const T *vals = static_cast<const T *>(a.vals);
-        for (int i = tid; i < nchild; i += NT) {
-            crd_s[pidx(i)] = a.crd3[t.n0 + i];
-            val_s[pidx(i)] = vals[t.n0 + i];
+        for (int c = tid; c < nchild; c += NT) {
+            Rec r;
+            r.koff = (uint32_t)a.crd3[t.n0 + c] * rowD;
+            r.v = vals[t.n0 + c];
+            r.e = -1;
+            r.s = -1;
+            rec_s[pidx(c)] = r;
         }
-        for (int i = tid; i <= na; i += NT) {
-            const int b = a.pos3[t.a0 + i];
-            ba_s[i] = min(max(b, t.n0), t.n1) - t.n0;
+        if (tid < U) {  // dummies that complete the last batch: value 0, row 0, no marks
+            Rec r;
+            r.koff = 0;
+            r.v = T(0);
+            r.e = -1;
+            r.s = -1;
+            rec_s[pidx(nchild + tid)] = r;
         }
-        if (tid == 0) ba_s[na + 1] = INT_MAX;
-        for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
-        for (int i = tid; i <= nb; i += NT) {
-            const int b = a.pos2[t.b0 + i];
-            bb_s[i] = min(max(b, t.a0), t.a0 + na) - t.a0;
-        }
-        if (tid == 0) bb_s[nb + 1] = INT_MAX;
-        for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
         P z;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
         reinterpret_cast<P *>(slot_s)[tid] = z;
         slot_id[tid] = -1;
+        chunk_coff[tid] = -1;
+        chunk_ls[tid] = -1;
+    }
+    constexpr int MAXF = 2;  // fibers per thread: ta <= MAXF * NT
+    int f_lo[MAXF], f_hi[MAXF];
+    uint32_t f_off[MAXF];
+#pragma unroll
+    for (int r = 0; r < MAXF; ++r) {
+        const int i = tid + r * NT;
+        f_lo[r] = f_hi[r] = 0;
+        f_off[r] = 0;
+        if (i < na) {
+            f_lo[r] = min(max(a.pos3[t.a0 + i], t.n0), t.n1) - t.n0;
+            f_hi[r] = min(max(a.pos3[t.a0 + i + 1], t.n0), t.n1) - t.n0;
+            f_off[r] = (uint32_t)a.crd2[t.a0 + i] * rowC;
+        }
+    }
+    int s_lo = 0, s_hi = 0;
+    if (tid < nb) {
+        const int flo = min(max(a.pos2[t.b0 + tid], t.a0), t.a0 + na);
+        const int fhi = min(max(a.pos2[t.b0 + tid + 1], t.a0), t.a0 + na);
+        s_lo = min(max(a.pos3[flo], t.n0), t.n1) - t.n0;
+        s_hi = min(max(a.pos3[fhi], t.n0), t.n1) - t.n0;
+        slo_s[tid] = s_lo;
+        crdb_s[tid] = a.crd1[t.b0 + tid];
+    }
+    __syncthreads();
+
+    // ---- stage 2: mark fiber ends, slice ends and the nodes cut by chunk boundaries ----
+#pragma unroll
+    for (int r = 0; r < MAXF; ++r)
+        if (f_hi[r] > f_lo[r]) {
+            rec_s[pidx(f_hi[r] - 1)].e = (int32_t)f_off[r];
+            for (int m = f_lo[r] / q + 1; m * q < f_hi[r]; ++m) chunk_coff[m - 1] = (int32_t)f_off[r];
+        }
+    if (s_hi > s_lo) {
+        rec_s[pidx(s_hi - 1)].s = tid;
+        for (int m = s_lo / q + 1; m * q < s_hi; ++m) chunk_ls[m - 1] = tid;
     }
     __syncthreads();
 
     const int g = tid / LG, li = tid % LG;
-    const T *C = static_cast<const T *>(a.C);
-    const T *D = static_cast<const T *>(a.D);
+    const char *Cb = static_cast<const char *>(a.C) + li * 16;
+    const char *Db = static_cast<const char *>(a.D) + li * 16;
     T *A = static_cast<T *>(a.A);
     auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
     auto direct = [&](int ls, const P &row) {
@@ -520,74 +579,65 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
         }
     };
 
-    const int q = max((nchild + G - 1) / G, 1);
     const int gs = g * q, ge = min(gs + q, nchild);
     if (gs < ge) {
-        int lf = find_segment(ba_s, na, gs);        // fiber of the apply cursor
-        int ls = find_segment(bb_s, nb, lf);        // its slice
-        int send = bb_s[ls + 1];                    // first fiber after slice ls
-        bool whole = ba_s[bb_s[ls]] >= gs;          // slice ls starts inside this chunk
-        int lf_l = lf, fend_l = ba_s[lf + 1];       // load cursor
+        bool started = (gs == 0) || (rec_s[pidx(gs - 1)].s >= 0);  // the current slice starts in this chunk
         Acc tsum, asum;
         tsum.clear();
         asum.clear();
-        auto emit = [&](int s, bool wh) {
-            if (wh) {
+        auto emit = [&](int s, bool whole) {
+            if (whole) {
                 P o;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
                 direct(s, o);
             } else {
-                const int slot = ba_s[bb_s[s]] / q;
+                const int slot = slo_s[s] / q;
                 T *dst = slot_s + slot * W + li * VEC;
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) atomic_add(dst + i, asum.v[i]);
                 if (li == 0) slot_id[slot] = s;
             }
         };
+        // Chunks start at multiples of U and the records up to the next multiple of U past
+        // the tile's last nonzero are zero-valued dummies, so every batch is a full,
+        // branch-free group of U gathers (the compiler can then keep all of them in flight).
         for (int c = gs; c < ge; c += U) {
-            T v[U];
+            Rec r[U];
             P d[U], cc[U];
-            bool fe[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (c + u < ge) {
-                    const int k = crd_s[pidx(c + u)];
-                    v[u] = val_s[pidx(c + u)];
-                    d[u] = *reinterpret_cast<const P *>(D + (int64_t)k * a.ldD + li * VEC);
-                    fe[u] = (c + u + 1 == fend_l);
-                    if (fe[u]) {
-                        cc[u] = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf_l] * a.ldC + li * VEC);
-                        ++lf_l;
-                        fend_l = ba_s[lf_l + 1];
-                    }
+            for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                d[u] = *reinterpret_cast<const P *>(Db + r[u].koff);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) cc[u].v[i] = T(0);
+                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + (uint32_t)r[u].e);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const bool fiber_end = r[u].e >= 0;
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) {
+                    tsum.v[i] += r[u].v * d[u].v[i];
+                    asum.v[i] += tsum.v[i] * cc[u].v[i];   // cc is zero unless the fiber ends here
+                    tsum.v[i] = fiber_end ? T(0) : tsum.v[i];
                 }
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (c + u < ge) {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) tsum.v[i] += v[u] * d[u].v[i];
-                    if (fe[u]) {
-#pragma unroll
-                        for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cc[u].v[i];
-                        tsum.clear();
-                        ++lf;
-                        if (lf == send) {
-                            emit(ls, whole);
-                            asum.clear();
-                            whole = true;
-                            ++ls;
-                            send = bb_s[ls + 1];
-                        }
-                    }
+                if (r[u].s >= 0) {
+                    emit(r[u].s, started);
+                    asum.clear();
+                    started = true;
                 }
+            }
         }
-        if (ba_s[lf] < ge) {  // the chunk ends inside fiber lf: push its piece through the consumer
-            const P cl = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf] * a.ldC + li * VEC);
+        const int co = chunk_coff[g];
+        if (co >= 0) {  // the chunk ends inside a fiber: push its piece through the consumer
+            const P cl = *reinterpret_cast<const P *>(Cb + (uint32_t)co);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cl.v[i];
         }
-        if (ls < nb && ba_s[bb_s[ls]] < ge) emit(ls, false);
+        const int cs = chunk_ls[g];
+        if (cs >= 0) emit(cs, false);  // ... and inside a slice
     }
     __syncthreads();
     const int s = slot_id[g];
@@ -665,6 +715,9 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
     const bool had = p->kind == K_MTTKRP3;
+    // factor rows are addressed with 32-bit byte offsets
+    for (int s = 0; s < 2; ++s)
+        if ((uint64_t)fac[s].rows * (uint64_t)fac[s].ld * sizeof(T) >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
     const bool mfma = !had && sizeof(T) == 4 && W == 16 && a.L == 16;
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
@@ -747,9 +800,12 @@ size_t lds_bytes_needed(const sc_plan *p)
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:
-        if (uses_register_fused_mttkrp(p))
+        if (uses_register_fused_mttkrp(p)) {
+            // one thread stages at most two fibers and one slice
+            if (p->caps.ta > 2 * NT || p->caps.tb > NT) return SIZE_MAX;
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
+        }
         return p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
     default: return 0;
