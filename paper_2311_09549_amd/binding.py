@@ -234,8 +234,11 @@ class Plan:
         self.destroy()
 
     def destroy(self):
-        if getattr(self, "_h", None):
-            lib().sc_plan_destroy(self._h)
+        if getattr(self, "_h", None) and _lib is not None:
+            try:
+                _lib.sc_plan_destroy(self._h)
+            except Exception:  # interpreter shutdown
+                pass
             self._h = None
 
     @property
