@@ -218,9 +218,9 @@ def schedule(kind, intermediates=(), fuse_depth=(), deterministic=False) -> Sche
     s = Schedule()
     s.kind = {"linear": SC_SCHED_LINEAR, "fused": SC_SCHED_FUSED, "fissioned": SC_SCHED_FISSIONED}.get(kind, kind)
     s.n_intermediates = len(intermediates)
-    for t, name in enumerate(intermediates):
+    for t, name in enumerate(list(intermediates)[:2]):
         s.intermediate[t] = name.encode() if name is not None else None
-    for t, d in enumerate(fuse_depth):
+    for t, d in enumerate(list(fuse_depth)[:2]):
         s.fuse_depth[t] = int(d)
     s.deterministic = int(deterministic)
     return s

@@ -19,128 +19,9 @@
 // Because every stage is linear in its input, a node that is cut by a chunk or tile
 // boundary is simply treated as two nodes: each piece is pushed through the consumer
 // separately and only the final output rows need recombining.
-#include <hip/hip_runtime.h>
-
-#include <algorithm>
-#include <climits>
-
-#include "plan.h"
+#include "device_common.h"
 
 namespace sck {
-
-constexpr int NT = 256;  // threads per workgroup
-
-template <typename T, int N>
-struct alignas(sizeof(T) * N) Pack {
-    T v[N];
-};
-
-template <typename T>
-struct VecWidth {
-    static constexpr int value = 16 / (int)sizeof(T);
-};
-
-// Padded LDS index: spreads chunk starts that are a multiple of 32 words apart over banks.
-__device__ __forceinline__ int pidx(int i) { return i + (i >> 5); }
-__host__ __device__ constexpr int padded(int n) { return n + (n >> 5) + 1; }
-
-template <typename T>
-__device__ __forceinline__ void atomic_add(T *p, T v)
-{
-    atomicAdd(p, v);
-}
-
-// Largest lp in [0, np) with bnd[lp] <= x  (bnd[0] <= x < bnd[np] assumed).
-__device__ __forceinline__ int find_segment(const int *bnd, int np, int x)
-{
-    int lo = 0, hi = np;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (bnd[mid] <= x) lo = mid; else hi = mid;
-    }
-    return lo;
-}
-
-// ------------------------------------------------------------------------------------------
-// fill
-// ------------------------------------------------------------------------------------------
-template <typename T>
-__global__ void __launch_bounds__(NT) fill_zero_kernel(T *__restrict__ p, int64_t n)
-{
-    constexpr int VEC = VecWidth<T>::value;
-    const int64_t nvec = n / VEC;
-    Pack<T, VEC> z;
-#pragma unroll
-    for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
-    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * NT)
-        reinterpret_cast<Pack<T, VEC> *>(p)[i] = z;
-    for (int64_t i = nvec * VEC + (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) p[i] = T(0);
-}
-
-// Zeroes the rows of a W-wide temporary that are shared between tiles (the first node of a
-// tile that continues from the previous tile), so that the tiles can add their pieces
-// atomically.  `level` selects which node level the rows belong to (0 = a, 1 = b).
-template <typename T>
-__global__ void __launch_bounds__(NT) zero_shared_rows_kernel(const TileRec *__restrict__ tiles, int ntiles, int level,
-                                                              T *__restrict__ rows, int W)
-{
-    const int per = NT / 64;
-    const int t = blockIdx.x * per + threadIdx.x / 64;
-    if (t >= ntiles) return;
-    const TileRec tr = tiles[t];
-    const bool shared = (tr.flags >> (2 * level)) & 1;
-    if (!shared) return;
-    const int64_t row = level == 0 ? tr.a0 : tr.b0;
-    for (int x = threadIdx.x % 64; x < W; x += 64) rows[row * W + x] = T(0);
-}
-
-// ------------------------------------------------------------------------------------------
-// segmented walk of one lane group over children [gs, ge) of a tile
-//   bnd[lp] = first child (tile-local) of local parent lp; bnd[np] = child count; bnd[np+1] = INT_MAX
-//   load(c)            -> Item   (issues the memory reads for child c)
-//   apply(acc, item)             (adds child contribution into acc)
-//   emit(lp, acc, whole)         (parent lp finished or chunk ended; `whole` = the parent lies
-//                                 entirely inside this lane group's chunk)
-// ------------------------------------------------------------------------------------------
-template <int U, typename Acc, typename Item, typename Load, typename Apply, typename Emit>
-__device__ __forceinline__ void seg_walk(int gs, int ge, const int *bnd, int np, Load load, Apply apply, Emit emit)
-{
-    if (gs >= ge) return;
-    int lp = find_segment(bnd, np, gs);
-    int pend = bnd[lp + 1];
-    bool whole = bnd[lp] >= gs;
-    Acc acc;
-    acc.clear();
-    for (int c = gs; c < ge; c += U) {
-        Item it[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (c + u < ge) it[u] = load(c + u);
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (c + u < ge) {
-                apply(acc, it[u]);
-                if (c + u + 1 == pend) {
-                    emit(lp, acc, whole);
-                    acc.clear();
-                    whole = true;
-                    ++lp;
-                    pend = bnd[lp + 1];
-                }
-            }
-    }
-    if (bnd[lp] < ge) emit(lp, acc, false);
-}
-
-template <typename T, int VEC>
-struct AccVec {
-    T v[VEC];
-    __device__ __forceinline__ void clear()
-    {
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) v[i] = T(0);
-    }
-};
 
 // ------------------------------------------------------------------------------------------
 // Order-3 kernels:  T(f, x) = sum_{k' in fiber f} B * D(k, x)   then
@@ -649,14 +530,6 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 // ------------------------------------------------------------------------------------------
 namespace {
 
-bool rank_ok(int64_t w, sc_dtype dt)
-{
-    const int vec = dt == SC_F64 ? 2 : 4;
-    if (w % vec) return false;
-    const int64_t lg = w / vec;
-    return lg >= 1 && lg <= 64 && (lg & (lg - 1)) == 0;
-}
-
 int64_t producer_width(const sc_plan *p)
 {
     switch (p->kind) {
@@ -664,36 +537,6 @@ int64_t producer_width(const sc_plan *p)
     case K_MTTKRP3: return p->fcols[0];
     default: return 0;
     }
-}
-
-struct Launcher {
-    const sc_plan *plan;
-    hipStream_t stream;
-    sc_status status = SC_OK;
-    void begin(const char *name)
-    {
-        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
-        plan->launch_name[plan->n_launch] = name;
-        if (hipEventRecord(plan->ev_begin[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
-    }
-    void end()
-    {
-        if (hipGetLastError() != hipSuccess) status = SC_ERR_DEVICE;
-        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
-        if (hipEventRecord(plan->ev_end[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
-        plan->n_launch++;
-    }
-};
-
-template <typename T>
-void launch_fill(Launcher &ln, T *p, int64_t n, const char *name)
-{
-    if (n <= 0) return;
-    const int64_t nvec = (n + VecWidth<T>::value - 1) / VecWidth<T>::value;
-    const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, 256 * 16);
-    ln.begin(name);
-    fill_zero_kernel<T><<<blocks, NT, 0, ln.stream>>>(p, n);
-    ln.end();
 }
 
 template <typename T, int W>
@@ -769,6 +612,42 @@ bool uses_register_fused_mttkrp(const sc_plan *p) { return p->kind == K_MTTKRP3 
 
 }  // namespace
 
+// Leaves -> rows of the first temporary in the workspace (first kernel of every FISSIONED
+// schedule of order >= 3): T(f, :) = sum over the leaves z of fiber f of vals[z] * F(crd[z], :).
+template <typename T, int W>
+static sc_status leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
+                               const sc_dense_view &F, void *Tout, const char *name)
+{
+    const int ntiles = (int)p->tiles.size();
+    Order3Args a = {};
+    a.tiles = p->d_tiles;
+    a.pos3 = pos_leaf; a.crd3 = crd_leaf;
+    a.vals = vals;
+    a.D = F.data; a.ldD = F.ld;
+    a.T = Tout;
+    a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
+    ln.begin("zero_shared_rows");
+    zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
+    ln.end();
+    ln.begin(name);
+    order3_kernel<T, W, 1, 0><<<ntiles, NT, order3_lds_bytes<T>(W, a.tn, a.ta), ln.stream>>>(a);
+    ln.end();
+    return ln.status;
+}
+
+sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
+                               const sc_dense_view &F, void *Tout, int W, const char *name)
+{
+    const bool f64 = p->dtype == SC_F64;
+    switch (W) {
+    case 8: return f64 ? leaf_producer<double, 8>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)
+                       : leaf_producer<float, 8>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
+    case 16: return f64 ? leaf_producer<double, 16>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)
+                        : leaf_producer<float, 16>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
+    default: return SC_ERR_SCHED_UNSUPPORTED;
+    }
+}
+
 TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols)
 {
     TileCaps c{0, 0, 0};
@@ -790,7 +669,8 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
         }
         break;
     }
-    default: break;
+    case K_SDDMM_SPMM: return order2_caps(dtype, fcols);
+    case K_TTMC4: return order4_caps(dtype, fcols);
     }
     return c;
 }
@@ -808,6 +688,8 @@ size_t lds_bytes_needed(const sc_plan *p)
         }
         return p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
+    case K_SDDMM_SPMM: return order2_lds_bytes_needed(p);
+    case K_TTMC4: return order4_lds_bytes_needed(p);
     default: return 0;
     }
 }
@@ -820,8 +702,10 @@ sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vi
     case K_MTTKRP3:
         return p->dtype == SC_F64 ? dispatch_order3<double>(p, sp, fac, out, ws, stream)
                                   : dispatch_order3<float>(p, sp, fac, out, ws, stream);
-    default:
-        return SC_ERR_SCHED_UNSUPPORTED;
+    case K_SDDMM_SPMM: return launch_order2(p, sp, fac, out, ws, stream);
+    case K_TTMC4: return launch_order4(p, sp, fac, out, ws, stream);
+    default: return SC_ERR_SCHED_UNSUPPORTED;
+
     }
 }
 

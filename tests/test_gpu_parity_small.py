@@ -9,7 +9,7 @@ from helpers import assert_parity, run_library
 
 pytestmark = pytest.mark.gpu
 
-SMALL = [(1, 1.0), (2, 0.004), (3, 0.003)]
+SMALL = [(1, 1.0), (2, 0.004), (3, 0.003), (4, 0.003), (5, 0.004)]
 
 
 @pytest.mark.parametrize("which", ["fused", "fissioned"])

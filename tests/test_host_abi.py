@@ -1,0 +1,260 @@
+"""Host side of the C ABI, without a GPU: the library loads and exports every declared
+symbol, COO -> CSF conversion, validation / error codes, derived temporaries, tile tables."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2311_09549_amd import binding as sc
+from paper_2311_09549_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _status(fn, *args, **kw):
+    try:
+        fn(*args, **kw)
+    except sc.ScError as e:
+        return sc.STATUS_NAMES[e.status]
+    return "SC_OK"
+
+
+def _small(cid=3, scale=0.002):
+    cfg = synth.config(cid, scale)
+    data = synth.generate(cfg)
+    csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
+    return cfg, data, csf
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "sparsecontract.h")).read()
+    declared = sorted(set(re.findall(r"\b(sc_[a-z_0-9]+)\s*\(", hdr)) - {"sc_status"})  # the type name occurs in a comment
+    assert set(declared) == set(sc.EXPORTS)
+    lib = ctypes.CDLL(sc.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sc.version() == (0, 1)
+    assert sc.status_string(0) == "ok" and "unknown" in sc.status_string(99)
+
+
+def test_coo_to_csf_matches_numpy_prefix_structure():
+    for cid, scale in [(1, 1.0), (2, 0.002), (4, 0.002), (5, 0.01)]:
+        cfg = synth.config(cid, scale)
+        data = synth.generate(cfg)
+        coords, dims = data["coords"], cfg["dims"]
+        csf = sc.coo_to_csf(list(coords), data["vals"], dims)
+        order = len(dims)
+        key = np.zeros(coords.shape[1], dtype=np.int64)
+        for m in range(order):
+            key = key * dims[m] + coords[m]
+            uniq, first = np.unique(key, return_index=True)
+            assert csf.nfib[m] == uniq.size
+            np.testing.assert_array_equal(csf.crd[m], coords[m][first])   # coordinate of each node
+            if m:
+                # children of node p of level m-1 are the level-m nodes sharing its prefix
+                parent_key = uniq // dims[m]
+                starts = np.searchsorted(parent_key, prev_uniq)
+                np.testing.assert_array_equal(csf.pos[m][:-1], starts)
+                assert csf.pos[m][-1] == uniq.size
+            prev_uniq = uniq
+        assert csf.nnz == coords.shape[1] and csf.vals is not None
+
+
+def test_coo_validation_errors():
+    dims = (4, 5, 6)
+    good = [np.array([0, 0, 1], np.int32), np.array([1, 2, 0], np.int32), np.array([3, 3, 5], np.int32)]
+    vals = np.ones(3, np.float32)
+    assert sc.coo_to_csf_sizes(good, vals, dims) == [2, 3, 3]
+    unsorted = [good[0][::-1].copy(), good[1][::-1].copy(), good[2][::-1].copy()]
+    assert _status(sc.coo_to_csf_sizes, unsorted, vals, dims) == "SC_ERR_UNSORTED"
+    dup = [np.array([0, 0], np.int32), np.array([1, 1], np.int32), np.array([3, 3], np.int32)]
+    assert _status(sc.coo_to_csf_sizes, dup, vals[:2], dims) == "SC_ERR_DUPLICATE"
+    rng = [np.array([0], np.int32), np.array([5], np.int32), np.array([0], np.int32)]
+    assert _status(sc.coo_to_csf_sizes, rng, vals[:1], dims) == "SC_ERR_CRD_RANGE"
+    assert _status(sc.coo_to_csf_sizes, good, vals, (4, 5, 0)) == "SC_ERR_BAD_DIMS"
+    assert _status(sc.coo_to_csf_sizes, good[:1], vals, (4,)) == "SC_ERR_BAD_ORDER"
+    v = sc.coo_view(good, vals, dims)
+    v.dtype = 7
+    nf = (ctypes.c_int64 * 4)()
+    assert sc.lib().sc_coo_to_csf_sizes(ctypes.byref(v), nf) == sc.STATUS_NAMES.index("SC_ERR_BAD_DTYPE")
+    assert sc.lib().sc_coo_to_csf_sizes(None, nf) == sc.STATUS_NAMES.index("SC_ERR_NULL")
+
+
+def test_empty_tensor_converts_and_plans():
+    dims = (4, 5, 6)
+    empty = [np.zeros(0, np.int32)] * 3
+    csf = sc.coo_to_csf(empty, np.zeros(0, np.float32), dims)
+    assert csf.nfib == (0, 0, 0) and [int(p[0]) for p in csf.pos[1:]] == [0, 0]
+    plan = sc.plan_create("A(i,l,m)=B(i,j,k)*C(j,l)*D(k,m)", csf,
+                          [sc.dense_view(None, "f32", 5, 8), sc.dense_view(None, "f32", 6, 8)], sc.schedule("fused"))
+    assert sc.plan_tile_count(plan) == 0
+
+
+@pytest.mark.parametrize("cid,scale,temps", [
+    (1, 1.0, ["T(i,j,m)"]), (2, 0.002, ["T(i,j,r)"]), (4, 0.002, ["T(i,j)"]), (5, 0.01, ["T1(i,j,k,n)", "T2(i,j,m,n)"])])
+def test_derived_temporaries_and_workspace(cid, scale, temps):
+    """The temporaries' index sets follow from the split positions (Section 4.2): indices of
+    the producer that also occur in the consumer or the output."""
+    cfg, data, csf = _small(cid, scale)
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned", temps, [0] * len(temps)))
+    text = sc.plan_describe(plan)
+    for t in temps:
+        assert t in text
+    esz = 8 if cfg["dtype"] == "f64" else 4
+    order = len(cfg["dims"])
+    ranks = cfg["ranks"]
+    if cfg["kind"] == "ttmc4":
+        shapes = [(csf.nfib[2], ranks[2]), (csf.nfib[1], ranks[1] * ranks[2])]
+    elif cfg["kind"] == "sddmm_spmm":
+        shapes = [(csf.nnz, 1)]
+    else:
+        shapes = [(csf.nfib[order - 2], ranks[-1])]
+    need = 0
+    for t, (rows, cols) in enumerate(shapes):
+        off, r, c = sc.plan_intermediate(plan, t)
+        assert (r, c) == (rows, cols) and off == need and off % 256 == 0
+        need += (rows * cols * esz + 255) // 256 * 256
+    assert sc.plan_workspace_bytes(plan) == need
+    # same index set in another order is accepted; a wrong set, a wrong count or a fuse depth are not
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
+                   sc.schedule("fissioned", [temps[0].replace("(i,j", "(j,i")] + temps[1:], [0] * len(temps))) == "SC_OK"
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
+                   sc.schedule("fissioned", ["T(i,q)"] + temps[1:], [0] * len(temps))) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
+                   sc.schedule("fissioned", temps + ["X(i)"], [0] * (len(temps) + 1))) in ("SC_ERR_SCHED_UNSUPPORTED",)
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
+                   sc.schedule("fissioned", temps, [1] * len(temps))) == "SC_ERR_SCHED_UNSUPPORTED"
+    fused = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused", temps, [1] * len(temps)))
+    assert sc.plan_workspace_bytes(fused) == 0
+    assert _status(sc.plan_intermediate, fused, 0) == "SC_ERR_SCHED_UNSUPPORTED"
+
+
+def test_expression_family():
+    cfg, data, csf = _small(3, 0.002)
+    f = data["factors"]
+    ok = sc.schedule("fused")
+    # free index names, factors in either order, "+=" accepted
+    assert _status(sc.plan_create, "Out(a,x,y) += Bt(a,b,c) * Dm(c,y) * Cm(b,x)", csf, [f[1], f[0]], ok) == "SC_OK"
+    assert _status(sc.plan_create, "A(i,l,m)=B(i,j,k)*C(j,l)*D(k,m", csf, f, ok) == "SC_ERR_EXPR_PARSE"
+    assert _status(sc.plan_create, "A(i,l,m)=B(i,j,k)*C(j,l)+D(k,m)", csf, f, ok) == "SC_ERR_EXPR_PARSE"
+    assert _status(sc.plan_create, "A(l,m,i)=B(i,j,k)*C(j,l)*D(k,m)", csf, f, ok) == "SC_ERR_EXPR_UNSUPPORTED"
+    assert _status(sc.plan_create, "A(l,m,n)=B(i,j,k)*C(i,l)*D(j,m)", csf, f, ok) == "SC_ERR_EXPR_UNSUPPORTED"
+    assert _status(sc.plan_create, "A(i,m,l)=B(i,j,k)*C(j,l)*D(k,m)", csf, f, ok) == "SC_ERR_EXPR_UNSUPPORTED"
+    assert _status(sc.plan_create, "A(i,l)=B(i,j)*C(j,l)", csf, f[:1], ok) == "SC_ERR_EXPR_UNSUPPORTED"
+    assert _status(sc.plan_create, "A(i,l,m,n)=B(i,j,k,p)*C(j,l)*D(k,m)*E(p,n)", csf, f + [f[0]], ok) == "SC_ERR_BAD_ORDER"
+    assert _status(sc.plan_create, cfg["expr"], csf, f[:1], ok) == "SC_ERR_SHAPE_MISMATCH"
+    assert _status(sc.plan_create, cfg["expr"], csf, [f[1], f[0]], ok) == "SC_ERR_SHAPE_MISMATCH"   # rows != dims
+    assert _status(sc.plan_create, cfg["expr"], csf, [f[0].astype(np.float64), f[1]], ok) == "SC_ERR_BAD_DTYPE"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("linear")) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("fused", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    odd = np.ones((cfg["dims"][2], 12), np.float32)   # a rank no kernel is instantiated for
+    assert _status(sc.plan_create, cfg["expr"], csf, [f[0], odd], ok) == "SC_ERR_SCHED_UNSUPPORTED"
+
+
+def test_structure_validation_errors():
+    cfg, data, csf = _small(3, 0.002)
+    f, ok = data["factors"], sc.schedule("fused")
+
+    def broken(mutate):
+        c = sc.Csf(csf.order, csf.dims, csf.nnz, csf.dtype_code, csf.nfib, [None] + [p.copy() for p in csf.pos[1:]],
+                   [x.copy() for x in csf.crd], csf.vals, False)
+        mutate(c)
+        return _status(sc.plan_create, cfg["expr"], c, f, ok)
+
+    def swap_pos(c): c.pos[2][3], c.pos[2][4] = c.pos[2][4], c.pos[2][3]
+    def empty_node(c): c.pos[1][2] = c.pos[1][1]
+    def bad_end(c): c.pos[2][-1] += 1
+    def crd_range(c): c.crd[2][5] = cfg["dims"][2]
+    def crd_neg(c): c.crd[1][0] = -1
+    def unsorted_leaf(c):
+        lo, hi = c.pos[2][np.argmax(np.diff(c.pos[2]) >= 2)], 0
+        c.crd[2][lo], c.crd[2][lo + 1] = c.crd[2][lo + 1], c.crd[2][lo]
+    def dup_leaf(c):
+        lo = c.pos[2][np.argmax(np.diff(c.pos[2]) >= 2)]
+        c.crd[2][lo + 1] = c.crd[2][lo]
+    def dup_slice(c): c.crd[0][1] = c.crd[0][0]
+    def nfib_mismatch(c): c.nfib = (c.nfib[0], c.nfib[1], c.nfib[2] - 1)
+    def too_many_slices(c): c.dims = (c.nfib[0] - 1,) + tuple(c.dims[1:])
+
+    assert broken(swap_pos) == "SC_ERR_BAD_POS"
+    assert broken(empty_node) == "SC_ERR_BAD_POS"
+    assert broken(bad_end) == "SC_ERR_BAD_POS"
+    assert broken(crd_range) == "SC_ERR_CRD_RANGE"
+    assert broken(crd_neg) == "SC_ERR_CRD_RANGE"
+    assert broken(unsorted_leaf) == "SC_ERR_UNSORTED"
+    assert broken(dup_leaf) == "SC_ERR_DUPLICATE"
+    assert broken(dup_slice) == "SC_ERR_DUPLICATE"
+    assert broken(nfib_mismatch) == "SC_ERR_BAD_DIMS"
+    assert broken(too_many_slices) in ("SC_ERR_BAD_DIMS", "SC_ERR_CRD_RANGE")
+    assert sc.lib().sc_plan_create(None, b"x", None, None, 0, None) == sc.STATUS_NAMES.index("SC_ERR_NULL")
+
+
+@pytest.mark.parametrize("cid,scale,which", [(2, 0.004, "fused"), (2, 0.004, "fissioned"), (3, 0.003, "fused"),
+                                             (4, 0.003, "fused"), (5, 0.004, "fused"), (1, 1.0, "fissioned")])
+def test_tiles_partition_the_nonzeros(cid, scale, which):
+    """Tiles are contiguous, cover every nonzero once, respect their caps, and their node
+    ranges and continuation flags agree with the CSF pos arrays."""
+    cfg, data, csf = _small(cid, scale)
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule(which))
+    nt = sc.plan_tile_count(plan)
+    recs = np.array([sc.plan_tile(plan, i) for i in range(nt)])
+    text = sc.plan_describe(plan)
+    caps = [int(x) for x in re.search(r"tiles: \d+ \(<= (\d+) leaves, <= (\d+) level-a", text).groups()]
+    order = csf.order
+    assert recs[0, 0] == 0 and recs[-1, 1] == csf.nnz
+    np.testing.assert_array_equal(recs[1:, 0], recs[:-1, 1])
+    sizes = recs[:, 1] - recs[:, 0]
+    assert sizes.min() >= 1 and sizes.max() <= caps[0]
+    assert recs[:, 3].max() <= caps[1]
+    levels = [(order - 1, 2, 3)] + ([(order - 2, 4, 5)] if order >= 3 else []) + ([(order - 3, 6, 7)] if order >= 4 else [])
+    # leaf index -> node index at each level above
+    idx_lo, idx_hi = recs[:, 0].copy(), recs[:, 1] - 1
+    lo_leaf, hi_leaf = recs[:, 0], recs[:, 1]
+    for depth, (lvl, c0, cn) in enumerate(levels):
+        pos = csf.pos[lvl]
+        first = np.searchsorted(pos, idx_lo, side="right") - 1
+        last = np.searchsorted(pos, idx_hi, side="right") - 1
+        np.testing.assert_array_equal(recs[:, c0], first)
+        np.testing.assert_array_equal(recs[:, cn], last - first + 1)
+        # leaf range covered by the first / last node, to check the continuation flags
+        start_leaf, end_leaf = pos[first], pos[last + 1]
+        for deeper in range(lvl + 1, order):
+            start_leaf, end_leaf = csf.pos[deeper][start_leaf], csf.pos[deeper][end_leaf]
+        np.testing.assert_array_equal((recs[:, 8] >> (2 * depth)) & 1, (start_leaf < lo_leaf).astype(int))
+        np.testing.assert_array_equal((recs[:, 8] >> (2 * depth + 1)) & 1, (end_leaf > hi_leaf).astype(int))
+        idx_lo, idx_hi = first, last
+
+
+def test_tuning_knobs_and_lds_limit():
+    cfg, data, csf = _small(3, 0.003)
+    try:
+        sc.tuning_set("tile_leaves", 256)
+        plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+        recs = np.array([sc.plan_tile(plan, i) for i in range(sc.plan_tile_count(plan))])
+        assert (recs[:, 1] - recs[:, 0]).max() <= 256
+        sc.tuning_set("tile_nodes_a", 1 << 14)   # T rows would not fit in LDS
+        assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused")) == "SC_ERR_SCHED_UNSUPPORTED"
+        assert _status(sc.tuning_set, "no_such_knob", 1) == "SC_ERR_EXPR_PARSE"
+    finally:
+        for k in ("tile_leaves", "tile_nodes_a", "tile_nodes_b"):
+            sc.tuning_set(k, 0)
+
+
+def test_execute_without_gpu_or_with_host_views_is_refused():
+    cfg, data, csf = _small(3, 0.002)
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+    out = np.zeros(synth.output_shape(cfg), np.float32)
+    # host views are never executable: the library has no CPU path
+    assert _status(sc.execute, plan, csf, data["factors"], out) == "SC_ERR_DEVICE"
+
+
+def test_model_counts():
+    cfg, data, csf = _small(3, 0.002)
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+    flops, byts = sc.plan_model(plan)
+    L, M = cfg["ranks"]
+    assert flops == 2 * M * csf.nnz + 2 * L * M * csf.nfib[1]
+    fis = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned"))
+    assert sc.plan_model(fis)[1] == byts + 2 * csf.nfib[1] * M * 4
