@@ -51,7 +51,7 @@ def _sample_rows(data, dims0, n_heavy, n_random, seed):
 
 
 @pytest.mark.parametrize("which", ["fused", "fissioned"])
-@pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000)])
+@pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000), (4, None, None), (5, 10, 500)])
 def test_parity_full(oracle, cid, n_heavy, n_random, which):
     cfg, data = _get(cid)
     print(f"config {cid} full size {which} nnz={cfg['nnz']}", flush=True)
