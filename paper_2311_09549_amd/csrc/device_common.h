@@ -98,7 +98,7 @@ __device__ __forceinline__ void seg_walk(int gs, int ge, const int *bnd, int np,
         Item it[U];
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (c + u < ge) it[u] = load(c + u);
+            it[u] = load(min(c + u, ge - 1));   // unconditional: keeps all U gathers of a batch in flight
 #pragma unroll
         for (int u = 0; u < U; ++u)
             if (c + u < ge) {

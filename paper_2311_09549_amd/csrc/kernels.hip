@@ -280,29 +280,39 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
                         if (lane == 0) slot_id[slot] = s;
                     }
                 };
-                for (int fb = ws; fb < we; fb += 4) {
-                    const int bend = min(fb + 4, we);
-                    const int lf = fb + kk;
-                    float cv = 0.f, tv = 0.f;
-                    if (lf < bend) {
-                        cv = reinterpret_cast<const float *>(C)[(int64_t)crda_s[lf] * a.ldC + col];
-                        tv = reinterpret_cast<const float *>(T_s)[lf * 16 + col];
+                constexpr int UB = 4;  // 4-fiber blocks whose operand gathers are issued together
+                for (int fb0 = ws; fb0 < we; fb0 += 4 * UB) {
+                    float cvs[UB], tvs[UB];
+#pragma unroll
+                    for (int ub = 0; ub < UB; ++ub) {
+                        // lanes past the chunk end read a valid fiber; they are masked below
+                        const int lfc = min(fb0 + 4 * ub + kk, we - 1);
+                        cvs[ub] = reinterpret_cast<const float *>(C)[(int64_t)crda_s[lfc] * a.ldC + col];
+                        tvs[ub] = reinterpret_cast<const float *>(T_s)[lfc * 16 + col];
                     }
-                    int from = fb;  // fibers of this block in [from, bend) are not yet consumed
-                    for (;;) {
-                        const int upto = min(send, bend);
-                        const bool mine = lf >= from && lf < upto;
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv : 0.f, acc, 0, 0, 0);
-                        if (send <= bend) {
-                            emit(ls, whole);
-                            acc = floatx4{0.f, 0.f, 0.f, 0.f};
-                            whole = true;
-                            from = send;
-                            ++ls;
-                            send = bb_s[ls + 1];
-                            if (from >= bend) break;
-                        } else {
-                            break;
+#pragma unroll
+                    for (int ub = 0; ub < UB; ++ub) {
+                        const int fb = fb0 + 4 * ub;
+                        if (fb >= we) break;
+                        const int bend = min(fb + 4, we);
+                        const int lf = fb + kk;
+                        const float cv = cvs[ub], tv = tvs[ub];
+                        int from = fb;  // fibers of this block in [from, bend) are not yet consumed
+                        for (;;) {
+                            const int upto = min(send, bend);
+                            const bool mine = lf >= from && lf < upto;
+                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv : 0.f, acc, 0, 0, 0);
+                            if (send <= bend) {
+                                emit(ls, whole);
+                                acc = floatx4{0.f, 0.f, 0.f, 0.f};
+                                whole = true;
+                                from = send;
+                                ++ls;
+                                send = bb_s[ls + 1];
+                                if (from >= bend) break;
+                            } else {
+                                break;
+                            }
                         }
                     }
                 }

@@ -266,35 +266,45 @@ __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
                         if (lane == 0) slot_id[slot] = s;
                     }
                 };
-                for (int fb = ws; fb < we; fb += 4) {
-                    const int bend = min(fb + 4, we);
-                    const int lf = fb + kk;
-                    float cv = 0.f, tv[NB];
+                constexpr int UB = 4;  // 4-fiber blocks whose C gathers are issued together
+                const int colc = min(col, L - 1);
+                for (int fb0 = ws; fb0 < we; fb0 += 4 * UB) {
+                    float cvs[UB];
 #pragma unroll
-                    for (int b = 0; b < NB; ++b) tv[b] = 0.f;
-                    if (lf < bend) {
-                        if (col < L) cv = reinterpret_cast<const float *>(C)[(int64_t)crdb_s[lf] * a.ldC + col];
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) tv[b] = reinterpret_cast<const float *>(T2_s)[lf * W2 + b * 16 + col];
+                    for (int ub = 0; ub < UB; ++ub) {
+                        const int lfc = min(fb0 + 4 * ub + kk, we - 1);   // masked below when past the end
+                        cvs[ub] = reinterpret_cast<const float *>(C)[(int64_t)crdb_s[lfc] * a.ldC + colc];
                     }
-                    int from = fb;
-                    for (;;) {
-                        const int upto = min(send, bend);
-                        const bool mine = lf >= from && lf < upto;
 #pragma unroll
-                        for (int b = 0; b < NB; ++b)
-                            acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv[b] : 0.f, acc[b], 0, 0, 0);
-                        if (send <= bend) {
-                            emit(ls, whole);
+                    for (int ub = 0; ub < UB; ++ub) {
+                        const int fb = fb0 + 4 * ub;
+                        if (fb >= we) break;
+                        const int bend = min(fb + 4, we);
+                        const int lf = fb + kk;
+                        const int lfc = min(lf, we - 1);
+                        const float cv = col < L ? cvs[ub] : 0.f;
+                        float tv[NB];
 #pragma unroll
-                            for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-                            whole = true;
-                            from = send;
-                            ++ls;
-                            send = bc_s[ls + 1];
-                            if (from >= bend) break;
-                        } else {
-                            break;
+                        for (int b = 0; b < NB; ++b) tv[b] = reinterpret_cast<const float *>(T2_s)[lfc * W2 + b * 16 + col];
+                        int from = fb;
+                        for (;;) {
+                            const int upto = min(send, bend);
+                            const bool mine = lf >= from && lf < upto;
+#pragma unroll
+                            for (int b = 0; b < NB; ++b)
+                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv[b] : 0.f, acc[b], 0, 0, 0);
+                            if (send <= bend) {
+                                emit(ls, whole);
+#pragma unroll
+                                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
+                                whole = true;
+                                from = send;
+                                ++ls;
+                                send = bc_s[ls + 1];
+                                if (from >= bend) break;
+                            } else {
+                                break;
+                            }
                         }
                     }
                 }
