@@ -408,6 +408,7 @@ extern "C" sc_status sc_tuning_set(const char *name, int64_t value)
     if (!strcmp(name, "tile_leaves")) t.tn = (int32_t)value;
     else if (!strcmp(name, "tile_nodes_a")) t.ta = (int32_t)value;
     else if (!strcmp(name, "tile_nodes_b")) t.tb = (int32_t)value;
+    else if (!strcmp(name, "tile_interleave")) t.interleave = (int32_t)value;
     else return SC_ERR_EXPR_PARSE;
     return SC_OK;
 }
@@ -716,7 +717,18 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     if (hipGetDeviceCount(&ndev) == hipSuccess && ndev > 0) {
         if (!p->tiles.empty()) {
             if (hipMalloc((void **)&p->d_tiles, sizeof(TileRec) * p->tiles.size()) != hipSuccess) return SC_ERR_DEVICE;
-            if (hipMemcpy(p->d_tiles, p->tiles.data(), sizeof(TileRec) * p->tiles.size(), hipMemcpyHostToDevice) != hipSuccess)
+            // Upload in an interleaved order: workgroups that run at the same time then work on
+            // tiles far apart in the tensor, so the atomic updates of one heavy output row are
+            // spread over the kernel's duration instead of queueing on one address.
+            const size_t nt = p->tiles.size();
+            const size_t stride = (size_t)std::max<int32_t>(1, tuning().interleave ? tuning().interleave : 64);
+            std::vector<TileRec> order;
+            try {
+                order.reserve(nt);
+            } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
+            for (size_t r = 0; r < stride; ++r)
+                for (size_t t = r; t < nt; t += stride) order.push_back(p->tiles[t]);
+            if (hipMemcpy(p->d_tiles, order.data(), sizeof(TileRec) * nt, hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
         p->has_device = true;

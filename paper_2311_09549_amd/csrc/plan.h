@@ -92,6 +92,7 @@ namespace sck {
 // Process-global tuning overrides (0 = use the built-in choice).
 struct Tuning {
     int32_t tn = 0, ta = 0, tb = 0;
+    int32_t interleave = 0;  // stride of the tile upload order (0 = built-in)
 };
 Tuning &tuning();
 
