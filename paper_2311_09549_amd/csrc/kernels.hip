@@ -585,12 +585,8 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         }
         ln.end();
     } else {
-        ln.begin("zero_shared_rows");
-        zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(a.T), W);
-        ln.end();
-        ln.begin("order3_traverse");
-        order3_kernel<T, W, 1, 0><<<ntiles, NT, lds, stream>>>(a);
-        ln.end();
+        const sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse");
+        if (st != SC_OK) return st;
         if (had) {
             ln.begin("mttkrp3_consume");
             order3_kernel<T, W, 2, 0><<<ntiles, NT, lds, stream>>>(a);
@@ -621,42 +617,6 @@ sc_status dispatch_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dens
 bool uses_register_fused_mttkrp(const sc_plan *p) { return p->kind == K_MTTKRP3 && p->sched == SC_SCHED_FUSED; }
 
 }  // namespace
-
-// Leaves -> rows of the first temporary in the workspace (first kernel of every FISSIONED
-// schedule of order >= 3): T(f, :) = sum over the leaves z of fiber f of vals[z] * F(crd[z], :).
-template <typename T, int W>
-static sc_status leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, const char *name)
-{
-    const int ntiles = (int)p->tiles.size();
-    Order3Args a = {};
-    a.tiles = p->d_tiles;
-    a.pos3 = pos_leaf; a.crd3 = crd_leaf;
-    a.vals = vals;
-    a.D = F.data; a.ldD = F.ld;
-    a.T = Tout;
-    a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
-    ln.begin("zero_shared_rows");
-    zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
-    ln.end();
-    ln.begin(name);
-    order3_kernel<T, W, 1, 0><<<ntiles, NT, order3_lds_bytes<T>(W, a.tn, a.ta), ln.stream>>>(a);
-    ln.end();
-    return ln.status;
-}
-
-sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name)
-{
-    const bool f64 = p->dtype == SC_F64;
-    switch (W) {
-    case 8: return f64 ? leaf_producer<double, 8>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)
-                       : leaf_producer<float, 8>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
-    case 16: return f64 ? leaf_producer<double, 16>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)
-                        : leaf_producer<float, 16>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
-    default: return SC_ERR_SCHED_UNSUPPORTED;
-    }
-}
 
 TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols)
 {
