@@ -632,9 +632,15 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             // fiber sums live in registers: only boundary tables limit the node counts
             c.ta = 512;
             c.tb = 128;
-        } else {
+        } else if (kind == K_MTTKRP3) {
             // keep the T rows of a tile within 32 KB of LDS
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(1024, (32 * 1024) / (w * e)));
+            c.tb = c.ta;
+        } else {
+            // smaller tiles (T rows within 16 KB) let more workgroups share a CU, which measured
+            // faster than larger tiles for the outer-product consumer
+            c.tn = 512;
+            c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
         }
         break;

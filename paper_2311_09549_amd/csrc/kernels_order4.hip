@@ -388,7 +388,7 @@ TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols)
     if (dtype == SC_F64) {
         c.tn = 512; c.ta = 256; c.tb = 40;
     } else {
-        c.tn = 768; c.ta = 512; c.tb = 96;
+        c.tn = 640; c.ta = 384; c.tb = 72;
     }
     return c;
 }
