@@ -456,8 +456,10 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
     __syncthreads();
 
     const int g = tid / LG, li = tid % LG;
-    const char *Cb = static_cast<const char *>(a.C) + li * 16;
-    const char *Db = static_cast<const char *>(a.D) + li * 16;
+    // uniform base + 32-bit per-lane byte offset: one address add per gather
+    const char *Cb = static_cast<const char *>(a.C);
+    const char *Db = static_cast<const char *>(a.D);
+    const uint32_t lo = (uint32_t)li * 16u;
     T *A = static_cast<T *>(a.A);
     auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
     auto direct = [&](int ls, const P &row) {
@@ -500,10 +502,10 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
             for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                d[u] = *reinterpret_cast<const P *>(Db + r[u].koff);
+                d[u] = *reinterpret_cast<const P *>(Db + (r[u].koff + lo));
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) cc[u].v[i] = T(0);
-                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + (uint32_t)r[u].e);
+                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + ((uint32_t)r[u].e + lo));
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -523,7 +525,7 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
         }
         const int co = chunk_coff[g];
         if (co >= 0) {  // the chunk ends inside a fiber: push its piece through the consumer
-            const P cl = *reinterpret_cast<const P *>(Cb + (uint32_t)co);
+            const P cl = *reinterpret_cast<const P *>(Cb + ((uint32_t)co + lo));
 #pragma unroll
             for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cl.v[i];
         }
