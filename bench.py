@@ -43,6 +43,8 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also queue the library's plain copy kernel (256 MiB) a few times, for counter runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding by top-level slice is "
@@ -54,6 +56,7 @@ def main() -> int:
 
     from paper_2311_09549_amd import binding as sc
     from paper_2311_09549_amd import synth
+    from paper_2311_09549_amd import traffic as traffic_store
     from paper_2311_09549_amd.driver import Contraction
 
     if not torch.cuda.is_available():
@@ -110,6 +113,17 @@ def main() -> int:
     out_bytes = float(np.prod(out_shape)) * elem
     dom_bytes = bytes_fused  # the fused kernel reads every input once and writes the output once
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    # HBM bytes per launch from stored FETCH_SIZE / WRITE_SIZE counter runs (calibrated against
+    # a copy of known size); None when absent or taken from other kernel sources
+    measured = traffic_store.lookup(f"{args.config}:{dom_name}") if args.scale == 1.0 else None
+
+    if args.calibrate_copy:
+        src = torch.empty(traffic_store.COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "effective GFLOP/s of the fused schedule (schedule flops / step time), 1 MI355X",
@@ -127,7 +141,7 @@ def main() -> int:
         "config": {"workload": WORKLOAD_TEXT[args.config] + (f" (scaled by {args.scale})" if args.scale != 1.0 else ""),
                    "schedule": "fused", "nnz": int(cfg["nnz"]), "tiles": sc.plan_tile_count(fused.plan)},
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured["hbm_bytes"] if measured else None,
                      "algorithmic_bytes": dom_bytes, "kernel_ms": dom_ms},
         "kernels_ms": kt,
         "schedule_flops": flops,

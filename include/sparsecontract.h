@@ -209,6 +209,14 @@ sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9]);
  * SC_ERR_EXPR_PARSE; sc_plan_create rejects caps whose on-chip buffers do not fit. */
 sc_status sc_tuning_set(const char *name, int64_t value);
 
+/* Measurement aid, not part of the contraction path: queues a plain streaming copy of
+ * `bytes` bytes (a multiple of 16) from `src` to `dst` (both device, 16-byte aligned, not
+ * overlapping) on `hip_stream`.  Hardware counters of memory traffic are calibrated against
+ * this kernel, whose traffic is known: `bytes` read and `bytes` written.  Returns
+ * SC_ERR_NULL for NULL pointers, SC_ERR_BAD_DIMS for a size or pointer that is not a multiple of 16,
+ * SC_ERR_DEVICE when the launch fails. */
+sc_status sc_stream_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
 /* Frees the plan and its device tables.  NULL is accepted. */
 sc_status sc_plan_destroy(sc_plan *plan);
 

@@ -33,7 +33,7 @@ EXPORTS = [
     "sc_version", "sc_status_string", "sc_coo_to_csf_sizes", "sc_coo_to_csf", "sc_plan_create",
     "sc_plan_workspace_bytes", "sc_plan_describe", "sc_plan_model", "sc_plan_intermediate", "sc_execute",
     "sc_plan_set_profiling", "sc_plan_kernel_count", "sc_plan_kernel_time", "sc_plan_tile_count", "sc_plan_tile",
-    "sc_tuning_set", "sc_plan_destroy",
+    "sc_tuning_set", "sc_stream_copy", "sc_plan_destroy",
 ]
 
 _c_i32p = ctypes.POINTER(ctypes.c_int32)
@@ -296,6 +296,12 @@ def plan_tile(plan: Plan, index: int):
 
 def tuning_set(name: str, value: int):
     _check(lib().sc_tuning_set(name.encode(), ctypes.c_int64(value)), "sc_tuning_set")
+
+
+def stream_copy(dst, src, nbytes: int, stream=0):
+    """Queues the library's plain copy kernel (counter calibration) on `stream`."""
+    _check(lib().sc_stream_copy(ctypes.c_void_p(_addr(dst)), ctypes.c_void_p(_addr(src)), ctypes.c_size_t(int(nbytes)),
+                                ctypes.c_void_p(int(stream))), "sc_stream_copy")
 
 
 def execute(plan: Plan, csf: Csf, factors, out, workspace=None, workspace_bytes=0, stream=0):

@@ -688,3 +688,24 @@ sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vi
 }
 
 }  // namespace sck
+
+// ------------------------------------------------------------------------------------------
+// plain streaming copy (calibration of memory-traffic counters)
+// ------------------------------------------------------------------------------------------
+namespace sck {
+__global__ void __launch_bounds__(NT) stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < n; i += (int64_t)gridDim.x * NT) dst[i] = src[i];
+}
+}  // namespace sck
+
+extern "C" sc_status sc_stream_copy(void *dst, const void *src, size_t bytes, void *hip_stream)
+{
+    if (!dst || !src) return SC_ERR_NULL;
+    if (bytes % 16 != 0 || (reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) % 16 != 0) return SC_ERR_BAD_DIMS;
+    if (bytes == 0) return SC_OK;
+    const int64_t n = (int64_t)(bytes / 16);
+    const int blocks = (int)std::min<int64_t>((n + sck::NT - 1) / sck::NT, 256 * 32);
+    sck::stream_copy_kernel<<<blocks, sck::NT, 0, (hipStream_t)hip_stream>>>(static_cast<uint4 *>(dst), static_cast<const uint4 *>(src), n);
+    return hipGetLastError() == hipSuccess ? SC_OK : SC_ERR_DEVICE;
+}

@@ -3,6 +3,7 @@ workloads (sizes the oracle finishes in seconds, several tiles, ragged tails).""
 import numpy as np
 import pytest
 
+from paper_2311_09549_amd import binding as sc
 from paper_2311_09549_amd import synth
 
 from helpers import assert_parity, run_library
@@ -21,3 +22,15 @@ def test_parity_small(oracle, cid, scale, which):
     con, got = run_library(cfg, data, which)
     worst = assert_parity(oracle, cfg, data, got)
     print(f"  max scaled error {worst:.3e}", flush=True)
+
+
+@pytest.mark.gpu
+def test_stream_copy_copies():
+    """The calibration copy kernel moves exactly the bytes it is given (ragged grid tail included)."""
+    import torch
+    n = 16 * (256 * 8192 + 37)
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda:0")
+    dst = torch.zeros_like(src)
+    sc.stream_copy(dst, src, n, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)

@@ -258,3 +258,14 @@ def test_model_counts():
     assert flops == 2 * M * csf.nnz + 2 * L * M * csf.nfib[1]
     fis = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned"))
     assert sc.plan_model(fis)[1] == byts + 2 * csf.nfib[1] * M * 4
+
+
+def test_stream_copy_argument_checks():
+    """The calibration copy validates its arguments on the host before any launch."""
+    lib = sc.lib()
+    buf = np.zeros(64, dtype=np.uint8)
+    p = buf.ctypes.data & ~15
+    assert lib.sc_stream_copy(None, ctypes.c_void_p(p), ctypes.c_size_t(16), None) == sc.STATUS_NAMES.index("SC_ERR_NULL")
+    assert lib.sc_stream_copy(ctypes.c_void_p(p + 16), ctypes.c_void_p(p), ctypes.c_size_t(12), None) == sc.STATUS_NAMES.index("SC_ERR_BAD_DIMS")
+    assert lib.sc_stream_copy(ctypes.c_void_p(p + 17), ctypes.c_void_p(p), ctypes.c_size_t(16), None) == sc.STATUS_NAMES.index("SC_ERR_BAD_DIMS")
+    assert lib.sc_stream_copy(ctypes.c_void_p(p + 16), ctypes.c_void_p(p), ctypes.c_size_t(0), None) == 0
