@@ -205,7 +205,9 @@ sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9]);
 /* Process-global tuning knobs; they affect plans created afterwards.  Names:
  * "tile_leaves", "tile_nodes_a", "tile_nodes_b" (upper bounds on the leaves / level-a /
  * level-b nodes of one work tile; 0 restores the built-in choice), "tile_interleave"
- * (stride of the order in which tiles are handed to workgroups; 1 = tensor order).  Unknown names give
+ * (stride of the order in which tiles are handed to workgroups; 1 = tensor order),
+ * "persistent_per_cu" (workgroups per compute unit launched by the kernels that loop over
+ * tiles; 0 = as many as fit; read at execute time).  Unknown names give
  * SC_ERR_EXPR_PARSE; sc_plan_create rejects caps whose on-chip buffers do not fit. */
 sc_status sc_tuning_set(const char *name, int64_t value);
 

@@ -166,9 +166,9 @@ inline void launch_fill(Launcher &ln, T *p, int64_t n, const char *name)
     ln.end();
 }
 
-// Leaf traversal of the FISSIONED schedules of order >= 3 (defined with the order-2 kernels, whose
-// SpMM half is the same single-level segmented reduction).
-size_t leaf_traverse_lds_bytes(const sc_plan *p);
+// Leaf traversal of the FISSIONED schedules of order >= 3 (its own kernel file); W = row width of
+// the temporary it writes.
+size_t leaf_traverse_lds_bytes(const sc_plan *p, int W);
 sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
                                const sc_dense_view &F, void *Tout, int W, const char *name);
 

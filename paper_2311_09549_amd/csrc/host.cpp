@@ -409,6 +409,7 @@ extern "C" sc_status sc_tuning_set(const char *name, int64_t value)
     else if (!strcmp(name, "tile_nodes_a")) t.ta = (int32_t)value;
     else if (!strcmp(name, "tile_nodes_b")) t.tb = (int32_t)value;
     else if (!strcmp(name, "tile_interleave")) t.interleave = (int32_t)value;
+    else if (!strcmp(name, "persistent_per_cu")) t.per_cu = (int32_t)value;
     else return SC_ERR_EXPR_PARSE;
     return SC_OK;
 }

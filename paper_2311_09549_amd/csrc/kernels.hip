@@ -664,8 +664,12 @@ size_t lds_bytes_needed(const sc_plan *p)
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
         }
-        return p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
-                                  : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
+        {
+            const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
+                                                  : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
+            if (p->sched != SC_SCHED_FISSIONED) return own;
+            return std::max(own, leaf_traverse_lds_bytes(p, (int)producer_width(p)));  // first FISSIONED kernel
+        }
     case K_SDDMM_SPMM: return order2_lds_bytes_needed(p);
     case K_TTMC4: return order4_lds_bytes_needed(p);
     default: return 0;

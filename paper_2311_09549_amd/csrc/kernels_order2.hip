@@ -7,10 +7,6 @@
 //                 across the lane group and accumulates t * Z(j,:) into the row sum.
 // MODE 1 (FISSIONED, first kernel, SDDMM):  t(z) written to the workspace, one per entry.
 // MODE 2 (FISSIONED, second kernel, SpMM):  A(i,:) += t(z) * Z(j,:) with t read back.
-// MODE 3 (leaf traversal of any FISSIONED schedule of order >= 3): the same single-level
-//                 segmented reduction with the leaf level in place of the rows,
-//                 T(f,:) = sum_{z in fiber f} vals[z] * F(crd[z],:), written to row f of the
-//                 temporary (a0 + local fiber number) instead of a row named by crd1.
 //
 // Work is cut into equal-nnz tiles (rows are level "a" of the tile record); a lane group of
 // LG = W / VEC lanes owns one stored entry per step (W = K = L).  Staging builds one LDS
@@ -75,12 +71,11 @@ __global__ void __launch_bounds__(NT) sddmm_spmm_kernel(Order2Args a)
     // ---- stage 1: row tables, marks cleared ----
     for (int i = tid; i <= na; i += NT) ba_s[i] = min(max(a.pos2[t.a0 + i], t.n0), t.n1) - t.n0;
     if (tid == 0) ba_s[na + 1] = INT_MAX;
-    if (MODE != 3)
-        for (int i = tid; i < na; i += NT) {
-            const int row = a.crd1[t.a0 + i];
-            crda_s[i] = row;
-            xrow_s[i] = (uint32_t)row * rowX;
-        }
+    for (int i = tid; i < na; i += NT) {
+        const int row = a.crd1[t.a0 + i];
+        crda_s[i] = row;
+        xrow_s[i] = (uint32_t)row * rowX;
+    }
     for (int c = tid; c < nchild + U; c += NT) end_s[pidx(c)] = -1;
     {
         P z;
@@ -109,7 +104,7 @@ __global__ void __launch_bounds__(NT) sddmm_spmm_kernel(Order2Args a)
                     }
                     const uint32_t j = (uint32_t)a.crd2[t.n0 + c];
                     Rec rec;
-                    rec.xoff = MODE == 3 ? 0u : xrow_s[lr];
+                    rec.xoff = xrow_s[lr];
                     rec.yoff = j * rowY;
                     rec.zoff = j * rowZ;
                     rec.v = vals[t.n0 + c];
@@ -140,7 +135,7 @@ __global__ void __launch_bounds__(NT) sddmm_spmm_kernel(Order2Args a)
     T *A = static_cast<T *>(a.A);
     auto row_shared = [&](int lr) { return (lr == 0 && (t.flags & 1)) || (lr == na - 1 && (t.flags & 2)); };
     auto direct = [&](int lr, const P &row) {
-        T *dst = A + (int64_t)(MODE == 3 ? t.a0 + lr : crda_s[lr]) * W + li * VEC;
+        T *dst = A + (int64_t)crda_s[lr] * W + li * VEC;
         if (!row_shared(lr)) {
             *reinterpret_cast<P *>(dst) = row;
         } else {
@@ -271,55 +266,6 @@ sc_status dispatch_order2(const sc_plan *p, const sc_csf_view *sp, const sc_dens
 }
 
 }  // namespace
-
-namespace {
-template <typename T, int W>
-sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                        const sc_dense_view &F, void *Tout, const char *name)
-{
-    const int ntiles = (int)p->tiles.size();
-    if ((uint64_t)F.rows * (uint64_t)F.ld * sizeof(T) >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
-    if (p->caps.tn > 4 * NT) return SC_ERR_SCHED_UNSUPPORTED;
-    Order2Args a = {};
-    a.tiles = p->d_tiles;
-    a.pos2 = pos_leaf; a.crd2 = crd_leaf;
-    a.vals = vals;
-    a.X = a.Y = a.Z = F.data;
-    a.ldX = a.ldY = a.ldZ = F.ld;
-    a.A = Tout;
-    a.tn = p->caps.tn; a.ta = p->caps.ta;
-    ln.begin("zero_shared_rows");
-    zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
-    ln.end();
-    ln.begin(name);
-    sddmm_spmm_kernel<T, W, 3><<<ntiles, NT, order2_lds_bytes<T>(a.tn, a.ta), ln.stream>>>(a);
-    ln.end();
-    return ln.status;
-}
-}  // namespace
-
-size_t leaf_traverse_lds_bytes(const sc_plan *p)
-{
-    return p->dtype == SC_F64 ? order2_lds_bytes<double>(p->caps.tn, p->caps.ta) : order2_lds_bytes<float>(p->caps.tn, p->caps.ta);
-}
-
-sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name)
-{
-    const bool f64 = p->dtype == SC_F64;
-#define SC_LEAF(WW)                                                                                   \
-    case WW:                                                                                          \
-        return f64 ? leaf_traverse<double, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)        \
-                   : leaf_traverse<float, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
-    switch (W) {
-        SC_LEAF(8)
-        SC_LEAF(16)
-        SC_LEAF(32)
-        SC_LEAF(64)
-    default: return SC_ERR_SCHED_UNSUPPORTED;
-    }
-#undef SC_LEAF
-}
 
 TileCaps order2_caps(sc_dtype dtype, const int64_t *fcols)
 {

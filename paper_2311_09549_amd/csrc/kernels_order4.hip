@@ -396,9 +396,10 @@ TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols)
 size_t order4_lds_bytes_needed(const sc_plan *p)
 {
     const int N = (int)p->fcols[2], W2 = (int)(p->fcols[1] * p->fcols[2]), L = (int)p->fcols[0];
-    // the order-3 producer kernel is reused for the first FISSIONED kernel and must fit too
-    return p->dtype == SC_F64 ? order4_lds_bytes<double>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb)
-                              : order4_lds_bytes<float>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb);
+    const size_t own = p->dtype == SC_F64 ? order4_lds_bytes<double>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb)
+                                          : order4_lds_bytes<float>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb);
+    if (p->sched != SC_SCHED_FISSIONED) return own;
+    return std::max(own, leaf_traverse_lds_bytes(p, N));  // the leaf traversal is the first FISSIONED kernel
 }
 
 sc_status launch_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)

@@ -1,0 +1,308 @@
+// Leaf traversal of the FISSIONED schedules of order >= 3: the producer half of a split nest
+// (Section 3.1, Algorithm 1 with nothing fused), materialising the temporary
+//     T(f,:) = sum_{z in fiber f} vals[z] * F(crd[z],:)
+// with one W-wide row per leaf fiber f (position-compressed along the sparse levels).
+//
+// The stage streams crd/vals once, gathers cached factor rows and writes T once, so it is
+// bound by memory traffic.  What limits it in practice is the number of vector-memory
+// instructions, not bytes: a lane group that stores its own 16..128-byte row whenever a
+// fiber ends issues one mostly-masked store per step.  The kernel therefore collects the
+// rows of a tile in LDS and writes them out at the end with full-width stores:
+//
+//   stage 1  tile-local fiber bounds; one LDS record per nonzero {factor row offset, value}
+//   stage 2  fiber ends marked in the records (top bit of the offset); first fiber of every
+//            lane-group chunk
+//   walk     a lane group of LG = W / VEC lanes owns a contiguous chunk of nonzeros and keeps
+//            U gathers in flight.  The walk has no branches: after every nonzero the running
+//            sum is written to the current fiber's row of the LDS tile (the last write of a
+//            fiber leaves its sum), and a fiber end only changes registers (sum cleared, row
+//            advanced).  The piece of a fiber that began in an earlier chunk is written to a
+//            spare row nobody reads, captured in registers and added to its row after a barrier.
+//   flush    rows leave LDS as contiguous 16-byte-per-lane stores; the (at most two) rows
+//            shared with neighbouring tiles are added atomically to pre-zeroed memory
+#include "device_common.h"
+
+namespace sck {
+
+constexpr int LNT = 256;  // threads per workgroup of the traversal kernel
+
+struct LeafArgs {
+    const int32_t *pos, *crd;
+    const void *vals;
+    const void *F;
+    int64_t ldF;
+    void *Tout;
+    int32_t tn, ta;
+    int32_t ntiles;
+};
+
+template <typename T>
+struct alignas(sizeof(T) == 4 ? 8 : 16) LeafRec {
+    uint32_t koff;  // byte offset of the factor row; bit 31 set when the nonzero ends its fiber
+    T v;
+};
+
+// LDS rows are W + 16 bytes apart (keeps 16-byte alignment, spreads rows over banks); the tile
+// holds ta rows and, behind them, one spare row per lane group of a wavefront; the spare rows
+// absorb the writes of the padding records and of the chunk heads.
+template <typename T>
+__host__ __device__ constexpr int leaf_row_stride(int W)
+{
+    return W + 16 / (int)sizeof(T);
+}
+
+template <typename T>
+__host__ __device__ constexpr size_t leaf_lds_bytes(int W, int tn, int ta)
+{
+    const int spare = 64 / (W / (16 / (int)sizeof(T)));
+    return (size_t)(ta + spare) * leaf_row_stride<T>(W) * sizeof(T) + (size_t)padded(tn + 8) * sizeof(LeafRec<T>) +
+           (size_t)(ta + 2) * 4 + (size_t)LNT * 4 + 64;
+}
+
+// Global reads of one tile's staging, held in registers until the tile's turn.
+template <typename T>
+struct LeafStage {
+    static constexpr int MAXR = 4;   // tn <= MAXR * LNT
+    static constexpr int MAXB = 3;   // ta + 1 <= MAXB * LNT
+    uint32_t kk[MAXR];
+    T vv[MAXR];
+    int bb[MAXB];
+};
+
+// Issues every global read of a tile's staging at once (clamped indices keep the redundant
+// ones in bounds), so the staging costs one memory latency, not one per loop trip.
+template <typename T>
+__device__ __forceinline__ void leaf_issue(const LeafArgs &a, const TileRec &t, int tid, LeafStage<T> &s)
+{
+    const T *vals = static_cast<const T *>(a.vals);
+    const int nchild = t.n1 - t.n0;
+#pragma unroll
+    for (int r = 0; r < LeafStage<T>::MAXR; ++r) {
+        const int c = t.n0 + min(tid + r * LNT, nchild - 1);
+        s.kk[r] = (uint32_t)a.crd[c];
+        s.vv[r] = vals[c];
+    }
+#pragma unroll
+    for (int r = 0; r < LeafStage<T>::MAXB; ++r) s.bb[r] = a.pos[t.a0 + min(tid + r * LNT, t.na)];
+}
+
+// Persistent workgroups: workgroup b handles tiles b, b + gridDim.x, ...  While one tile is
+// walked, the staging reads of the next are already in flight, and the row stores of the
+// previous tile drain behind them, so the three phases of consecutive tiles overlap.
+template <typename T, int W>
+__global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const TileRec *__restrict__ tiles)
+{
+    // `tiles` is a separate restrict-qualified argument so that the tile records stay scalar
+    // loads inside the loop (nothing the kernel stores can alias them).
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int LG = W / VEC;
+    constexpr int G = LNT / LG;
+    constexpr int U = 4;
+    static_assert(W % VEC == 0 && (LG & (LG - 1)) == 0 && LG <= 64, "row width");
+    using P = Pack<T, VEC>;
+    using Acc = AccVec<T, VEC>;
+    using Rec = LeafRec<T>;
+    using Stage = LeafStage<T>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int RS = leaf_row_stride<T>(W);
+    constexpr int SPARE = 64 / LG;
+    T *row_s = reinterpret_cast<T *>(smem);                                    // (ta + SPARE) rows of RS
+    Rec *rec_s = reinterpret_cast<Rec *>(row_s + (size_t)(a.ta + SPARE) * RS); // padded(tn + 8)
+    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));         // ta + 2: first nonzero of each fiber (tile-local)
+    int *chunk_lr = ba_s + a.ta + 2;                                       // LNT: fiber holding the first nonzero of each chunk
+
+    const int tid = threadIdx.x;
+    const int g = tid / LG, li = tid % LG;
+    const uint32_t rowF = (uint32_t)(a.ldF * sizeof(T));
+    const char *Fb = static_cast<const char *>(a.F);
+    const uint32_t lo16 = (uint32_t)li * 16u;
+    const int stride = gridDim.x, last = a.ntiles - 1;
+
+    int nx = blockIdx.x + stride;                 // the launch has at most ntiles workgroups
+    TileRec t = tiles[blockIdx.x];
+    TileRec t1 = tiles[min(nx, last)];
+    Stage st;
+    leaf_issue(a, t, tid, st);
+    // First tile: wait here, so that the loop body itself never waits on staging registers
+    // (a wait there would also wait for the previous tile's row stores): vmcnt(0).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    for (;;) {
+        const int nchild = t.n1 - t.n0;
+        const int na = t.na;
+        const int q = max(((nchild + G - 1) / G + U - 1) / U * U, U);   // nonzeros per lane group, multiple of U
+
+        // ---- stage 1: registers -> LDS ----
+#pragma unroll
+        for (int r = 0; r < Stage::MAXR; ++r) {
+            const int c = tid + r * LNT;
+            if (c < nchild) {
+                Rec rec;
+                rec.koff = st.kk[r] * rowF;
+                rec.v = st.vv[r];
+                rec_s[pidx(c)] = rec;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < Stage::MAXB; ++r) {
+            const int i = tid + r * LNT;
+            if (i <= na) ba_s[i] = min(max(st.bb[r], t.n0), t.n1) - t.n0;
+        }
+        if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
+            Rec rec;
+            rec.koff = 0;
+            rec.v = T(0);
+            rec_s[pidx(nchild + tid)] = rec;
+        }
+        __syncthreads();
+
+        // ---- stage 2 ----
+        for (int i = tid; i < na; i += LNT) {
+            const int lo = ba_s[i], hi = ba_s[i + 1];
+            if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
+            rec_s[pidx(hi - 1)].koff |= 0x80000000u;
+            for (int m = (lo + q - 1) / q; m * q < hi; ++m) chunk_lr[m] = i;
+        }
+        __syncthreads();
+
+        // ---- reads of the next tile (and the record of the one after) go out now ----
+        const bool more = nx < a.ntiles;
+        Stage sn;
+        if (more) leaf_issue(a, t1, tid, sn);
+        const TileRec t2 = tiles[min(nx + stride, last)];
+
+        // ---- walk ----
+        const int gs = g * q, ge = min(gs + q, nchild);
+        bool head = false;   // the chunk starts inside a fiber that began in an earlier chunk
+        int lr0 = 0;
+        Acc carry;           // sum of that fiber's nonzeros inside this chunk
+        carry.clear();
+        if (gs < ge) {
+            lr0 = chunk_lr[g];
+            head = ba_s[lr0] != gs;
+            bool inhead = head;
+            T *rowp = row_s + lr0 * RS + li * VEC;
+            T *dst = head ? row_s + (a.ta + g % SPARE) * RS + li * VEC : rowp;
+            Acc acc;
+            acc.clear();
+            for (int c = gs; c < ge; c += U) {
+                Rec r[U];
+                P d[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
+#pragma unroll
+                for (int u = 0; u < U; ++u) d[u] = *reinterpret_cast<const P *>(Fb + ((r[u].koff & 0x7fffffffu) + lo16));
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    P o;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        acc.v[i] += r[u].v * d[u].v[i];
+                        o.v[i] = acc.v[i];
+                    }
+                    *reinterpret_cast<P *>(dst) = o;
+                    const bool end = (int32_t)r[u].koff < 0;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        carry.v[i] = inhead ? acc.v[i] : carry.v[i];
+                        acc.v[i] = end ? T(0) : acc.v[i];
+                    }
+                    inhead = inhead && !end;
+                    rowp = end ? rowp + RS : rowp;
+                    dst = end ? rowp : dst;
+                }
+            }
+        }
+        // The prefetched registers are complete here, before any store is queued behind
+        // them (waits count loads and stores in issue order): vmcnt(0), other counters free.
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+
+        // ---- carries ----
+        if (head) {
+            T *dst = row_s + lr0 * RS + li * VEC;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) atomic_add(dst + i, carry.v[i]);
+        }
+        __syncthreads();
+
+        // ---- flush ----
+        T *Tout = static_cast<T *>(a.Tout) + (int64_t)t.a0 * W;
+        for (int r = g; r < na; r += G) {
+            const P row = *reinterpret_cast<const P *>(row_s + r * RS + li * VEC);
+            T *dst = Tout + (int64_t)r * W + li * VEC;
+            const bool shared = (r == 0 && (t.flags & 1)) || (r == na - 1 && (t.flags & 2));
+            if (!shared) {
+                *reinterpret_cast<P *>(dst) = row;
+            } else {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+            }
+        }
+        if (!more) break;
+        t = t1;
+        t1 = t2;
+        st = sn;
+        nx += stride;
+    }
+}
+
+namespace {
+template <typename T, int W>
+sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
+                        const sc_dense_view &F, void *Tout, const char *name)
+{
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0) return SC_OK;
+    // factor rows are addressed with 31-bit byte offsets (bit 31 marks fiber ends)
+    if ((uint64_t)F.rows * (uint64_t)F.ld * sizeof(T) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
+    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta + 1 > LeafStage<float>::MAXB * LNT) return SC_ERR_SCHED_UNSUPPORTED;   // staging registers
+    LeafArgs a = {};
+    a.pos = pos_leaf; a.crd = crd_leaf;
+    a.vals = vals;
+    a.F = F.data;
+    a.ldF = F.ld;
+    a.Tout = Tout;
+    a.tn = p->caps.tn; a.ta = p->caps.ta;
+    ln.begin("zero_shared_rows");
+    zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
+    ln.end();
+    ln.begin(name);
+    // persistent launch: as many workgroups as fit on the chip at once (LDS-limited), never more than tiles
+    a.ntiles = ntiles;
+    const size_t lds = leaf_lds_bytes<T>(W, a.tn, a.ta);
+    const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
+    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 16) : fit;
+    const int blocks = std::min(ntiles, 256 * per_cu);
+    leaf_traverse_kernel<T, W><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
+    ln.end();
+    return ln.status;
+}
+}  // namespace
+
+size_t leaf_traverse_lds_bytes(const sc_plan *p, int W)
+{
+    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta + 1 > LeafStage<float>::MAXB * LNT) return SIZE_MAX;   // staging registers
+    return p->dtype == SC_F64 ? leaf_lds_bytes<double>(W, p->caps.tn, p->caps.ta) : leaf_lds_bytes<float>(W, p->caps.tn, p->caps.ta);
+}
+
+sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
+                               const sc_dense_view &F, void *Tout, int W, const char *name)
+{
+    const bool f64 = p->dtype == SC_F64;
+#define SC_LEAF(WW)                                                                                   \
+    case WW:                                                                                          \
+        return f64 ? leaf_traverse<double, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)        \
+                   : leaf_traverse<float, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
+    switch (W) {
+        SC_LEAF(8)
+        SC_LEAF(16)
+        SC_LEAF(32)
+        SC_LEAF(64)
+    default: return SC_ERR_SCHED_UNSUPPORTED;
+    }
+#undef SC_LEAF
+}
+
+}  // namespace sck

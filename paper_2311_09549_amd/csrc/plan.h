@@ -93,6 +93,7 @@ namespace sck {
 struct Tuning {
     int32_t tn = 0, ta = 0, tb = 0;
     int32_t interleave = 0;  // stride of the tile upload order (0 = built-in)
+    int32_t per_cu = 0;      // workgroups per compute unit of the persistent kernels (0 = as many as fit)
 };
 Tuning &tuning();
 
