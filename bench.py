@@ -44,7 +44,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also queue the library's plain copy kernel (256 MiB) a few times, for counter runs")
+                    help="also queue and time the library's plain copy kernel (1 GiB), for counter runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding by top-level slice is "
@@ -120,10 +120,23 @@ def main() -> int:
     if args.calibrate_copy:
         src = torch.empty(traffic_store.COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
+        stream = torch.cuda.current_stream().cuda_stream
         for _ in range(3):
-            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, torch.cuda.current_stream().cuda_stream)
+            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
         torch.cuda.synchronize()
+        beg, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        beg.record()
+        for _ in range(10):
+            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
+        end.record()
+        torch.cuda.synchronize()
+        copy_ms = beg.elapsed_time(end) / 10
+        # the library's plain copy kernel as a practical ceiling: bytes read + bytes written per second
+        stream_copy = {"bytes_each_way": traffic_store.COPY_BYTES, "ms": copy_ms,
+                       "gbs_read_plus_write": 2 * traffic_store.COPY_BYTES / (copy_ms * 1e-3) / 1e9}
         del src, dst
+    else:
+        stream_copy = None
 
     result = {
         "metric": "effective GFLOP/s of the fused schedule (schedule flops / step time), 1 MI355X",
@@ -148,6 +161,8 @@ def main() -> int:
         "algorithmic_gbs_whole_step": bytes_fused / (ms * 1e-3) / 1e9,
         "setup_s": {"generate": t_gen, "convert_plan_upload": t_plan},
     }
+    if stream_copy:
+        result["stream_copy"] = stream_copy
     del fused
     torch.cuda.empty_cache()
 

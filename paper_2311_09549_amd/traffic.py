@@ -24,7 +24,7 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 DEFAULT_PATH = os.path.join(HERE, "traffic.json")
 COPY_KERNEL = "stream_copy_kernel"
-COPY_BYTES = 256 << 20  # size of the calibration copy bench.py queues
+COPY_BYTES = 1 << 30  # size of the calibration copy bench.py queues (well beyond the 256 MB last-level cache)
 
 
 def source_digest() -> str:
