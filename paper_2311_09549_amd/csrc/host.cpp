@@ -722,7 +722,8 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             // tiles far apart in the tensor, so the atomic updates of one heavy output row are
             // spread over the kernel's duration instead of queueing on one address.
             const size_t nt = p->tiles.size();
-            const size_t stride = (size_t)std::max<int32_t>(1, tuning().interleave ? tuning().interleave : 64);
+            const size_t stride =
+                plan_wants_tensor_order(p) ? 1 : (size_t)std::max<int32_t>(1, tuning().interleave ? tuning().interleave : 64);
             std::vector<TileRec> order;
             try {
                 order.reserve(nt);

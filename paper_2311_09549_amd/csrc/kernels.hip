@@ -579,8 +579,8 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.begin("mttkrp3_fused");
             mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
-            ln.begin("ttmc3_fused_mfma");
-            order3_kernel<T, W, 0, 2><<<ntiles, NT, lds, stream>>>(a);
+            ln.status = launch_ttmc3_fused_mfma(p, ln, sp, fac, out);
+            return ln.status;
         } else {
             ln.begin("ttmc3_fused_valu");
             order3_kernel<T, W, 0, 1><<<ntiles, NT, lds, stream>>>(a);
@@ -644,6 +644,12 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.tn = 512;
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
+            if (sched == SC_SCHED_FUSED && dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
+                // matrix-core kernel: measured best on the 30 M-nonzero workload (row tile + carry rows + records in ~40 KB)
+                c.tn = 768;
+                c.ta = 224;
+                c.tb = 64;
+            }
         }
         break;
     }
@@ -651,6 +657,11 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
     case K_TTMC4: return order4_caps(dtype, fcols);
     }
     return c;
+}
+
+bool plan_wants_tensor_order(const sc_plan *p)
+{
+    return p->kind == K_TTMC3 && p->sched == SC_SCHED_FUSED && p->dtype == SC_F32 && p->fcols[0] == 16 && p->fcols[1] == 16;
 }
 
 size_t lds_bytes_needed(const sc_plan *p)
@@ -664,6 +675,7 @@ size_t lds_bytes_needed(const sc_plan *p)
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
         }
+        if (plan_wants_tensor_order(p)) return ttmc3_mfma_caps_ok(p) ? ttmc3_mfma_lds_bytes(p) : SIZE_MAX;
         {
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);

@@ -12,15 +12,13 @@
 //   stage 1  tile-local fiber bounds; one LDS record per nonzero {factor row offset, value}
 //   stage 2  fiber ends marked in the records (top bit of the offset); first fiber of every
 //            lane-group chunk
-//   walk     a lane group of LG = W / VEC lanes owns a contiguous chunk of nonzeros and keeps
-//            U gathers in flight.  The walk has no branches: after every nonzero the running
-//            sum is written to the current fiber's row of the LDS tile (the last write of a
-//            fiber leaves its sum), and a fiber end only changes registers (sum cleared, row
-//            advanced).  The piece of a fiber that began in an earlier chunk is written to a
-//            spare row nobody reads, captured in registers and added to its row after a barrier.
+//   walk     the shared branch-free leaf walk: a lane group of LG = W / VEC lanes owns a
+//            contiguous chunk of nonzeros, keeps U gathers in flight and writes the running
+//            sum to the current fiber's row of the LDS tile after every nonzero; chunk heads
+//            are combined after a barrier without atomics
 //   flush    rows leave LDS as contiguous 16-byte-per-lane stores; the (at most two) rows
 //            shared with neighbouring tiles are added atomically to pre-zeroed memory
-#include "device_common.h"
+#include "leaf_walk.h"
 
 namespace sck {
 
@@ -37,26 +35,9 @@ struct LeafArgs {
 };
 
 template <typename T>
-struct alignas(sizeof(T) == 4 ? 8 : 16) LeafRec {
-    uint32_t koff;  // byte offset of the factor row; bit 31 set when the nonzero ends its fiber
-    T v;
-};
-
-// LDS rows are W + 16 bytes apart (keeps 16-byte alignment, spreads rows over banks); the tile
-// holds ta rows and, behind them, one spare row per lane group of a wavefront; the spare rows
-// absorb the writes of the padding records and of the chunk heads.
-template <typename T>
-__host__ __device__ constexpr int leaf_row_stride(int W)
-{
-    return W + 16 / (int)sizeof(T);
-}
-
-template <typename T>
 __host__ __device__ constexpr size_t leaf_lds_bytes(int W, int tn, int ta)
 {
-    const int spare = 64 / (W / (16 / (int)sizeof(T)));
-    return (size_t)(ta + spare) * leaf_row_stride<T>(W) * sizeof(T) + (size_t)padded(tn + 8) * sizeof(LeafRec<T>) +
-           (size_t)(ta + 2) * 4 + (size_t)LNT * 4 + 64;
+    return leaf_walk_lds_bytes<T>(W, tn, ta, LNT) + 64;
 }
 
 // Global reads of one tile's staging, held in registers until the tile's turn.
@@ -100,23 +81,20 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
     constexpr int U = 4;
     static_assert(W % VEC == 0 && (LG & (LG - 1)) == 0 && LG <= 64, "row width");
     using P = Pack<T, VEC>;
-    using Acc = AccVec<T, VEC>;
     using Rec = LeafRec<T>;
     using Stage = LeafStage<T>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int RS = leaf_row_stride<T>(W);
-    constexpr int SPARE = 64 / LG;
-    T *row_s = reinterpret_cast<T *>(smem);                                    // (ta + SPARE) rows of RS
-    Rec *rec_s = reinterpret_cast<Rec *>(row_s + (size_t)(a.ta + SPARE) * RS); // padded(tn + 8)
-    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));         // ta + 2: first nonzero of each fiber (tile-local)
-    int *chunk_lr = ba_s + a.ta + 2;                                       // LNT: fiber holding the first nonzero of each chunk
+    T *row_s = reinterpret_cast<T *>(smem);                                    // (ta + 1) rows of RS
+    T *carry_s = row_s + (size_t)(a.ta + 1) * RS;                              // G rows of RS
+    Rec *rec_s = reinterpret_cast<Rec *>(carry_s + (size_t)G * RS);            // padded(tn + 8)
+    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));             // ta + 2: first nonzero of each fiber (tile-local)
+    int *chunk_lr = ba_s + a.ta + 2;                                           // G: fiber holding the first nonzero of each chunk
 
     const int tid = threadIdx.x;
     const int g = tid / LG, li = tid % LG;
     const uint32_t rowF = (uint32_t)(a.ldF * sizeof(T));
-    const char *Fb = static_cast<const char *>(a.F);
-    const uint32_t lo16 = (uint32_t)li * 16u;
     const int stride = gridDim.x, last = a.ntiles - 1;
 
     int nx = blockIdx.x + stride;                 // the launch has at most ntiles workgroups
@@ -131,7 +109,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
     for (;;) {
         const int nchild = t.n1 - t.n0;
         const int na = t.na;
-        const int q = max(((nchild + G - 1) / G + U - 1) / U * U, U);   // nonzeros per lane group, multiple of U
+        const int q = leaf_chunk<U>(nchild, G);   // nonzeros per lane group, multiple of U
 
         // ---- stage 1: registers -> LDS ----
 #pragma unroll
@@ -158,12 +136,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
         __syncthreads();
 
         // ---- stage 2 ----
-        for (int i = tid; i < na; i += LNT) {
-            const int lo = ba_s[i], hi = ba_s[i + 1];
-            if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
-            rec_s[pidx(hi - 1)].koff |= 0x80000000u;
-            for (int m = (lo + q - 1) / q; m * q < hi; ++m) chunk_lr[m] = i;
-        }
+        leaf_mark(rec_s, ba_s, chunk_lr, tid, LNT, na, q);
         __syncthreads();
 
         // ---- reads of the next tile (and the record of the one after) go out now ----
@@ -173,58 +146,12 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
         const TileRec t2 = tiles[min(nx + stride, last)];
 
         // ---- walk ----
-        const int gs = g * q, ge = min(gs + q, nchild);
-        bool head = false;   // the chunk starts inside a fiber that began in an earlier chunk
-        int lr0 = 0;
-        Acc carry;           // sum of that fiber's nonzeros inside this chunk
-        carry.clear();
-        if (gs < ge) {
-            lr0 = chunk_lr[g];
-            head = ba_s[lr0] != gs;
-            bool inhead = head;
-            T *rowp = row_s + lr0 * RS + li * VEC;
-            T *dst = head ? row_s + (a.ta + g % SPARE) * RS + li * VEC : rowp;
-            Acc acc;
-            acc.clear();
-            for (int c = gs; c < ge; c += U) {
-                Rec r[U];
-                P d[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
-#pragma unroll
-                for (int u = 0; u < U; ++u) d[u] = *reinterpret_cast<const P *>(Fb + ((r[u].koff & 0x7fffffffu) + lo16));
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    P o;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) {
-                        acc.v[i] += r[u].v * d[u].v[i];
-                        o.v[i] = acc.v[i];
-                    }
-                    *reinterpret_cast<P *>(dst) = o;
-                    const bool end = (int32_t)r[u].koff < 0;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) {
-                        carry.v[i] = inhead ? acc.v[i] : carry.v[i];
-                        acc.v[i] = end ? T(0) : acc.v[i];
-                    }
-                    inhead = inhead && !end;
-                    rowp = end ? rowp + RS : rowp;
-                    dst = end ? rowp : dst;
-                }
-            }
-        }
+        const LeafCarry cst = leaf_walk<T, W, U>(row_s, carry_s, rec_s, ba_s, chunk_lr, a.F, g, li, q, nchild);
         // The prefetched registers are complete here, before any store is queued behind
         // them (waits count loads and stores in issue order): vmcnt(0), other counters free.
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-
-        // ---- carries ----
-        if (head) {
-            T *dst = row_s + lr0 * RS + li * VEC;
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) atomic_add(dst + i, carry.v[i]);
-        }
+        leaf_combine<T, W>(row_s, carry_s, ba_s, chunk_lr, cst, g, li, q);
         __syncthreads();
 
         // ---- flush ----

@@ -100,6 +100,10 @@ Tuning &tuning();
 // Built-in tile caps for a contraction (host side; the kernels size their LDS from them).
 TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols);
 
+// True when the plan's kernels walk contiguous runs of tiles and therefore want the device tile
+// table in tensor order rather than interleaved.
+bool plan_wants_tensor_order(const sc_plan *plan);
+
 // Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
 size_t lds_bytes_needed(const sc_plan *plan);
 
