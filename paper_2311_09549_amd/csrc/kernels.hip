@@ -472,24 +472,31 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
         }
     };
 
+    // A lane group whose chunk starts inside a slice keeps that slice's piece ("head") in
+    // registers when the slice ends; a chunk that ends inside a slice parks its running sum
+    // ("tail") in its LDS row together with a flag telling whether the slice began in this
+    // chunk.  After the barrier the group holding a head adds the tails of the chunks before
+    // it, back to the one in which the slice began, and issues the tile's single update of
+    // that output row.  (LDS float atomics for this measured about a quarter of the kernel.)
     const int gs = g * q, ge = min(gs + q, nchild);
+    int head_ls = -1;
+    P headv;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) headv.v[i] = T(0);
     if (gs < ge) {
         bool started = (gs == 0) || (rec_s[pidx(gs - 1)].s >= 0);  // the current slice starts in this chunk
         Acc tsum, asum;
         tsum.clear();
         asum.clear();
         auto emit = [&](int s, bool whole) {
-            if (whole) {
-                P o;
+            P o;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            if (whole) {
                 direct(s, o);
             } else {
-                const int slot = slo_s[s] / q;
-                T *dst = slot_s + slot * W + li * VEC;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, asum.v[i]);
-                if (li == 0) slot_id[slot] = s;
+                headv = o;
+                head_ls = s;
             }
         };
         // Chunks start at multiples of U and the records up to the next multiple of U past
@@ -529,12 +536,24 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 #pragma unroll
             for (int i = 0; i < VEC; ++i) asum.v[i] += tsum.v[i] * cl.v[i];
         }
-        const int cs = chunk_ls[g];
-        if (cs >= 0) emit(cs, false);  // ... and inside a slice
+        if (chunk_ls[g] >= 0) {  // ... and inside a slice: park the tail
+            P o;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            *reinterpret_cast<P *>(slot_s + g * W + li * VEC) = o;
+            if (li == 0) slot_id[g] = started ? 1 : 0;
+        }
     }
     __syncthreads();
-    const int s = slot_id[g];
-    if (s >= 0) direct(s, *reinterpret_cast<const P *>(slot_s + g * W + li * VEC));
+    if (head_ls >= 0) {
+        for (int h = g - 1; h >= 0; --h) {
+            const P tl = *reinterpret_cast<const P *>(slot_s + h * W + li * VEC);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) headv.v[i] += tl.v[i];
+            if (slot_id[h] != 0) break;   // the slice began in chunk h
+        }
+        direct(head_ls, headv);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
