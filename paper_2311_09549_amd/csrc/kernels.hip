@@ -680,7 +680,9 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 
 bool plan_wants_tensor_order(const sc_plan *p)
 {
-    return p->kind == K_TTMC3 && p->sched == SC_SCHED_FUSED && p->dtype == SC_F32 && p->fcols[0] == 16 && p->fcols[1] == 16;
+    if (p->sched != SC_SCHED_FUSED || p->dtype != SC_F32) return false;
+    if (p->kind == K_TTMC3) return p->fcols[0] == 16 && p->fcols[1] == 16;
+    return p->kind == K_TTMC4;
 }
 
 size_t lds_bytes_needed(const sc_plan *p)
@@ -694,7 +696,7 @@ size_t lds_bytes_needed(const sc_plan *p)
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
         }
-        if (plan_wants_tensor_order(p)) return ttmc3_mfma_caps_ok(p) ? ttmc3_mfma_lds_bytes(p) : SIZE_MAX;
+        if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) return ttmc3_mfma_caps_ok(p) ? ttmc3_mfma_lds_bytes(p) : SIZE_MAX;
         {
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);

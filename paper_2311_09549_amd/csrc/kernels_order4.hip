@@ -350,8 +350,8 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
-            ln.begin("ttmc4_fused_mfma");
-            order4_kernel<T, N, M, 0, 2><<<ntiles, NT, lds, stream>>>(a);
+            ln.status = launch_ttmc4_fused_mfma(p, ln, sp, fac, out);   // dedicated matrix-core kernel
+            return ln.status;
         } else {
             ln.begin("ttmc4_fused_valu");
             order4_kernel<T, N, M, 0, 1><<<ntiles, NT, lds, stream>>>(a);
@@ -398,6 +398,7 @@ size_t order4_lds_bytes_needed(const sc_plan *p)
     const int N = (int)p->fcols[2], W2 = (int)(p->fcols[1] * p->fcols[2]), L = (int)p->fcols[0];
     const size_t own = p->dtype == SC_F64 ? order4_lds_bytes<double>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb)
                                           : order4_lds_bytes<float>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb);
+    if (p->sched == SC_SCHED_FUSED && p->dtype == SC_F32) return ttmc4_mfma_caps_ok(p) ? ttmc4_mfma_lds_bytes(p) : SIZE_MAX;
     if (p->sched != SC_SCHED_FISSIONED) return own;
     return std::max(own, leaf_traverse_lds_bytes(p, N));  // the leaf traversal is the first FISSIONED kernel
 }

@@ -1,0 +1,305 @@
+// FUSED order-4 TTM chain on matrix cores, fp32, M = N = 8, L <= 16:
+//     A(i,l,m,n) = sum_{j,k,p} B(i,j,k,p) * C(j,l) * D(k,m) * E(p,n)
+// under the two-level nest obtained by applying the split-and-fuse step of Section 4.2 twice
+// (the shape of the second schedule of Table 2, kernel 5):
+//     T1(f3, n)    = sum_{p' in f3} B * E(p, n)              f3 = (i,j,k) fiber
+//     T2(f2, m, n) = sum_{f3 in f2} D(k, m) * T1(f3, n)      f2 = (i,j) fiber
+//     A(i, l, m, n) = sum_{f2 in slice i} C(j, l) * T2(f2, m, n)
+// Both temporaries live in LDS for the nodes of one tile.
+//
+//   stage    every global read of the tile is issued before the first is used
+//   leaves   the shared branch-free leaf walk with 8-wide rows (2 lanes per nonzero) -> T1 rows
+//   middle   the same walk one level up: children are the f3 fibers (their T1 row comes from
+//            LDS, the D row is gathered), a group of 16 lanes owns a chunk of children and
+//            keeps the 64-wide running sum of the current f2 fiber -> T2 rows
+//   consume  A(i, l, mn) = sum_f2 T2(f2, mn) * C(j, l): wavefront w owns the 16 columns
+//            mn = 16 w .. 16 w + 15 for every slice of the tile (four f2 fibers per
+//            v_mfma_f32_16x16x4_f32, l padded to 16), so no sums cross wavefronts; a lane ends
+//            up with four consecutive mn of one l, i.e. one 16-byte store
+//   carry    a workgroup owns a contiguous run of tiles; the sum of a slice that continues
+//            into the next tile stays in registers, so a heavy slice costs one global update
+//            per workgroup; only a slice that crosses the run's ends is added atomically to
+//            the zeroed output
+#include "leaf_walk.h"
+
+namespace sck {
+
+struct Ttmc4Args {
+    const int32_t *crd1, *pos2, *crd2, *pos3, *crd3, *pos4, *crd4;
+    const float *vals;
+    const float *C, *D, *E;
+    int64_t ldC, ldD, ldE;
+    float *A;
+    int32_t L;
+    int32_t tn, ta, tb;
+    int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
+};
+
+constexpr int T4_N = 8, T4_M = 8, T4_W2 = T4_M * T4_N;
+constexpr int T4_RS1 = leaf_row_stride<float>(T4_N);
+constexpr int T4_RS2 = leaf_row_stride<float>(T4_W2);
+constexpr int T4_G1 = NT / (T4_N / 4);     // lane groups of the leaf walk (2 lanes each)
+constexpr int T4_LG2 = T4_W2 / 4;          // lanes per T2 row
+constexpr int T4_G2 = NT / T4_LG2;         // lane groups of the middle walk
+constexpr int T4_MAXR = 3;                 // tn <= T4_MAXR * NT
+constexpr int T4_MAXA = 2;                 // ta + 1 <= T4_MAXA * NT, tb + 1 <= NT
+static_assert(NT / 64 == T4_W2 / 16, "one wavefront per 16 columns of a T2 row");
+
+__host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb)
+{
+    return leaf_walk_lds_bytes<float>(T4_N, tn, ta, NT) + (size_t)(tb + 1 + T4_G2) * T4_RS2 * 4 + (size_t)(ta + 4) * 4 +
+           (size_t)(tb + 2) * 4 + (size_t)T4_G2 * 4 + (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
+}
+
+typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
+
+__global__ void __launch_bounds__(NT) ttmc4_fused_mfma_kernel(Ttmc4Args a, const TileRec *__restrict__ tiles)
+{
+    using P = Pack<float, 4>;
+    using Rec = LeafRec<float>;
+    constexpr int U1 = 4, U2 = 4;
+    constexpr int RS1 = T4_RS1, RS2 = T4_RS2;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float *row1_s = reinterpret_cast<float *>(smem);                          // (ta + 1) rows of RS1: T1
+    float *carry1_s = row1_s + (size_t)(a.ta + 1) * RS1;                      // G1 rows of RS1
+    float *row2_s = carry1_s + (size_t)T4_G1 * RS1;                           // (tb + 1) rows of RS2: T2
+    float *carry2_s = row2_s + (size_t)(a.tb + 1) * RS2;                      // G2 rows of RS2
+    Rec *rec_s = reinterpret_cast<Rec *>(carry2_s + (size_t)T4_G2 * RS2);     // padded(tn + 8)
+    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // ta + 2: first nonzero of each f3
+    int *chunk_lr1 = ba_s + a.ta + 2;                                         // G1
+    uint32_t *krec_s = reinterpret_cast<uint32_t *>(chunk_lr1 + T4_G1);       // ta + 4: D row offset of each f3 | end-of-f2 bit 31
+    int *bb_s = reinterpret_cast<int *>(krec_s + a.ta + 4);                   // tb + 2: first f3 of each f2
+    int *chunk_lr2 = bb_s + a.tb + 2;                                         // G2
+    uint32_t *coff2_s = reinterpret_cast<uint32_t *>(chunk_lr2 + T4_G2);      // tb: byte offset of C(j,:) per f2
+    int *bc_s = reinterpret_cast<int *>(coff2_s + a.tb);                      // tb + 2: first f2 of each slice
+    int *crdc_s = bc_s + a.tb + 2;                                            // tb: output row of each slice
+
+    const int tid = threadIdx.x;
+    const int L = a.L;
+    const int rowA = L * T4_W2;
+    const uint32_t rowE = (uint32_t)(a.ldE * 4), rowD = (uint32_t)(a.ldD * 4), rowC = (uint32_t)(a.ldC * 4);
+    const int first = blockIdx.x * a.run, lastp1 = min(first + a.run, a.ntiles);
+    auto uni = [](int x) { return __builtin_amdgcn_readfirstlane(x); };
+    const int wave = uni(tid / 64), lane = tid % 64;
+    const int kk = lane / 16, col = lane % 16;
+    t4_floatx4 carry = {0.f, 0.f, 0.f, 0.f};   // this wavefront's columns of the slice continuing from the previous tile
+    bool chain_shared = false;                 // that slice began before this workgroup's run
+
+    for (int tile = first; tile < lastp1; ++tile) {
+        const TileRec t = tiles[tile];
+        const bool in_f = (t.flags & 16) != 0, out_f = (t.flags & 32) != 0;
+        if (tile == first && in_f) chain_shared = true;
+        const int nchild = t.n1 - t.n0;
+        const int na = t.na, nb = t.nb, nc = t.nc;
+        const int q1 = leaf_chunk<U1>(nchild, T4_G1);
+        const int q2 = leaf_chunk<U2>(na, T4_G2);
+
+        // ---- stage ----
+        {
+            uint32_t pp[T4_MAXR];
+            float vv[T4_MAXR];
+            int p4[T4_MAXA], k3[T4_MAXA];
+#pragma unroll
+            for (int r = 0; r < T4_MAXR; ++r) {
+                const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                pp[r] = (uint32_t)a.crd4[c];
+                vv[r] = a.vals[c];
+            }
+#pragma unroll
+            for (int r = 0; r < T4_MAXA; ++r) {
+                p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
+                k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
+            }
+            const int p3 = a.pos3[t.b0 + min(tid, nb)];
+            const int j2 = a.crd2[t.b0 + min(tid, nb - 1)];
+            const int p2 = a.pos2[t.c0 + min(tid, nc)];
+            const int i1 = a.crd1[t.c0 + min(tid, nc - 1)];
+#pragma unroll
+            for (int r = 0; r < T4_MAXR; ++r) {
+                const int c = tid + r * NT;
+                if (c < nchild) {
+                    Rec rec;
+                    rec.koff = pp[r] * rowE;
+                    rec.v = vv[r];
+                    rec_s[pidx(c)] = rec;
+                }
+            }
+            if (tid < U1) {  // dummies completing the last batch of the leaf walk
+                Rec rec;
+                rec.koff = 0;
+                rec.v = 0.f;
+                rec_s[pidx(nchild + tid)] = rec;
+            }
+#pragma unroll
+            for (int r = 0; r < T4_MAXA; ++r) {
+                const int i = tid + r * NT;
+                if (i <= na) ba_s[i] = min(max(p4[r], t.n0), t.n1) - t.n0;
+                if (i < na) krec_s[i] = (uint32_t)k3[r] * rowD;
+            }
+            if (tid < U2) krec_s[na + tid] = 0;   // dummies of the middle walk
+            if (tid <= nb) bb_s[tid] = min(max(p3, t.a0), t.a0 + na) - t.a0;
+            if (tid < nb) coff2_s[tid] = (uint32_t)j2 * rowC;
+            if (tid <= nc) bc_s[tid] = min(max(p2, t.b0), t.b0 + nb) - t.b0;
+            if (tid < nc) crdc_s[tid] = i1;
+        }
+        __syncthreads();
+
+        // ---- marks of both walks ----
+        leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
+        for (int i = tid; i < nb; i += NT) {
+            const int lo = bb_s[i], hi = bb_s[i + 1];
+            if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
+            krec_s[hi - 1] |= 0x80000000u;
+            for (int m = (lo + q2 - 1) / q2; m * q2 < hi; ++m) chunk_lr2[m] = i;
+        }
+        __syncthreads();
+
+        // ---- leaves -> T1 rows ----
+        {
+            const int g = tid / 2, li = tid % 2;
+            const LeafCarry st = leaf_walk<float, T4_N, U1>(row1_s, carry1_s, rec_s, ba_s, chunk_lr1, a.E, g, li, q1, nchild);
+            __syncthreads();
+            leaf_combine<float, T4_N>(row1_s, carry1_s, ba_s, chunk_lr1, st, g, li, q1);
+            __syncthreads();
+        }
+
+        // ---- f3 fibers -> T2 rows: T2(f2, m, :) += D(k, m) * T1(f3, :) ----
+        {
+            const int g = tid / T4_LG2, li = tid % T4_LG2;
+            const int m = li / 2, nq = (li % 2) * 4;
+            const char *Db = reinterpret_cast<const char *>(a.D) + m * 4;
+            LeafCarry st{0, false, false};
+            const int gs = g * q2, ge = min(gs + q2, na);
+            if (gs < ge) {
+                st.lr0 = chunk_lr2[g];
+                st.head = bb_s[st.lr0] != gs;
+                float *rowp = row2_s + st.lr0 * RS2 + li * 4;
+                float *const row0 = rowp;
+                float *dst = st.head ? carry2_s + g * RS2 + li * 4 : rowp;
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int c = gs; c < ge; c += U2) {
+                    uint32_t kr[U2];
+                    P t1[U2];
+                    float d[U2];
+#pragma unroll
+                    for (int u = 0; u < U2; ++u) {
+                        kr[u] = krec_s[c + u];
+                        t1[u] = *reinterpret_cast<const P *>(row1_s + (c + u) * RS1 + nq);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U2; ++u) d[u] = *reinterpret_cast<const float *>(Db + (kr[u] & 0x7fffffffu));
+#pragma unroll
+                    for (int u = 0; u < U2; ++u) {
+                        P o;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            acc[i] += d[u] * t1[u].v[i];
+                            o.v[i] = acc[i];
+                        }
+                        *reinterpret_cast<P *>(dst) = o;
+                        const bool end = (int32_t)kr[u] < 0;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) acc[i] = end ? 0.f : acc[i];
+                        rowp = end ? rowp + RS2 : rowp;
+                        dst = end ? rowp : dst;
+                    }
+                }
+                st.owner = st.head && (rowp != row0 || ge == na);
+            }
+            __syncthreads();
+            leaf_combine<float, T4_W2>(row2_s, carry2_s, bb_s, chunk_lr2, st, g, li, q2);
+            __syncthreads();
+        }
+
+        // ---- consume: T2 rows x gathered C rows -> A ----
+        {
+            const bool lval = col < L;
+            const char *Cb = reinterpret_cast<const char *>(a.C) + min(col, L - 1) * 4;
+            const bool last_tile = tile + 1 == lastp1;
+            auto emit = [&](const t4_floatx4 &v, int ls, bool atomic) {
+                // v[r] = A(l = col, mn = 16 wave + 4 kk + r)
+                if (!lval) return;
+                float *dst = a.A + (int64_t)uni(crdc_s[ls]) * rowA + col * T4_W2 + wave * 16 + 4 * kk;
+                if (!atomic) {
+                    *reinterpret_cast<t4_floatx4 *>(dst) = v;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) atomic_add(dst + r, v[r]);
+                }
+            };
+            for (int ls = 0; ls < nc; ++ls) {
+                const int f0 = uni(bc_s[ls]), f1 = uni(bc_s[ls + 1]);
+                t4_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                constexpr int UB = 4;   // 4-fiber blocks whose operand reads are issued together
+                for (int fb = f0; fb < f1; fb += 4 * UB) {
+                    float cv[UB], tv[UB];
+#pragma unroll
+                    for (int ub = 0; ub < UB; ++ub) {
+                        const int lf = fb + 4 * ub + kk;
+                        const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
+                        const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
+                        const float cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
+                        tv[ub] = lf < f1 ? tvr : 0.f;
+                        cv[ub] = lval ? cvr : 0.f;
+                    }
+#pragma unroll
+                    for (int ub = 0; ub < UB; ++ub)
+                        if (fb + 4 * ub < f1) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(tv[ub], cv[ub], acc, 0, 0, 0);
+                }
+                const bool incoming = ls == 0 && in_f, outgoing = ls == nc - 1 && out_f;
+                if (incoming) acc += carry;
+                if (outgoing) {
+                    if (last_tile) emit(acc, ls, true);   // continues in another workgroup's run
+                    else carry = acc;
+                } else {
+                    emit(acc, ls, incoming && chain_shared);
+                    if (incoming) chain_shared = false;
+                }
+            }
+        }
+        __syncthreads();
+    }  // tiles of the run
+}
+
+size_t ttmc4_mfma_lds_bytes(const sc_plan *p) { return ttmc4_lds_bytes(p->caps.tn, p->caps.ta, p->caps.tb); }
+
+bool ttmc4_mfma_caps_ok(const sc_plan *p)
+{
+    return p->caps.tn <= T4_MAXR * NT && p->caps.ta + 1 <= T4_MAXA * NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
+}
+
+sc_status launch_ttmc4_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out)
+{
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0) return SC_OK;
+    if (!ttmc4_mfma_caps_ok(p) || p->fcols[0] > 16 || p->fcols[1] != T4_M || p->fcols[2] != T4_N) return SC_ERR_SCHED_UNSUPPORTED;
+    // E and D rows are addressed with 31-bit byte offsets (bit 31 marks node ends), C rows with 32-bit ones
+    if ((uint64_t)fac[2].rows * (uint64_t)fac[2].ld * 4 >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
+    if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * 4 >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
+    if ((uint64_t)fac[0].rows * (uint64_t)fac[0].ld * 4 >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
+    Ttmc4Args a;
+    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1]; a.pos3 = sp->pos[2]; a.crd3 = sp->crd[2];
+    a.pos4 = sp->pos[3]; a.crd4 = sp->crd[3];
+    a.vals = static_cast<const float *>(sp->vals);
+    a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
+    a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;
+    a.E = static_cast<const float *>(fac[2].data); a.ldE = fac[2].ld;
+    a.A = static_cast<float *>(out);
+    a.L = (int32_t)p->fcols[0];
+    a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
+    // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
+    const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb);
+    const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
+    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : fit;
+    const int want = std::min(ntiles, 256 * per_cu);
+    a.ntiles = ntiles;
+    a.run = (ntiles + want - 1) / want;
+    const int blocks = (ntiles + a.run - 1) / a.run;
+    ln.begin("ttmc4_fused_mfma");
+    ttmc4_fused_mfma_kernel<<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    ln.end();
+    return ln.status;
+}
+
+}  // namespace sck

@@ -3,8 +3,8 @@
 // the producer of a split nest (Section 3.1) at the granularity of one work tile.
 //
 // LDS layout the caller provides:
-//   row_s    (ta + 1) rows of RS = W + 16 bytes (16-byte aligned, rows spread over banks);
-//            the extra row absorbs the writes of the padding records
+//   row_s    (ta + 1) rows of RS floats (leaf_row_stride: 16-byte aligned, wide rows padded so
+//            that they spread over banks); the extra row absorbs the writes of the padding records
 //   carry_s  one row of RS per lane group
 //   rec_s    padded(tn + 8) records {factor row byte offset | end-of-fiber bit 31, value}
 //   ba_s     ta + 2 ints: first nonzero (tile-local) of each fiber, ba_s[na] = nonzeros in tile
@@ -30,10 +30,12 @@ struct alignas(sizeof(T) == 4 ? 8 : 16) LeafRec {
     T v;
 };
 
+// Rows of 64 bytes or more are padded by 16 bytes, which spreads consecutive rows over the
+// LDS banks; narrower rows are packed.
 template <typename T>
 __host__ __device__ constexpr int leaf_row_stride(int W)
 {
-    return W + 16 / (int)sizeof(T);
+    return W + (W * (int)sizeof(T) >= 64 ? 16 / (int)sizeof(T) : 0);
 }
 
 // LDS bytes of row_s + carry_s + rec_s + ba_s + chunk_lr for a workgroup of `nthreads`.
