@@ -257,7 +257,8 @@ sc_status launch_ttmc3_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_v
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc3_lds_bytes(a.tn, a.ta, a.tb);
     const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
-    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : fit;
+    // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
+    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
     const int want = std::min(ntiles, 256 * per_cu);
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
