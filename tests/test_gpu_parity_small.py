@@ -34,3 +34,21 @@ def test_stream_copy_copies():
     sc.stream_copy(dst, src, n, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     assert torch.equal(dst, src)
+
+
+@pytest.mark.parametrize("per_cu", [1, 3, 64])
+@pytest.mark.parametrize("cid,scale", [(3, 0.003), (5, 0.004)])
+def test_parity_any_run_length(oracle, cid, scale, per_cu):
+    """The persistent fused kernels carry slice sums across the tiles of a run; the result must
+    not depend on how the tiles are cut into runs (long runs, and one tile per run)."""
+    sc.tuning_set("persistent_per_cu", per_cu)
+    sc.tuning_set("tile_leaves", 128)   # many tiles per slice
+    try:
+        cfg = synth.config(cid, scale)
+        data = synth.generate(cfg)
+        print(f"config {cid} scale {scale} fused, {per_cu} workgroups per CU", flush=True)
+        con, got = run_library(cfg, data, "fused")
+        assert_parity(oracle, cfg, data, got)
+    finally:
+        sc.tuning_set("persistent_per_cu", 0)
+        sc.tuning_set("tile_leaves", 0)

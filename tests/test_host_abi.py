@@ -237,8 +237,11 @@ def test_tuning_knobs_and_lds_limit():
         sc.tuning_set("tile_nodes_a", 1 << 14)   # T rows would not fit in LDS
         assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused")) == "SC_ERR_SCHED_UNSUPPORTED"
         assert _status(sc.tuning_set, "no_such_knob", 1) == "SC_ERR_EXPR_PARSE"
+        sc.tuning_set("persistent_per_cu", 2)
+        sc.tuning_set("tile_interleave", 8)
+        assert _status(sc.tuning_set, "persistent_per_cu", -1) == "SC_ERR_BAD_DIMS"
     finally:
-        for k in ("tile_leaves", "tile_nodes_a", "tile_nodes_b"):
+        for k in ("tile_leaves", "tile_nodes_a", "tile_nodes_b", "persistent_per_cu", "tile_interleave"):
             sc.tuning_set(k, 0)
 
 
