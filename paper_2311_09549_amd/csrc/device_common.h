@@ -172,10 +172,11 @@ size_t leaf_traverse_lds_bytes(const sc_plan *p, int W);
 sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
                                const sc_dense_view &F, void *Tout, int W, const char *name);
 
-// FUSED order-3 TTM chain on matrix cores (fp32, L = M = 16; its own kernel file).
+// Order-3 TTM chain on matrix cores (fp32, L = M = 16; its own kernel file): the FUSED schedule (T == nullptr)
+// or the consumer kernel of the FISSIONED one.
 size_t ttmc3_mfma_lds_bytes(const sc_plan *p);
 bool ttmc3_mfma_caps_ok(const sc_plan *p);
-sc_status launch_ttmc3_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out);
+sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out);
 
 // FUSED order-4 TTM chain on matrix cores (fp32, M = N = 8, L <= 16; its own kernel file).
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p);

@@ -598,7 +598,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.begin("mttkrp3_fused");
             mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
-            ln.status = launch_ttmc3_fused_mfma(p, ln, sp, fac, out);
+            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out);
             return ln.status;
         } else {
             ln.begin("ttmc3_fused_valu");
@@ -612,8 +612,8 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.begin("mttkrp3_consume");
             order3_kernel<T, W, 2, 0><<<ntiles, NT, lds, stream>>>(a);
         } else if (mfma) {
-            ln.begin("ttmc3_consume_mfma");
-            order3_kernel<T, W, 2, 2><<<ntiles, NT, lds, stream>>>(a);
+            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out);
+            return ln.status;
         } else {
             ln.begin("ttmc3_consume_valu");
             order3_kernel<T, W, 2, 1><<<ntiles, NT, lds, stream>>>(a);
@@ -663,7 +663,7 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.tn = 512;
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
-            if (sched == SC_SCHED_FUSED && dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
+            if (dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
                 // matrix-core kernel: measured best on the 30 M-nonzero workload (row tile + carry rows + records in ~40 KB)
                 c.tn = 768;
                 c.ta = 224;
@@ -680,9 +680,9 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 
 bool plan_wants_tensor_order(const sc_plan *p)
 {
-    if (p->sched != SC_SCHED_FUSED || p->dtype != SC_F32) return false;
+    if (p->dtype != SC_F32 || p->sched == SC_SCHED_LINEAR) return false;
     if (p->kind == K_TTMC3) return p->fcols[0] == 16 && p->fcols[1] == 16;
-    return p->kind == K_TTMC4;
+    return p->kind == K_TTMC4 && p->sched == SC_SCHED_FUSED;
 }
 
 size_t lds_bytes_needed(const sc_plan *p)
@@ -696,7 +696,11 @@ size_t lds_bytes_needed(const sc_plan *p)
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
         }
-        if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) return ttmc3_mfma_caps_ok(p) ? ttmc3_mfma_lds_bytes(p) : SIZE_MAX;
+        if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) {
+            if (!ttmc3_mfma_caps_ok(p)) return SIZE_MAX;
+            if (p->sched != SC_SCHED_FISSIONED) return ttmc3_mfma_lds_bytes(p);
+            return std::max(ttmc3_mfma_lds_bytes(p), leaf_traverse_lds_bytes(p, 16));
+        }
         {
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);

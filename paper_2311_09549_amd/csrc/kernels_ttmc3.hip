@@ -1,4 +1,6 @@
-// FUSED TTM chain of order 3 on matrix cores (Table 2, kernel 6 <SpTTM, TTM>), fp32, L = M = 16:
+// TTM chain of order 3 on matrix cores (Table 2, kernel 6 <SpTTM, TTM>), fp32, L = M = 16; the FUSED
+// schedule in one kernel and, with FUSED = false, the consumer half of the FISSIONED schedule (the
+// rows of T then come from the workspace instead of the leaf walk):
 //     T(f,:)   = sum_{k' in fiber f} B * D(k,:)              (producer, leaf traversal)
 //     A(i,:,:) += C(j,:)^T (x) T(f,:)   over the fibers of slice i   (consumer, rank-1 updates)
 // The temporary of the `where` nest lives in LDS for the fibers of one tile; the consumer is a
@@ -33,6 +35,7 @@ struct Ttmc3Args {
     const float *vals;
     const float *C, *D;
     int64_t ldC, ldD;
+    const float *T;   // FISSIONED consumer: the materialised temporary, one 16-wide row per fiber
     float *A;
     int32_t tn, ta, tb;
     int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
@@ -56,7 +59,8 @@ __host__ __device__ constexpr size_t ttmc3_lds_bytes(int tn, int ta, int tb)
 
 typedef float t3_floatx4 __attribute__((ext_vector_type(4)));
 
-__global__ void __launch_bounds__(NT) ttmc3_fused_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
+template <bool FUSED>
+__global__ void __launch_bounds__(NT) ttmc3_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
 {
     constexpr int U = 8;
     constexpr int RS = T3_RS;
@@ -88,40 +92,64 @@ __global__ void __launch_bounds__(NT) ttmc3_fused_mfma_kernel(Ttmc3Args a, const
 
     // ---- stage 1 ----
     {
+        constexpr int TR = (NT + T3_G - 1) / T3_G;   // T rows copied per lane group: ta <= TR * G
         uint32_t kk[T3_MAXR];
         float vv[T3_MAXR];
         int pb[T3_MAXB];
+        Pack<float, 4> trow[TR];
+        if (FUSED) {
 #pragma unroll
-        for (int r = 0; r < T3_MAXR; ++r) {
-            const int c = t.n0 + min(tid + r * NT, nchild - 1);
-            kk[r] = (uint32_t)a.crd3[c];
-            vv[r] = a.vals[c];
+            for (int r = 0; r < T3_MAXR; ++r) {
+                const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                kk[r] = (uint32_t)a.crd3[c];
+                vv[r] = a.vals[c];
+            }
+#pragma unroll
+            for (int r = 0; r < T3_MAXB; ++r) pb[r] = a.pos3[t.a0 + min(tid + r * NT, na)];
+        } else {
+#pragma unroll
+            for (int r = 0; r < TR; ++r) {
+                const int f = min(tid / T3_LG + r * T3_G, na - 1);
+                trow[r] = *reinterpret_cast<const Pack<float, 4> *>(a.T + (int64_t)(t.a0 + f) * T3_W + (tid % T3_LG) * 4);
+            }
         }
-#pragma unroll
-        for (int r = 0; r < T3_MAXB; ++r) pb[r] = a.pos3[t.a0 + min(tid + r * NT, na)];
         const int cj = a.crd2[t.a0 + min(tid, na - 1)];
         const int ps = a.pos2[t.b0 + min(tid, nb)];
         const int ci = a.crd1[t.b0 + min(tid, nb - 1)];
+        if (FUSED) {
 #pragma unroll
-        for (int r = 0; r < T3_MAXR; ++r) {
-            const int c = tid + r * NT;
-            if (c < nchild) {
-                Ttmc3Rec rec;
-                rec.koff = kk[r] * rowD;
-                rec.v = vv[r];
-                rec_s[pidx(c)] = rec;
+            for (int r = 0; r < T3_MAXR; ++r) {
+                const int c = tid + r * NT;
+                if (c < nchild) {
+                    Ttmc3Rec rec;
+                    rec.koff = kk[r] * rowD;
+                    rec.v = vv[r];
+                    rec_s[pidx(c)] = rec;
+                }
             }
-        }
-        if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
-            Ttmc3Rec rec;
-            rec.koff = 0;
-            rec.v = 0.f;
-            rec_s[pidx(nchild + tid)] = rec;
-        }
+            if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
+                Ttmc3Rec rec;
+                rec.koff = 0;
+                rec.v = 0.f;
+                rec_s[pidx(nchild + tid)] = rec;
+            }
 #pragma unroll
-        for (int r = 0; r < T3_MAXB; ++r) {
-            const int i = tid + r * NT;
-            if (i <= na) ba_s[i] = min(max(pb[r], t.n0), t.n1) - t.n0;
+            for (int r = 0; r < T3_MAXB; ++r) {
+                const int i = tid + r * NT;
+                if (i <= na) ba_s[i] = min(max(pb[r], t.n0), t.n1) - t.n0;
+            }
+        } else {
+            // A fiber cut by a tile boundary has one complete row in the workspace; the tile in
+            // which it starts consumes it, the tiles it continues into see a zero row.
+#pragma unroll
+            for (int r = 0; r < TR; ++r) {
+                const int f = tid / T3_LG + r * T3_G;
+                if (f < na) {
+                    Pack<float, 4> v = trow[r];
+                    if (f == 0 && (t.flags & 1)) v = Pack<float, 4>{{0.f, 0.f, 0.f, 0.f}};
+                    *reinterpret_cast<Pack<float, 4> *>(row_s + f * RS + (tid % T3_LG) * 4) = v;
+                }
+            }
         }
         if (tid < na) coff_s[tid] = (uint32_t)cj * rowC;
         if (tid <= nb) bb_s[tid] = min(max(ps, t.a0), t.a0 + na) - t.a0;
@@ -130,9 +158,9 @@ __global__ void __launch_bounds__(NT) ttmc3_fused_mfma_kernel(Ttmc3Args a, const
     __syncthreads();
 
     // ---- stage 2, walk (leaves -> T rows in LDS), combine ----
-    leaf_mark(rec_s, ba_s, chunk_lr, tid, NT, na, q);
-    __syncthreads();
-    {
+    if (FUSED) {
+        leaf_mark(rec_s, ba_s, chunk_lr, tid, NT, na, q);
+        __syncthreads();
         const int g = tid / T3_LG, li = tid % T3_LG;
         const LeafCarry st = leaf_walk<float, T3_W, U>(row_s, carry_s, rec_s, ba_s, chunk_lr, a.D, g, li, q, nchild);
         __syncthreads();
@@ -239,8 +267,9 @@ bool ttmc3_mfma_caps_ok(const sc_plan *p)
     return p->caps.tn <= T3_MAXR * NT && p->caps.ta + 1 <= T3_MAXB * NT && p->caps.ta <= NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
 }
 
-sc_status launch_ttmc3_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out)
+sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out)
 {
+    // T == nullptr: FUSED schedule; otherwise the consumer kernel of the FISSIONED schedule
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return SC_OK;
     if (!ttmc3_mfma_caps_ok(p)) return SC_ERR_SCHED_UNSUPPORTED;
@@ -252,6 +281,7 @@ sc_status launch_ttmc3_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_v
     a.vals = static_cast<const float *>(sp->vals);
     a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
     a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;
+    a.T = static_cast<const float *>(T);
     a.A = static_cast<float *>(out);
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
@@ -263,8 +293,13 @@ sc_status launch_ttmc3_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_v
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
     const int blocks = (ntiles + a.run - 1) / a.run;
-    ln.begin("ttmc3_fused_mfma");
-    ttmc3_fused_mfma_kernel<<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    if (T == nullptr) {
+        ln.begin("ttmc3_fused_mfma");
+        ttmc3_mfma_kernel<true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    } else {
+        ln.begin("ttmc3_consume_mfma");
+        ttmc3_mfma_kernel<false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    }
     ln.end();
     return ln.status;
 }
