@@ -682,7 +682,7 @@ bool plan_wants_tensor_order(const sc_plan *p)
 {
     if (p->dtype != SC_F32 || p->sched == SC_SCHED_LINEAR) return false;
     if (p->kind == K_TTMC3) return p->fcols[0] == 16 && p->fcols[1] == 16;
-    return p->kind == K_TTMC4 && p->sched == SC_SCHED_FUSED;
+    return p->kind == K_TTMC4;
 }
 
 size_t lds_bytes_needed(const sc_plan *p)

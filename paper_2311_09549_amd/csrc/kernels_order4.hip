@@ -350,7 +350,7 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
-            ln.status = launch_ttmc4_fused_mfma(p, ln, sp, fac, out);   // dedicated matrix-core kernel
+            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 0, nullptr, nullptr, out);   // dedicated matrix-core kernel
             return ln.status;
         } else {
             ln.begin("ttmc4_fused_valu");
@@ -363,6 +363,12 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         ln.begin("zero_shared_rows_t2");
         zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 1, static_cast<T *>(a.T2), M * N);
         ln.end();
+        if (mfma) {
+            st = launch_ttmc4_mfma(p, ln, sp, fac, 1, a.T1, a.T2, out);
+            if (st != SC_OK) return st;
+            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 2, a.T1, a.T2, out);
+            return ln.status;
+        }
         ln.begin("ttmc4_middle");
         order4_kernel<T, N, M, 2, 1><<<ntiles, NT, lds, stream>>>(a);
         ln.end();
@@ -398,7 +404,11 @@ size_t order4_lds_bytes_needed(const sc_plan *p)
     const int N = (int)p->fcols[2], W2 = (int)(p->fcols[1] * p->fcols[2]), L = (int)p->fcols[0];
     const size_t own = p->dtype == SC_F64 ? order4_lds_bytes<double>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb)
                                           : order4_lds_bytes<float>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb);
-    if (p->sched == SC_SCHED_FUSED && p->dtype == SC_F32) return ttmc4_mfma_caps_ok(p) ? ttmc4_mfma_lds_bytes(p) : SIZE_MAX;
+    if (p->dtype == SC_F32 && p->fcols[0] <= 16) {
+        if (!ttmc4_mfma_caps_ok(p)) return SIZE_MAX;
+        if (p->sched != SC_SCHED_FISSIONED) return ttmc4_mfma_lds_bytes(p);
+        return std::max(ttmc4_mfma_lds_bytes(p), leaf_traverse_lds_bytes(p, N));
+    }
     if (p->sched != SC_SCHED_FISSIONED) return own;
     return std::max(own, leaf_traverse_lds_bytes(p, N));  // the leaf traversal is the first FISSIONED kernel
 }

@@ -1,4 +1,6 @@
-// FUSED order-4 TTM chain on matrix cores, fp32, M = N = 8, L <= 16:
+// Order-4 TTM chain on matrix cores, fp32, M = N = 8, L <= 16; MODE 0 is the FUSED schedule in one
+// kernel, MODE 1 and 2 are the second and third kernel of the FISSIONED schedule (T1 rows read from
+// the workspace and T2 rows written to it; T2 rows read from the workspace):
 //     A(i,l,m,n) = sum_{j,k,p} B(i,j,k,p) * C(j,l) * D(k,m) * E(p,n)
 // under the two-level nest obtained by applying the split-and-fuse step of Section 4.2 twice
 // (the shape of the second schedule of Table 2, kernel 5):
@@ -29,6 +31,8 @@ struct Ttmc4Args {
     const float *vals;
     const float *C, *D, *E;
     int64_t ldC, ldD, ldE;
+    const float *T1;   // MODE 1: materialised T1, one 8-wide row per f3 fiber
+    float *T2;         // MODE 1 writes, MODE 2 reads: one 64-wide row per f2 fiber
     float *A;
     int32_t L;
     int32_t tn, ta, tb;
@@ -43,6 +47,8 @@ constexpr int T4_LG2 = T4_W2 / 4;          // lanes per T2 row
 constexpr int T4_G2 = NT / T4_LG2;         // lane groups of the middle walk
 constexpr int T4_MAXR = 3;                 // tn <= T4_MAXR * NT
 constexpr int T4_MAXA = 2;                 // ta + 1 <= T4_MAXA * NT, tb + 1 <= NT
+constexpr int T4_TR1 = 3;                  // MODE 1: T1 rows copied per 2-lane group, ta <= T4_TR1 * G1
+constexpr int T4_TR2 = 5;                  // MODE 2: T2 rows copied per 16-lane group, tb <= T4_TR2 * G2
 static_assert(NT / 64 == T4_W2 / 16, "one wavefront per 16 columns of a T2 row");
 
 __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb)
@@ -53,7 +59,8 @@ __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb)
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
 
-__global__ void __launch_bounds__(NT) ttmc4_fused_mfma_kernel(Ttmc4Args a, const TileRec *__restrict__ tiles)
+template <int MODE>
+__global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileRec *__restrict__ tiles)
 {
     using P = Pack<float, 4>;
     using Rec = LeafRec<float>;
@@ -100,63 +107,120 @@ __global__ void __launch_bounds__(NT) ttmc4_fused_mfma_kernel(Ttmc4Args a, const
             uint32_t pp[T4_MAXR];
             float vv[T4_MAXR];
             int p4[T4_MAXA], k3[T4_MAXA];
+            int p3 = 0, j2 = 0, p2 = 0, i1 = 0;
+            P t1row[T4_TR1], t2row[T4_TR2];
+            if (MODE == 0) {
 #pragma unroll
-            for (int r = 0; r < T4_MAXR; ++r) {
-                const int c = t.n0 + min(tid + r * NT, nchild - 1);
-                pp[r] = (uint32_t)a.crd4[c];
-                vv[r] = a.vals[c];
+                for (int r = 0; r < T4_MAXR; ++r) {
+                    const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                    pp[r] = (uint32_t)a.crd4[c];
+                    vv[r] = a.vals[c];
+                }
+#pragma unroll
+                for (int r = 0; r < T4_MAXA; ++r) p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
             }
+            if (MODE != 2) {
 #pragma unroll
-            for (int r = 0; r < T4_MAXA; ++r) {
-                p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
-                k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
+                for (int r = 0; r < T4_MAXA; ++r) k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
+                p3 = a.pos3[t.b0 + min(tid, nb)];
             }
-            const int p3 = a.pos3[t.b0 + min(tid, nb)];
-            const int j2 = a.crd2[t.b0 + min(tid, nb - 1)];
-            const int p2 = a.pos2[t.c0 + min(tid, nc)];
-            const int i1 = a.crd1[t.c0 + min(tid, nc - 1)];
+            if (MODE != 1) {
+                j2 = a.crd2[t.b0 + min(tid, nb - 1)];
+                p2 = a.pos2[t.c0 + min(tid, nc)];
+                i1 = a.crd1[t.c0 + min(tid, nc - 1)];
+            }
+            if (MODE == 1) {
 #pragma unroll
-            for (int r = 0; r < T4_MAXR; ++r) {
-                const int c = tid + r * NT;
-                if (c < nchild) {
-                    Rec rec;
-                    rec.koff = pp[r] * rowE;
-                    rec.v = vv[r];
-                    rec_s[pidx(c)] = rec;
+                for (int r = 0; r < T4_TR1; ++r) {
+                    const int f = min(tid / 2 + r * T4_G1, na - 1);
+                    t1row[r] = *reinterpret_cast<const P *>(a.T1 + (int64_t)(t.a0 + f) * T4_N + (tid % 2) * 4);
                 }
             }
-            if (tid < U1) {  // dummies completing the last batch of the leaf walk
-                Rec rec;
-                rec.koff = 0;
-                rec.v = 0.f;
-                rec_s[pidx(nchild + tid)] = rec;
-            }
+            if (MODE == 2) {
 #pragma unroll
-            for (int r = 0; r < T4_MAXA; ++r) {
-                const int i = tid + r * NT;
-                if (i <= na) ba_s[i] = min(max(p4[r], t.n0), t.n1) - t.n0;
-                if (i < na) krec_s[i] = (uint32_t)k3[r] * rowD;
+                for (int r = 0; r < T4_TR2; ++r) {
+                    const int f = min(tid / T4_LG2 + r * T4_G2, nb - 1);
+                    t2row[r] = *reinterpret_cast<const P *>(a.T2 + (int64_t)(t.b0 + f) * T4_W2 + (tid % T4_LG2) * 4);
+                }
             }
-            if (tid < U2) krec_s[na + tid] = 0;   // dummies of the middle walk
-            if (tid <= nb) bb_s[tid] = min(max(p3, t.a0), t.a0 + na) - t.a0;
-            if (tid < nb) coff2_s[tid] = (uint32_t)j2 * rowC;
-            if (tid <= nc) bc_s[tid] = min(max(p2, t.b0), t.b0 + nb) - t.b0;
-            if (tid < nc) crdc_s[tid] = i1;
+            if (MODE == 0) {
+#pragma unroll
+                for (int r = 0; r < T4_MAXR; ++r) {
+                    const int c = tid + r * NT;
+                    if (c < nchild) {
+                        Rec rec;
+                        rec.koff = pp[r] * rowE;
+                        rec.v = vv[r];
+                        rec_s[pidx(c)] = rec;
+                    }
+                }
+                if (tid < U1) {  // dummies completing the last batch of the leaf walk
+                    Rec rec;
+                    rec.koff = 0;
+                    rec.v = 0.f;
+                    rec_s[pidx(nchild + tid)] = rec;
+                }
+#pragma unroll
+                for (int r = 0; r < T4_MAXA; ++r) {
+                    const int i = tid + r * NT;
+                    if (i <= na) ba_s[i] = min(max(p4[r], t.n0), t.n1) - t.n0;
+                }
+            }
+            // A node cut by a tile boundary has one complete row in the workspace; the tile in
+            // which it starts consumes it, the tiles it continues into see a zero row.
+            if (MODE == 1) {
+#pragma unroll
+                for (int r = 0; r < T4_TR1; ++r) {
+                    const int f = tid / 2 + r * T4_G1;
+                    if (f < na) {
+                        P v = t1row[r];
+                        if (f == 0 && (t.flags & 1)) v = P{{0.f, 0.f, 0.f, 0.f}};
+                        *reinterpret_cast<P *>(row1_s + f * RS1 + (tid % 2) * 4) = v;
+                    }
+                }
+            }
+            if (MODE == 2) {
+#pragma unroll
+                for (int r = 0; r < T4_TR2; ++r) {
+                    const int f = tid / T4_LG2 + r * T4_G2;
+                    if (f < nb) {
+                        P v = t2row[r];
+                        if (f == 0 && (t.flags & 4)) v = P{{0.f, 0.f, 0.f, 0.f}};
+                        *reinterpret_cast<P *>(row2_s + f * RS2 + (tid % T4_LG2) * 4) = v;
+                    }
+                }
+            }
+            if (MODE != 2) {
+#pragma unroll
+                for (int r = 0; r < T4_MAXA; ++r) {
+                    const int i = tid + r * NT;
+                    if (i < na) krec_s[i] = (uint32_t)k3[r] * rowD;
+                }
+                if (tid < U2) krec_s[na + tid] = 0;   // dummies of the middle walk
+                if (tid <= nb) bb_s[tid] = min(max(p3, t.a0), t.a0 + na) - t.a0;
+            }
+            if (MODE != 1) {
+                if (tid < nb) coff2_s[tid] = (uint32_t)j2 * rowC;
+                if (tid <= nc) bc_s[tid] = min(max(p2, t.b0), t.b0 + nb) - t.b0;
+                if (tid < nc) crdc_s[tid] = i1;
+            }
         }
         __syncthreads();
 
         // ---- marks of both walks ----
-        leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
-        for (int i = tid; i < nb; i += NT) {
-            const int lo = bb_s[i], hi = bb_s[i + 1];
-            if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
-            krec_s[hi - 1] |= 0x80000000u;
-            for (int m = (lo + q2 - 1) / q2; m * q2 < hi; ++m) chunk_lr2[m] = i;
+        if (MODE == 0) leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
+        if (MODE != 2) {
+            for (int i = tid; i < nb; i += NT) {
+                const int lo = bb_s[i], hi = bb_s[i + 1];
+                if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
+                krec_s[hi - 1] |= 0x80000000u;
+                for (int m = (lo + q2 - 1) / q2; m * q2 < hi; ++m) chunk_lr2[m] = i;
+            }
+            __syncthreads();
         }
-        __syncthreads();
 
         // ---- leaves -> T1 rows ----
-        {
+        if (MODE == 0) {
             const int g = tid / 2, li = tid % 2;
             const LeafCarry st = leaf_walk<float, T4_N, U1>(row1_s, carry1_s, rec_s, ba_s, chunk_lr1, a.E, g, li, q1, nchild);
             __syncthreads();
@@ -165,7 +229,7 @@ __global__ void __launch_bounds__(NT) ttmc4_fused_mfma_kernel(Ttmc4Args a, const
         }
 
         // ---- f3 fibers -> T2 rows: T2(f2, m, :) += D(k, m) * T1(f3, :) ----
-        {
+        if (MODE != 2) {
             const int g = tid / T4_LG2, li = tid % T4_LG2;
             const int m = li / 2, nq = (li % 2) * 4;
             const char *Db = reinterpret_cast<const char *>(a.D) + m * 4;
@@ -212,8 +276,26 @@ __global__ void __launch_bounds__(NT) ttmc4_fused_mfma_kernel(Ttmc4Args a, const
             __syncthreads();
         }
 
+        if (MODE == 1) {
+            // write the tile's T2 rows; rows shared with a neighbouring tile are added atomically to
+            // pre-zeroed memory
+            const int g = tid / T4_LG2, li = tid % T4_LG2;
+            float *Tg = a.T2 + (int64_t)t.b0 * T4_W2;
+            for (int r = g; r < nb; r += T4_G2) {
+                const P row = *reinterpret_cast<const P *>(row2_s + r * RS2 + li * 4);
+                float *dst = Tg + (int64_t)r * T4_W2 + li * 4;
+                const bool shared = (r == 0 && (t.flags & 4)) || (r == nb - 1 && (t.flags & 8));
+                if (!shared) {
+                    *reinterpret_cast<P *>(dst) = row;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) atomic_add(dst + i, row.v[i]);
+                }
+            }
+        }
+
         // ---- consume: T2 rows x gathered C rows -> A ----
-        {
+        if (MODE != 1) {
             const bool lval = col < L;
             const char *Cb = reinterpret_cast<const char *>(a.C) + min(col, L - 1) * 4;
             const bool last_tile = tile + 1 == lastp1;
@@ -266,11 +348,14 @@ size_t ttmc4_mfma_lds_bytes(const sc_plan *p) { return ttmc4_lds_bytes(p->caps.t
 
 bool ttmc4_mfma_caps_ok(const sc_plan *p)
 {
-    return p->caps.tn <= T4_MAXR * NT && p->caps.ta + 1 <= T4_MAXA * NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
+    return p->caps.tn <= T4_MAXR * NT && p->caps.ta + 1 <= T4_MAXA * NT && p->caps.ta <= T4_TR1 * T4_G1 && p->caps.tb <= T4_TR2 * T4_G2 &&
+           p->caps.tb >= 1;
 }
 
-sc_status launch_ttmc4_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out)
+sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
+                            void *T2, void *out)
 {
+    // mode 0: FUSED schedule; 1: T1 -> T2 and 2: T2 -> A of the FISSIONED schedule
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return SC_OK;
     if (!ttmc4_mfma_caps_ok(p) || p->fcols[0] > 16 || p->fcols[1] != T4_M || p->fcols[2] != T4_N) return SC_ERR_SCHED_UNSUPPORTED;
@@ -285,6 +370,8 @@ sc_status launch_ttmc4_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_v
     a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
     a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;
     a.E = static_cast<const float *>(fac[2].data); a.ldE = fac[2].ld;
+    a.T1 = static_cast<const float *>(T1);
+    a.T2 = static_cast<float *>(T2);
     a.A = static_cast<float *>(out);
     a.L = (int32_t)p->fcols[0];
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
@@ -297,8 +384,16 @@ sc_status launch_ttmc4_fused_mfma(const sc_plan *p, Launcher &ln, const sc_csf_v
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
     const int blocks = (ntiles + a.run - 1) / a.run;
-    ln.begin("ttmc4_fused_mfma");
-    ttmc4_fused_mfma_kernel<<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    if (mode == 0) {
+        ln.begin("ttmc4_fused_mfma");
+        ttmc4_mfma_kernel<0><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    } else if (mode == 1) {
+        ln.begin("ttmc4_middle");
+        ttmc4_mfma_kernel<1><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    } else {
+        ln.begin("ttmc4_consume_mfma");
+        ttmc4_mfma_kernel<2><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+    }
     ln.end();
     return ln.status;
 }
