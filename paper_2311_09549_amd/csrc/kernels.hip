@@ -557,6 +557,165 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 }
 
 // ------------------------------------------------------------------------------------------
+// MTTKRP, FISSIONED, second kernel: A(i, r) = sum_{fibers f of slice i} C(j_f, r) * T(f, r) with T
+// read back from the workspace (the consumer of the split nest, Section 3.1).  The same walk
+// as the fused kernel one level up: the children are the tile's fibers (their T rows are
+// contiguous in memory, 16 bytes per lane), the parents its slices.  One 8-byte LDS record
+// per fiber {C row offset, slice id at slice end}; slice pieces cut by chunk boundaries are
+// parked and summed by the group where the slice ends.  A fiber that continues from the
+// previous tile belongs to the tile it starts in and is skipped here.
+// ------------------------------------------------------------------------------------------
+struct FibRec {
+    uint32_t coff;
+    int32_t s;
+};
+
+template <typename T>
+__host__ __device__ constexpr size_t hadamard_lds_bytes(int ta, int tb)
+{
+    return (size_t)NT * 16 + (size_t)padded(ta + 8) * sizeof(FibRec) + (size_t)(2 * tb + 2 * (NT / 2)) * 4 + 64;
+}
+
+template <typename T, int W>
+__global__ void __launch_bounds__(NT) hadamard_consume_kernel(Order3Args a)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int LG = W / VEC;
+    constexpr int G = NT / LG;
+    constexpr int GMAX = NT / 2;
+    constexpr int U = 4;
+    static_assert(G <= GMAX, "lane group count");
+    using P = Pack<T, VEC>;
+    using Acc = AccVec<T, VEC>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T *slot_s = reinterpret_cast<T *>(smem);                                   // NT * VEC: one parked row per lane group
+    FibRec *rec_s = reinterpret_cast<FibRec *>(slot_s + NT * VEC);             // padded(ta + 8)
+    int *slo_s = reinterpret_cast<int *>(rec_s + padded(a.ta + 8));            // tb: first fiber of each slice
+    int *crdb_s = slo_s + a.tb;                                                // tb: output row of each slice
+    int *chunk_ls = crdb_s + a.tb;                                             // GMAX
+    int *slot_id = chunk_ls + GMAX;                                            // GMAX
+
+    const TileRec t = a.tiles[blockIdx.x];
+    const int tid = threadIdx.x;
+    const int cf0 = (t.flags & 1) ? 1 : 0;
+    const int na = t.na, nb = t.nb;
+    const int nfib = na - cf0;                    // fibers this tile consumes; may be 0
+    const int q = max(((nfib + G - 1) / G + U - 1) / U * U, U);
+    const uint32_t rowC = (uint32_t)(a.ldC * sizeof(T));
+
+    // ---- stage: every global read before the first use ----
+    {
+        constexpr int MAXF = 2;   // ta <= MAXF * NT
+        int cj[MAXF];
+#pragma unroll
+        for (int r = 0; r < MAXF; ++r) cj[r] = a.crd2[t.a0 + min(cf0 + tid + r * NT, na - 1)];
+        const int sb = t.b0 + min(tid, nb - 1);
+        const int p_lo = a.pos2[sb], p_hi = a.pos2[sb + 1], ci = a.crd1[sb];
+#pragma unroll
+        for (int r = 0; r < MAXF; ++r) {
+            const int f = tid + r * NT;
+            if (f < nfib + U) {   // the records past the last fiber complete the last batch: row 0 of C, no mark
+                FibRec rec;
+                rec.coff = f < nfib ? (uint32_t)cj[r] * rowC : 0u;
+                rec.s = -1;
+                rec_s[pidx(f)] = rec;
+            }
+        }
+        if (tid < GMAX) {
+            slot_id[tid] = -1;
+            chunk_ls[tid] = -1;
+        }
+        int s_lo = 0, s_hi = 0;
+        if (tid < nb) {
+            s_lo = max(min(max(p_lo, t.a0), t.a0 + na) - t.a0, cf0) - cf0;
+            s_hi = max(min(max(p_hi, t.a0), t.a0 + na) - t.a0, cf0) - cf0;
+            slo_s[tid] = s_lo;
+            crdb_s[tid] = ci;
+        }
+        __syncthreads();
+        if (s_hi > s_lo) {
+            rec_s[pidx(s_hi - 1)].s = tid;
+            for (int m = s_lo / q + 1; m * q < s_hi; ++m) chunk_ls[m - 1] = tid;
+        }
+    }
+    __syncthreads();
+
+    const int g = tid / LG, li = tid % LG;
+    const char *Cb = static_cast<const char *>(a.C);
+    const uint32_t lo = (uint32_t)li * 16u;
+    const T *Tg = static_cast<const T *>(a.T) + (int64_t)(t.a0 + cf0) * W + li * VEC;
+    T *A = static_cast<T *>(a.A);
+    auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
+    auto direct = [&](int ls, const P &row) {
+        T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
+        if (!slice_shared(ls)) {
+            *reinterpret_cast<P *>(dst) = row;
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+        }
+    };
+
+    const int gs = g * q, ge = min(gs + q, nfib);
+    int head_ls = -1;
+    P headv;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) headv.v[i] = T(0);
+    if (gs < ge) {
+        bool started = (gs == 0) || (rec_s[pidx(gs - 1)].s >= 0);   // the current slice starts in this chunk
+        Acc asum;
+        asum.clear();
+        for (int c = gs; c < ge; c += U) {
+            FibRec r[U];
+            P tt[U], cc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                tt[u] = *reinterpret_cast<const P *>(Tg + (int64_t)min(c + u, nfib - 1) * W);   // clamped: rows past the tile are never used
+                cc[u] = *reinterpret_cast<const P *>(Cb + (r[u].coff + lo));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) asum.v[i] += tt[u].v[i] * cc[u].v[i];
+                if (r[u].s >= 0) {
+                    P o;
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+                    if (started) {
+                        direct(r[u].s, o);
+                    } else {
+                        headv = o;
+                        head_ls = r[u].s;
+                    }
+                    asum.clear();
+                    started = true;
+                }
+            }
+        }
+        if (chunk_ls[g] >= 0) {   // the chunk ends inside a slice: park the tail
+            P o;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            *reinterpret_cast<P *>(slot_s + g * W + li * VEC) = o;
+            if (li == 0) slot_id[g] = started ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    if (head_ls >= 0) {
+        for (int h = g - 1; h >= 0; --h) {
+            const P tl = *reinterpret_cast<const P *>(slot_s + h * W + li * VEC);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) headv.v[i] += tl.v[i];
+            if (slot_id[h] != 0) break;   // the slice began in chunk h
+        }
+        direct(head_ls, headv);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // host side: caps, LDS sizing, dispatch
 // ------------------------------------------------------------------------------------------
 namespace {
@@ -609,8 +768,9 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         const sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse");
         if (st != SC_OK) return st;
         if (had) {
+            if (a.ta > 2 * NT - 4 || a.tb > NT) return SC_ERR_SCHED_UNSUPPORTED;   // staging registers of the consumer
             ln.begin("mttkrp3_consume");
-            order3_kernel<T, W, 2, 0><<<ntiles, NT, lds, stream>>>(a);
+            hadamard_consume_kernel<T, W><<<ntiles, NT, hadamard_lds_bytes<T>(a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
             ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out);
             return ln.status;
