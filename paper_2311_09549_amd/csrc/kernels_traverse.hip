@@ -24,6 +24,15 @@ namespace sck {
 
 constexpr int LNT = 256;  // threads per workgroup of the traversal kernel
 
+// 16-byte store with the non-temporal hint: rows of T are written once and not read by this kernel.
+typedef unsigned int leaf_u32x4 __attribute__((ext_vector_type(4)));
+template <typename T, typename PK>
+__device__ __forceinline__ void nt_store16(T *dst, const PK &v)
+{
+    static_assert(sizeof(PK) == 16, "pack size");
+    __builtin_nontemporal_store(__builtin_bit_cast(leaf_u32x4, v), reinterpret_cast<leaf_u32x4 *>(dst));
+}
+
 struct LeafArgs {
     const int32_t *pos, *crd;
     const void *vals;
@@ -161,7 +170,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
             T *dst = Tout + (int64_t)r * W + li * VEC;
             const bool shared = (r == 0 && (t.flags & 1)) || (r == na - 1 && (t.flags & 2));
             if (!shared) {
-                *reinterpret_cast<P *>(dst) = row;
+                nt_store16(dst, row);
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);

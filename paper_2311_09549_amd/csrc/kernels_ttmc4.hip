@@ -286,7 +286,8 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                 float *dst = Tg + (int64_t)r * T4_W2 + li * 4;
                 const bool shared = (r == 0 && (t.flags & 4)) || (r == nb - 1 && (t.flags & 8));
                 if (!shared) {
-                    *reinterpret_cast<P *>(dst) = row;
+                    // written once, read by the next kernel only: non-temporal
+                    __builtin_nontemporal_store(__builtin_bit_cast(t4_floatx4, row), reinterpret_cast<t4_floatx4 *>(dst));
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) atomic_add(dst + i, row.v[i]);
