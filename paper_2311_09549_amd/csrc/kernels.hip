@@ -815,8 +815,9 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.tb = 128;
         } else if (kind == K_MTTKRP3) {
             // keep the T rows of a tile within 32 KB of LDS
-            c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(1024, (32 * 1024) / (w * e)));
-            c.tb = c.ta;
+            // (at most 508 fibers: the traversal and consumer kernels stage two or three per thread)
+            c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(508, (32 * 1024) / (w * e)));
+            c.tb = std::min(c.ta, NT);   // the consumer stages one slice per thread
         } else {
             // smaller tiles (T rows within 16 KB) let more workgroups share a CU, which measured
             // faster than larger tiles for the outer-product consumer
@@ -865,6 +866,8 @@ size_t lds_bytes_needed(const sc_plan *p)
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
             if (p->sched != SC_SCHED_FISSIONED) return own;
+            // the Hadamard consumer stages two fibers and one slice per thread
+            if (p->kind == K_MTTKRP3 && (p->caps.ta > 2 * NT - 4 || p->caps.tb > NT)) return SIZE_MAX;
             return std::max(own, leaf_traverse_lds_bytes(p, (int)producer_width(p)));  // first FISSIONED kernel
         }
     case K_SDDMM_SPMM: return order2_lds_bytes_needed(p);

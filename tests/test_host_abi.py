@@ -272,3 +272,20 @@ def test_stream_copy_argument_checks():
     assert lib.sc_stream_copy(ctypes.c_void_p(p + 16), ctypes.c_void_p(p), ctypes.c_size_t(12), None) == sc.STATUS_NAMES.index("SC_ERR_BAD_DIMS")
     assert lib.sc_stream_copy(ctypes.c_void_p(p + 17), ctypes.c_void_p(p), ctypes.c_size_t(16), None) == sc.STATUS_NAMES.index("SC_ERR_BAD_DIMS")
     assert lib.sc_stream_copy(ctypes.c_void_p(p + 16), ctypes.c_void_p(p), ctypes.c_size_t(0), None) == 0
+
+
+@pytest.mark.parametrize("which", ["fused", "fissioned"])
+@pytest.mark.parametrize("cid,dtype,ranks", [
+    (2, "f32", (8,)), (2, "f32", (16,)), (2, "f32", (32,)), (2, "f32", (64,)), (2, "f64", (8,)), (2, "f64", (64,)),
+    (3, "f32", (8, 16)), (3, "f32", (16, 16)), (3, "f32", (16, 64)), (3, "f64", (16, 16)),
+    (4, "f32", (16, 16)), (4, "f32", (128, 128)), (4, "f64", (64, 64)),
+    (5, "f32", (4, 8, 8)), (5, "f32", (16, 8, 8)), (5, "f64", (8, 8, 8))])
+def test_built_in_tile_caps_fit_every_supported_rank(cid, dtype, ranks, which):
+    """The built-in tile caps must satisfy the LDS and staging limits of every kernel a plan
+    launches, for every rank / dtype combination the library accepts."""
+    cfg = synth.config(cid, 0.002)
+    cfg["dtype"], cfg["ranks"] = dtype, ranks
+    data = synth.generate(cfg)
+    csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule(which))
+    assert sc.plan_tile_count(plan) > 0
