@@ -357,10 +357,13 @@ struct alignas(sizeof(T) == 4 ? 16 : 8) NzRec {
     T v;
 };
 
+// W = rank; a lane group is W / (16 / sizeof(T)) lanes, and there is one parked row and one
+// entry of each chunk table per lane group.
 template <typename T>
-__host__ __device__ constexpr size_t mttkrp_lds_bytes(int tn, int ta, int tb)
+__host__ __device__ constexpr size_t mttkrp_lds_bytes(int W, int tn, int ta, int tb)
 {
-    return (size_t)NT * 16 + (size_t)padded(tn + 8) * sizeof(NzRec<T>) + (size_t)(2 * tb + 3 * NT) * 4 + 64;
+    const int groups = NT / (W / (16 / (int)sizeof(T)));
+    return (size_t)NT * 16 + (size_t)padded(tn + 8) * sizeof(NzRec<T>) + (size_t)(2 * tb + 3 * groups) * 4 + 64;
 }
 
 template <typename T, int W>
@@ -378,9 +381,9 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
     Rec *rec_s = reinterpret_cast<Rec *>(slot_s + NT * VEC);       // tn
     int *slo_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // tb: first nonzero of each slice
     int *crdb_s = slo_s + a.tb;                                    // tb: output row of each slice
-    int *chunk_coff = crdb_s + a.tb;                               // NT (G used)
-    int *chunk_ls = chunk_coff + NT;                               // NT (G used)
-    int *slot_id = chunk_ls + NT;                                  // NT (G used)
+    int *chunk_coff = crdb_s + a.tb;                               // G
+    int *chunk_ls = chunk_coff + G;                                // G
+    int *slot_id = chunk_ls + G;                                   // G
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
@@ -413,9 +416,11 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 #pragma unroll
         for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
         reinterpret_cast<P *>(slot_s)[tid] = z;
-        slot_id[tid] = -1;
-        chunk_coff[tid] = -1;
-        chunk_ls[tid] = -1;
+        if (tid < G) {
+            slot_id[tid] = -1;
+            chunk_coff[tid] = -1;
+            chunk_ls[tid] = -1;
+        }
     }
     constexpr int MAXF = 2;  // fibers per thread: ta <= MAXF * NT
     int f_lo[MAXF], f_hi[MAXF];
@@ -510,23 +515,23 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 d[u] = *reinterpret_cast<const P *>(Db + (r[u].koff + lo));
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) cc[u].v[i] = T(0);
-                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + ((uint32_t)r[u].e + lo));
+                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + ((uint32_t)r[u].e + lo));   // read only where loaded
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const bool fiber_end = r[u].e >= 0;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) {
-                    tsum.v[i] += r[u].v * d[u].v[i];
-                    asum.v[i] += tsum.v[i] * cc[u].v[i];   // cc is zero unless the fiber ends here
-                    tsum.v[i] = fiber_end ? T(0) : tsum.v[i];
-                }
-                if (r[u].s >= 0) {
-                    emit(r[u].s, started);
-                    asum.clear();
-                    started = true;
+                for (int i = 0; i < VEC; ++i) tsum.v[i] += r[u].v * d[u].v[i];
+                if (r[u].e >= 0) {   // the fiber ends here: through the consumer, under the lane mask
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) {
+                        asum.v[i] += tsum.v[i] * cc[u].v[i];
+                        tsum.v[i] = T(0);
+                    }
+                    if (r[u].s >= 0) {   // a slice can only end where a fiber ends
+                        emit(r[u].s, started);
+                        asum.clear();
+                        started = true;
+                    }
                 }
             }
         }
@@ -755,7 +760,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
             ln.begin("mttkrp3_fused");
-            mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(a.tn, a.ta, a.tb), stream>>>(a);
+            mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(W, a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
             ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out);
             return ln.status;
@@ -854,8 +859,9 @@ size_t lds_bytes_needed(const sc_plan *p)
         if (uses_register_fused_mttkrp(p)) {
             // one thread stages at most two fibers and one slice
             if (p->caps.ta > 2 * NT || p->caps.tb > NT) return SIZE_MAX;
-            return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(p->caps.tn, p->caps.ta, p->caps.tb)
-                                      : mttkrp_lds_bytes<float>(p->caps.tn, p->caps.ta, p->caps.tb);
+            const int w = (int)producer_width(p);
+            return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(w, p->caps.tn, p->caps.ta, p->caps.tb)
+                                      : mttkrp_lds_bytes<float>(w, p->caps.tn, p->caps.ta, p->caps.tb);
         }
         if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) {
             if (!ttmc3_mfma_caps_ok(p)) return SIZE_MAX;
