@@ -339,23 +339,25 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 // and the slice sum A(i, r) in registers (Table 2, kernel 8 producer: t += B * D, then
 // A += t * C at the end of each fiber).
 //
-// Staging turns the tile's CSF arrays into one 16-byte LDS record per nonzero:
+// Staging turns the tile's CSF arrays into per-nonzero LDS arrays (read four nonzeros at a time):
 //   koff  byte offset of the D row to gather
 //   v     the stored value
 //   e     byte offset of the C row if this nonzero is the last of its fiber (in the tile), else -1
-//   s     tile-local slice number if this nonzero is the last of its slice (in the tile), else -1
-// so the walk needs no boundary cursors or searches: a lane group reads one record per
+//   send  one bit: this nonzero is the last of its slice (in the tile)
+// so the walk needs no boundary cursors or searches: a lane group reads these per
 // nonzero, gathers D (and C when e >= 0, in the same batch of loads) and updates two
-// register accumulators.  Fibers / slices cut by a chunk boundary are described by two
-// small per-group tables (chunk_coff, chunk_ls) filled during staging.
+// register accumulators; the slice it is in is a counter that starts from chunk_ls0.
+// Fibers / slices cut by a chunk boundary are described by small per-group tables
+// (chunk_coff, chunk_ls) filled during staging.  12 bytes of LDS per nonzero (fp32) let
+// eight workgroups share a compute unit; the walk is bound by gather latency, and the
+// kernel's time fell almost in proportion as the workgroups per unit went from 4 to 7.
 // ------------------------------------------------------------------------------------------
-template <typename T>
-struct alignas(sizeof(T) == 4 ? 16 : 8) NzRec {
-    uint32_t koff;
-    int32_t e;
-    int32_t s;
-    T v;
-};
+// LDS index of nonzero c in the per-nonzero arrays: groups of four stay contiguous and
+// 16-byte aligned, and one group of padding after every eight spreads the lane groups of a
+// wavefront (whose chunks start a multiple of 32 nonzeros apart) over the banks.
+__host__ __device__ constexpr int nz_vec(int c4) { return c4 + (c4 >> 3); }           // c4 = c / 4
+__host__ __device__ constexpr int nz_idx(int c) { return 4 * nz_vec(c >> 2) + (c & 3); }
+__host__ __device__ constexpr int nz_padded(int n) { return 4 * (nz_vec((n + 3) >> 2) + 1); }
 
 // W = rank; a lane group is W / (16 / sizeof(T)) lanes, and there is one parked row and one
 // entry of each chunk table per lane group.
@@ -363,7 +365,8 @@ template <typename T>
 __host__ __device__ constexpr size_t mttkrp_lds_bytes(int W, int tn, int ta, int tb)
 {
     const int groups = NT / (W / (16 / (int)sizeof(T)));
-    return (size_t)NT * 16 + (size_t)padded(tn + 8) * sizeof(NzRec<T>) + (size_t)(2 * tb + 3 * groups) * 4 + 64;
+    const int pn = nz_padded(tn + 8);
+    return (size_t)NT * 16 + (size_t)pn * (sizeof(T) + 8) + (size_t)((tn + 8 + 31) / 32 + 1) * 4 + (size_t)(2 * tb + 4 * groups) * 4 + 64;
 }
 
 template <typename T, int W>
@@ -374,44 +377,48 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
     constexpr int G = NT / LG;
     using P = Pack<T, VEC>;
     using Acc = AccVec<T, VEC>;
-    using Rec = NzRec<T>;
+    struct alignas(16) Val4 { T v[4]; };
+    struct alignas(16) Int4 { int32_t v[4]; };
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T *slot_s = reinterpret_cast<T *>(smem);                       // NT * VEC
-    Rec *rec_s = reinterpret_cast<Rec *>(slot_s + NT * VEC);       // tn
-    int *slo_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // tb: first nonzero of each slice
+    const int pn = nz_padded(a.tn + 8);
+    T *slot_s = reinterpret_cast<T *>(smem);                       // NT * VEC: one parked row per lane group
+    T *v_s = slot_s + NT * VEC;                                    // pn: stored values
+    uint32_t *koff_s = reinterpret_cast<uint32_t *>(v_s + pn);     // pn: byte offset of the D row
+    int32_t *e_s = reinterpret_cast<int32_t *>(koff_s + pn);       // pn: byte offset of the C row at a fiber end, else -1
+    uint32_t *send_s = reinterpret_cast<uint32_t *>(e_s + pn);     // one bit per nonzero: last of its slice
+    const int nsend = (a.tn + 8 + 31) / 32 + 1;
+    int *slo_s = reinterpret_cast<int *>(send_s + nsend);          // tb: first nonzero of each slice
     int *crdb_s = slo_s + a.tb;                                    // tb: output row of each slice
-    int *chunk_coff = crdb_s + a.tb;                               // G
-    int *chunk_ls = chunk_coff + G;                                // G
-    int *slot_id = chunk_ls + G;                                   // G
+    int *chunk_coff = crdb_s + a.tb;                               // G: C row of the fiber a chunk ends inside, else -1
+    int *chunk_ls = chunk_coff + G;                                // G: slice a chunk ends inside, else -1
+    int *chunk_ls0 = chunk_ls + G;                                 // G: slice holding the first nonzero of a chunk
+    int *slot_id = chunk_ls0 + G;                                  // G
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
     const int nchild = t.n1 - t.n0;
     const int na = t.na, nb = t.nb;
-    constexpr int U = 4;                          // gathers kept in flight per lane
+    constexpr int U = 4;                          // gathers kept in flight per lane = nonzeros per LDS read
     const int q = max(((nchild + G - 1) / G + U - 1) / U * U, U);   // nonzeros per lane group, multiple of U
     const uint32_t rowD = (uint32_t)(a.ldD * sizeof(T)), rowC = (uint32_t)(a.ldC * sizeof(T));
 
-    // ---- stage 1: records, per-fiber and per-slice ranges (kept in registers) ----
+    // ---- stage 1: per-nonzero arrays, per-fiber and per-slice ranges (kept in registers) ----
     {
         const T *vals = static_cast<const T *>(a.vals);
         for (int c = tid; c < nchild; c += NT) {
-            Rec r;
-            r.koff = (uint32_t)a.crd3[t.n0 + c] * rowD;
-            r.v = vals[t.n0 + c];
-            r.e = -1;
-            r.s = -1;
-            rec_s[pidx(c)] = r;
+            const int p = nz_idx(c);
+            koff_s[p] = (uint32_t)a.crd3[t.n0 + c] * rowD;
+            v_s[p] = vals[t.n0 + c];
+            e_s[p] = -1;
         }
         if (tid < U) {  // dummies that complete the last batch: value 0, row 0, no marks
-            Rec r;
-            r.koff = 0;
-            r.v = T(0);
-            r.e = -1;
-            r.s = -1;
-            rec_s[pidx(nchild + tid)] = r;
+            const int p = nz_idx(nchild + tid);
+            koff_s[p] = 0;
+            v_s[p] = T(0);
+            e_s[p] = -1;
         }
+        if (tid < nsend) send_s[tid] = 0;
         P z;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
@@ -451,12 +458,15 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 #pragma unroll
     for (int r = 0; r < MAXF; ++r)
         if (f_hi[r] > f_lo[r]) {
-            rec_s[pidx(f_hi[r] - 1)].e = (int32_t)f_off[r];
+            e_s[nz_idx(f_hi[r] - 1)] = (int32_t)f_off[r];
             for (int m = f_lo[r] / q + 1; m * q < f_hi[r]; ++m) chunk_coff[m - 1] = (int32_t)f_off[r];
         }
     if (s_hi > s_lo) {
-        rec_s[pidx(s_hi - 1)].s = tid;
-        for (int m = s_lo / q + 1; m * q < s_hi; ++m) chunk_ls[m - 1] = tid;
+        atomicOr(&send_s[(s_hi - 1) >> 5], 1u << ((s_hi - 1) & 31));
+        for (int m = (s_lo + q - 1) / q; m * q < s_hi; ++m) {
+            chunk_ls0[m] = tid;
+            if (m * q > s_lo) chunk_ls[m - 1] = tid;
+        }
     }
     __syncthreads();
 
@@ -489,7 +499,8 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 #pragma unroll
     for (int i = 0; i < VEC; ++i) headv.v[i] = T(0);
     if (gs < ge) {
-        bool started = (gs == 0) || (rec_s[pidx(gs - 1)].s >= 0);  // the current slice starts in this chunk
+        int ls = chunk_ls0[g];                     // slice of the nonzero the walk is at
+        bool started = slo_s[ls] == gs;            // the current slice starts in this chunk
         Acc tsum, asum;
         tsum.clear();
         asum.clear();
@@ -504,33 +515,36 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
                 head_ls = s;
             }
         };
-        // Chunks start at multiples of U and the records up to the next multiple of U past
+        // Chunks start at multiples of U and the entries up to the next multiple of U past
         // the tile's last nonzero are zero-valued dummies, so every batch is a full,
         // branch-free group of U gathers (the compiler can then keep all of them in flight).
         for (int c = gs; c < ge; c += U) {
-            Rec r[U];
+            const int pv = nz_vec(c >> 2);
+            const Int4 kk = reinterpret_cast<const Int4 *>(koff_s)[pv];
+            const Val4 vv = reinterpret_cast<const Val4 *>(v_s)[pv];
+            const Int4 ee = reinterpret_cast<const Int4 *>(e_s)[pv];
+            const uint32_t sbits = send_s[c >> 5] >> (c & 31);   // the batch's four bits share a word
             P d[U], cc[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
-#pragma unroll
             for (int u = 0; u < U; ++u) {
-                d[u] = *reinterpret_cast<const P *>(Db + (r[u].koff + lo));
-                if (r[u].e >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + ((uint32_t)r[u].e + lo));   // read only where loaded
+                d[u] = *reinterpret_cast<const P *>(Db + ((uint32_t)kk.v[u] + lo));
+                if (ee.v[u] >= 0) cc[u] = *reinterpret_cast<const P *>(Cb + ((uint32_t)ee.v[u] + lo));   // read only where loaded
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) tsum.v[i] += r[u].v * d[u].v[i];
-                if (r[u].e >= 0) {   // the fiber ends here: through the consumer, under the lane mask
+                for (int i = 0; i < VEC; ++i) tsum.v[i] += vv.v[u] * d[u].v[i];
+                if (ee.v[u] >= 0) {   // the fiber ends here: through the consumer, under the lane mask
 #pragma unroll
                     for (int i = 0; i < VEC; ++i) {
                         asum.v[i] += tsum.v[i] * cc[u].v[i];
                         tsum.v[i] = T(0);
                     }
-                    if (r[u].s >= 0) {   // a slice can only end where a fiber ends
-                        emit(r[u].s, started);
+                    if ((sbits >> u) & 1u) {   // a slice can only end where a fiber ends
+                        emit(ls, started);
                         asum.clear();
                         started = true;
+                        ++ls;
                     }
                 }
             }
