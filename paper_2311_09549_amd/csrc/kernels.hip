@@ -844,9 +844,10 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
             if (dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
-                // matrix-core kernel: measured best on the 30 M-nonzero workload (row tile + carry rows + records in ~40 KB)
+                // matrix-core kernel: measured best on the 30 M-nonzero workload; 216 rows keep the
+                // workgroup's LDS just below the size at which five fit a compute unit
                 c.tn = 768;
-                c.ta = 224;
+                c.ta = 216;
                 c.tb = 64;
             }
         }

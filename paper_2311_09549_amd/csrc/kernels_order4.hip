@@ -394,7 +394,9 @@ TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols)
     if (dtype == SC_F64) {
         c.tn = 512; c.ta = 256; c.tb = 40;
     } else {
-        c.tn = 640; c.ta = 384; c.tb = 72;
+        // the largest tile with which four workgroups of the matrix-core kernel fit a compute unit
+        // (40,528 bytes of LDS each); measured best on the 50 M-nonzero workload
+        c.tn = 768; c.ta = 384; c.tb = 76;
     }
     return c;
 }

@@ -208,7 +208,7 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
     // persistent launch: as many workgroups as fit on the chip at once (LDS-limited), never more than tiles
     a.ntiles = ntiles;
     const size_t lds = leaf_lds_bytes<T>(W, a.tn, a.ta);
-    const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
+    const int fit = lds_workgroups_per_cu(lds);
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 16) : fit;
     const int blocks = std::min(ntiles, 256 * per_cu);
     leaf_traverse_kernel<T, W><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);

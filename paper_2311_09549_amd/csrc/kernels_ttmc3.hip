@@ -51,16 +51,26 @@ constexpr int T3_WAVES = NT / 64;
 constexpr int T3_MAXR = 4;          // tn <= T3_MAXR * NT
 constexpr int T3_MAXB = 2;          // ta + 1 <= T3_MAXB * NT, tb + 1 <= NT
 
+// The carry rows and the nonzero records are dead once the T rows of a tile are complete;
+// the pieces that the consumer parks (WAVES x {head, tail} x 256 floats) reuse their space.
+// The kernel is bound by latency and its time falls almost in proportion to the workgroups
+// that fit a compute unit, so LDS bytes are what to save.
+__host__ __device__ constexpr size_t ttmc3_scratch_bytes(int tn)
+{
+    const size_t walk = (size_t)T3_G * T3_RS * 4 + (size_t)padded(tn + 8) * sizeof(Ttmc3Rec);
+    const size_t park = (size_t)(2 * T3_WAVES) * 256 * 4;
+    return walk > park ? walk : park;
+}
+
 __host__ __device__ constexpr size_t ttmc3_lds_bytes(int tn, int ta, int tb)
 {
-    return leaf_walk_lds_bytes<float>(T3_W, tn, ta, NT) + (size_t)ta * 4 + (size_t)(2 * tb + 2) * 4 +
-           (size_t)(2 * T3_WAVES) * 256 * 4 + T3_WAVES * 16 + 64;
+    return (size_t)(ta + 1) * T3_RS * 4 + ttmc3_scratch_bytes(tn) + (size_t)(ta + 2 + T3_G + ta + 2 * tb + 2) * 4 + T3_WAVES * 16 + 64;
 }
 
 typedef float t3_floatx4 __attribute__((ext_vector_type(4)));
 
 template <bool FUSED>
-__global__ void __launch_bounds__(NT) ttmc3_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
+__global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
 {
     constexpr int U = 8;
     constexpr int RS = T3_RS;
@@ -68,9 +78,9 @@ __global__ void __launch_bounds__(NT) ttmc3_mfma_kernel(Ttmc3Args a, const TileR
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *row_s = reinterpret_cast<float *>(smem);                                      // (ta + 1) rows of RS
     float *carry_s = row_s + (size_t)(a.ta + 1) * RS;                                    // G rows of RS
-    float *part_s = carry_s + (size_t)T3_G * RS;                                         // WAVES x {head, tail} x 256
-    Ttmc3Rec *rec_s = reinterpret_cast<Ttmc3Rec *>(part_s + 2 * T3_WAVES * 256);         // padded(tn + 8)
-    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));                       // ta + 2
+    Ttmc3Rec *rec_s = reinterpret_cast<Ttmc3Rec *>(carry_s + (size_t)T3_G * RS);         // padded(tn + 8)
+    float *part_s = carry_s;                                                             // WAVES x {head, tail} x 256, once carry_s and rec_s are dead
+    int *ba_s = reinterpret_cast<int *>(reinterpret_cast<unsigned char *>(carry_s) + ttmc3_scratch_bytes(a.tn));   // ta + 2
     int *chunk_lr = ba_s + a.ta + 2;                                                     // G
     uint32_t *coff_s = reinterpret_cast<uint32_t *>(chunk_lr + T3_G);                    // ta: byte offset of C(j,:)
     int *bb_s = reinterpret_cast<int *>(coff_s + a.ta);                                  // tb + 2: first fiber of each slice
@@ -286,7 +296,7 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc3_lds_bytes(a.tn, a.ta, a.tb);
-    const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
+    const int fit = lds_workgroups_per_cu(lds);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
     const int want = std::min(ntiles, 256 * per_cu);

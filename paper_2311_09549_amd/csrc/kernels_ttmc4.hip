@@ -51,10 +51,26 @@ constexpr int T4_TR1 = 3;                  // MODE 1: T1 rows copied per 2-lane 
 constexpr int T4_TR2 = 5;                  // MODE 2: T2 rows copied per 16-lane group, tb <= T4_TR2 * G2
 static_assert(NT / 64 == T4_W2 / 16, "one wavefront per 16 columns of a T2 row");
 
+// What the leaf stage needs besides the T1 rows (carry rows, nonzero records, fiber bounds,
+// chunk heads) is dead before the first T2 row is written, and shares its space with the T2
+// rows.  The kernel is bound by latency and its time falls almost in proportion to the
+// workgroups that fit a compute unit, so LDS bytes are what to save.
+__host__ __device__ constexpr size_t ttmc4_leaf_scratch_bytes(int tn, int ta)
+{
+    return (size_t)T4_G1 * T4_RS1 * 4 + (size_t)padded(tn + 8) * sizeof(LeafRec<float>) + (size_t)(ta + 2) * 4 + (size_t)T4_G1 * 4;
+}
+
+__host__ __device__ constexpr size_t ttmc4_shared_bytes(int tn, int ta, int tb)
+{
+    const size_t leaf = ttmc4_leaf_scratch_bytes(tn, ta);
+    const size_t rows2 = (size_t)(tb + 1 + T4_G2) * T4_RS2 * 4;
+    return ((leaf > rows2 ? leaf : rows2) + 15) / 16 * 16;
+}
+
 __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb)
 {
-    return leaf_walk_lds_bytes<float>(T4_N, tn, ta, NT) + (size_t)(tb + 1 + T4_G2) * T4_RS2 * 4 + (size_t)(ta + 4) * 4 +
-           (size_t)(tb + 2) * 4 + (size_t)T4_G2 * 4 + (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
+    return (size_t)(ta + 1) * T4_RS1 * 4 + ttmc4_shared_bytes(tn, ta, tb) + (size_t)(ta + 4) * 4 + (size_t)(tb + 2) * 4 + (size_t)T4_G2 * 4 +
+           (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
 }
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
@@ -69,13 +85,16 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *row1_s = reinterpret_cast<float *>(smem);                          // (ta + 1) rows of RS1: T1
-    float *carry1_s = row1_s + (size_t)(a.ta + 1) * RS1;                      // G1 rows of RS1
-    float *row2_s = carry1_s + (size_t)T4_G1 * RS1;                           // (tb + 1) rows of RS2: T2
-    float *carry2_s = row2_s + (size_t)(a.tb + 1) * RS2;                      // G2 rows of RS2
-    Rec *rec_s = reinterpret_cast<Rec *>(carry2_s + (size_t)T4_G2 * RS2);     // padded(tn + 8)
+    unsigned char *shared_s = reinterpret_cast<unsigned char *>(row1_s + (size_t)(a.ta + 1) * RS1);
+    // leaf stage (dead once the T1 rows are complete) ...
+    float *carry1_s = reinterpret_cast<float *>(shared_s);                    // G1 rows of RS1
+    Rec *rec_s = reinterpret_cast<Rec *>(carry1_s + (size_t)T4_G1 * RS1);     // padded(tn + 8)
     int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // ta + 2: first nonzero of each f3
     int *chunk_lr1 = ba_s + a.ta + 2;                                         // G1
-    uint32_t *krec_s = reinterpret_cast<uint32_t *>(chunk_lr1 + T4_G1);       // ta + 4: D row offset of each f3 | end-of-f2 bit 31
+    // ... and, in the same space, what the middle walk and the consumer use
+    float *row2_s = reinterpret_cast<float *>(shared_s);                      // (tb + 1) rows of RS2: T2
+    float *carry2_s = row2_s + (size_t)(a.tb + 1) * RS2;                      // G2 rows of RS2
+    uint32_t *krec_s = reinterpret_cast<uint32_t *>(shared_s + ttmc4_shared_bytes(a.tn, a.ta, a.tb));   // ta + 4: D row offset of each f3 | end-of-f2 bit 31
     int *bb_s = reinterpret_cast<int *>(krec_s + a.ta + 4);                   // tb + 2: first f3 of each f2
     int *chunk_lr2 = bb_s + a.tb + 2;                                         // G2
     uint32_t *coff2_s = reinterpret_cast<uint32_t *>(chunk_lr2 + T4_G2);      // tb: byte offset of C(j,:) per f2
@@ -378,7 +397,7 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb);
-    const int fit = (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / (lds + 512)));
+    const int fit = lds_workgroups_per_cu(lds);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
     const int want = std::min(ntiles, 256 * per_cu);
