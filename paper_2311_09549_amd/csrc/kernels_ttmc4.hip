@@ -67,10 +67,11 @@ __host__ __device__ constexpr size_t ttmc4_shared_bytes(int tn, int ta, int tb)
     return ((leaf > rows2 ? leaf : rows2) + 15) / 16 * 16;
 }
 
-__host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb)
+// The third kernel of the FISSIONED schedule (mode 2) reads finished T2 rows and has no T1 rows.
+__host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb, int mode = 0)
 {
-    return (size_t)(ta + 1) * T4_RS1 * 4 + ttmc4_shared_bytes(tn, ta, tb) + (size_t)(ta + 4) * 4 + (size_t)(tb + 2) * 4 + (size_t)T4_G2 * 4 +
-           (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
+    return (size_t)(mode == 2 ? 0 : (ta + 1) * T4_RS1 * 4) + ttmc4_shared_bytes(tn, ta, tb) + (size_t)(ta + 4) * 4 + (size_t)(tb + 2) * 4 +
+           (size_t)T4_G2 * 4 + (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
 }
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
@@ -85,7 +86,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float *row1_s = reinterpret_cast<float *>(smem);                          // (ta + 1) rows of RS1: T1
-    unsigned char *shared_s = reinterpret_cast<unsigned char *>(row1_s + (size_t)(a.ta + 1) * RS1);
+    unsigned char *shared_s = reinterpret_cast<unsigned char *>(row1_s + (MODE == 2 ? (size_t)0 : (size_t)(a.ta + 1) * RS1));
     // leaf stage (dead once the T1 rows are complete) ...
     float *carry1_s = reinterpret_cast<float *>(shared_s);                    // G1 rows of RS1
     Rec *rec_s = reinterpret_cast<Rec *>(carry1_s + (size_t)T4_G1 * RS1);     // padded(tn + 8)
@@ -396,7 +397,7 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.L = (int32_t)p->fcols[0];
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
-    const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb);
+    const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb, mode);
     const int fit = lds_workgroups_per_cu(lds);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
