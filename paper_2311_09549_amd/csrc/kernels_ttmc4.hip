@@ -113,8 +113,59 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
     t4_floatx4 carry = {0.f, 0.f, 0.f, 0.f};   // this wavefront's columns of the slice continuing from the previous tile
     bool chain_shared = false;                 // that slice began before this workgroup's run
 
+    // Global reads of one tile's staging, held in registers: they are issued while the previous
+    // tile of the run is still being worked on.
+    struct Stage {
+        uint32_t pp[T4_MAXR];
+        float vv[T4_MAXR];
+        int p4[T4_MAXA], k3[T4_MAXA];
+        int p3, j2, p2, i1;
+        P t1row[MODE == 1 ? T4_TR1 : 1], t2row[MODE == 2 ? T4_TR2 : 1];
+    };
+    auto issue = [&](const TileRec &t, Stage &s) {
+        const int nchild = t.n1 - t.n0;
+        const int na = t.na, nb = t.nb, nc = t.nc;
+        if (MODE == 0) {
+#pragma unroll
+            for (int r = 0; r < T4_MAXR; ++r) {
+                const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                s.pp[r] = (uint32_t)a.crd4[c];
+                s.vv[r] = a.vals[c];
+            }
+#pragma unroll
+            for (int r = 0; r < T4_MAXA; ++r) s.p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
+        }
+        if (MODE != 2) {
+#pragma unroll
+            for (int r = 0; r < T4_MAXA; ++r) s.k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
+            s.p3 = a.pos3[t.b0 + min(tid, nb)];
+        }
+        if (MODE != 1) {
+            s.j2 = a.crd2[t.b0 + min(tid, nb - 1)];
+            s.p2 = a.pos2[t.c0 + min(tid, nc)];
+            s.i1 = a.crd1[t.c0 + min(tid, nc - 1)];
+        }
+        if (MODE == 1) {
+#pragma unroll
+            for (int r = 0; r < T4_TR1; ++r) {
+                const int f = min(tid / 2 + r * T4_G1, na - 1);
+                s.t1row[r] = *reinterpret_cast<const P *>(a.T1 + (int64_t)(t.a0 + f) * T4_N + (tid % 2) * 4);
+            }
+        }
+        if (MODE == 2) {
+#pragma unroll
+            for (int r = 0; r < T4_TR2; ++r) {
+                const int f = min(tid / T4_LG2 + r * T4_G2, nb - 1);
+                s.t2row[r] = *reinterpret_cast<const P *>(a.T2 + (int64_t)(t.b0 + f) * T4_W2 + (tid % T4_LG2) * 4);
+            }
+        }
+    };
+    TileRec t = tiles[first];   // a launched workgroup has at least one tile
+    Stage st;
+    issue(t, st);
+
     for (int tile = first; tile < lastp1; ++tile) {
-        const TileRec t = tiles[tile];
+        const TileRec tn = tiles[min(tile + 1, lastp1 - 1)];
         const bool in_f = (t.flags & 16) != 0, out_f = (t.flags & 32) != 0;
         if (tile == first && in_f) chain_shared = true;
         const int nchild = t.n1 - t.n0;
@@ -122,47 +173,15 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
         const int q1 = leaf_chunk<U1>(nchild, T4_G1);
         const int q2 = leaf_chunk<U2>(na, T4_G2);
 
-        // ---- stage ----
+        // ---- stage: registers -> LDS ----
         {
-            uint32_t pp[T4_MAXR];
-            float vv[T4_MAXR];
-            int p4[T4_MAXA], k3[T4_MAXA];
-            int p3 = 0, j2 = 0, p2 = 0, i1 = 0;
-            P t1row[T4_TR1], t2row[T4_TR2];
-            if (MODE == 0) {
-#pragma unroll
-                for (int r = 0; r < T4_MAXR; ++r) {
-                    const int c = t.n0 + min(tid + r * NT, nchild - 1);
-                    pp[r] = (uint32_t)a.crd4[c];
-                    vv[r] = a.vals[c];
-                }
-#pragma unroll
-                for (int r = 0; r < T4_MAXA; ++r) p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
-            }
-            if (MODE != 2) {
-#pragma unroll
-                for (int r = 0; r < T4_MAXA; ++r) k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
-                p3 = a.pos3[t.b0 + min(tid, nb)];
-            }
-            if (MODE != 1) {
-                j2 = a.crd2[t.b0 + min(tid, nb - 1)];
-                p2 = a.pos2[t.c0 + min(tid, nc)];
-                i1 = a.crd1[t.c0 + min(tid, nc - 1)];
-            }
-            if (MODE == 1) {
-#pragma unroll
-                for (int r = 0; r < T4_TR1; ++r) {
-                    const int f = min(tid / 2 + r * T4_G1, na - 1);
-                    t1row[r] = *reinterpret_cast<const P *>(a.T1 + (int64_t)(t.a0 + f) * T4_N + (tid % 2) * 4);
-                }
-            }
-            if (MODE == 2) {
-#pragma unroll
-                for (int r = 0; r < T4_TR2; ++r) {
-                    const int f = min(tid / T4_LG2 + r * T4_G2, nb - 1);
-                    t2row[r] = *reinterpret_cast<const P *>(a.T2 + (int64_t)(t.b0 + f) * T4_W2 + (tid % T4_LG2) * 4);
-                }
-            }
+            const uint32_t(&pp)[T4_MAXR] = st.pp;
+            const float(&vv)[T4_MAXR] = st.vv;
+            const int(&p4)[T4_MAXA] = st.p4;
+            const int(&k3)[T4_MAXA] = st.k3;
+            const int p3 = st.p3, j2 = st.j2, p2 = st.p2, i1 = st.i1;
+            const auto &t1row = st.t1row;
+            const auto &t2row = st.t2row;
             if (MODE == 0) {
 #pragma unroll
                 for (int r = 0; r < T4_MAXR; ++r) {
@@ -226,6 +245,10 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
             }
         }
         __syncthreads();
+
+        // ---- the next tile's reads go out now and land while this tile is worked on ----
+        Stage sn;
+        if (tile + 1 < lastp1) issue(tn, sn);
 
         // ---- marks of both walks ----
         if (MODE == 0) leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
@@ -362,6 +385,10 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
             }
         }
         __syncthreads();
+        if (tile + 1 < lastp1) {
+            t = tn;
+            st = sn;
+        }
     }  // tiles of the run
 }
 
