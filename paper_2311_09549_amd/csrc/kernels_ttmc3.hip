@@ -91,8 +91,44 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     const int first = blockIdx.x * a.run, lastp1 = min(first + a.run, a.ntiles);
     t3_floatx4 carry = {0.f, 0.f, 0.f, 0.f};   // wavefront 0: sum so far of the slice that continues from the previous tile
     bool chain_shared = false;                 // that slice began before this workgroup's run
+    // Global reads of one tile's staging, all issued before the first is used.
+    constexpr int TR = (NT + T3_G - 1) / T3_G;   // T rows copied per lane group: ta <= TR * G
+    struct Stage {
+        uint32_t kk[T3_MAXR];
+        float vv[T3_MAXR];
+        int pb[T3_MAXB];
+        Pack<float, 4> trow[FUSED ? 1 : TR];
+        int cj, ps, ci;
+    };
+    auto issue = [&](const TileRec &t, Stage &s) {
+        const int nchild = t.n1 - t.n0;
+        const int na = t.na, nb = t.nb;
+        if (FUSED) {
+#pragma unroll
+            for (int r = 0; r < T3_MAXR; ++r) {
+                const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                s.kk[r] = (uint32_t)a.crd3[c];
+                s.vv[r] = a.vals[c];
+            }
+#pragma unroll
+            for (int r = 0; r < T3_MAXB; ++r) s.pb[r] = a.pos3[t.a0 + min(tid + r * NT, na)];
+        } else {
+#pragma unroll
+            for (int r = 0; r < TR; ++r) {
+                const int f = min(tid / T3_LG + r * T3_G, na - 1);
+                s.trow[r] = *reinterpret_cast<const Pack<float, 4> *>(a.T + (int64_t)(t.a0 + f) * T3_W + (tid % T3_LG) * 4);
+            }
+        }
+        s.cj = a.crd2[t.a0 + min(tid, na - 1)];
+        s.ps = a.pos2[t.b0 + min(tid, nb)];
+        s.ci = a.crd1[t.b0 + min(tid, nb - 1)];
+    };
+    TileRec t = tiles[first];   // a launched workgroup has at least one tile
+    Stage st;
+    issue(t, st);
+
     for (int tile = first; tile < lastp1; ++tile) {
-    const TileRec t = tiles[tile];
+    const TileRec tn = tiles[min(tile + 1, lastp1 - 1)];
     const bool in_f = (t.flags & 4) != 0, out_f = (t.flags & 8) != 0;
     if (tile == first && in_f) chain_shared = true;
     const int nchild = t.n1 - t.n0;
@@ -100,32 +136,13 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     const int q = leaf_chunk<U>(nchild, T3_G);   // nonzeros per lane group, multiple of U
     const uint32_t rowD = (uint32_t)(a.ldD * 4), rowC = (uint32_t)(a.ldC * 4);
 
-    // ---- stage 1 ----
+    // ---- stage 1: registers -> LDS ----
     {
-        constexpr int TR = (NT + T3_G - 1) / T3_G;   // T rows copied per lane group: ta <= TR * G
-        uint32_t kk[T3_MAXR];
-        float vv[T3_MAXR];
-        int pb[T3_MAXB];
-        Pack<float, 4> trow[TR];
-        if (FUSED) {
-#pragma unroll
-            for (int r = 0; r < T3_MAXR; ++r) {
-                const int c = t.n0 + min(tid + r * NT, nchild - 1);
-                kk[r] = (uint32_t)a.crd3[c];
-                vv[r] = a.vals[c];
-            }
-#pragma unroll
-            for (int r = 0; r < T3_MAXB; ++r) pb[r] = a.pos3[t.a0 + min(tid + r * NT, na)];
-        } else {
-#pragma unroll
-            for (int r = 0; r < TR; ++r) {
-                const int f = min(tid / T3_LG + r * T3_G, na - 1);
-                trow[r] = *reinterpret_cast<const Pack<float, 4> *>(a.T + (int64_t)(t.a0 + f) * T3_W + (tid % T3_LG) * 4);
-            }
-        }
-        const int cj = a.crd2[t.a0 + min(tid, na - 1)];
-        const int ps = a.pos2[t.b0 + min(tid, nb)];
-        const int ci = a.crd1[t.b0 + min(tid, nb - 1)];
+        const uint32_t(&kk)[T3_MAXR] = st.kk;
+        const float(&vv)[T3_MAXR] = st.vv;
+        const int(&pb)[T3_MAXB] = st.pb;
+        const auto &trow = st.trow;
+        const int cj = st.cj, ps = st.ps, ci = st.ci;
         if (FUSED) {
 #pragma unroll
             for (int r = 0; r < T3_MAXR; ++r) {
@@ -166,6 +183,11 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
         if (tid < nb) crdb_s[tid] = ci;
     }
     __syncthreads();
+
+    // ---- consumer kernel: the next tile's reads go out now and land while this tile is worked on
+    // (the fused kernel has no registers to spare for that: it measured slower with spills) ----
+    Stage sn;
+    if (!FUSED && tile + 1 < lastp1) issue(tn, sn);
 
     // ---- stage 2, walk (leaves -> T rows in LDS), combine ----
     if (FUSED) {
@@ -267,6 +289,11 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
         }
     }
     __syncthreads();
+    if (tile + 1 < lastp1) {
+        if (FUSED) issue(tn, sn);
+        t = tn;
+        st = sn;
+    }
     }  // tiles of the run
 }
 
