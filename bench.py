@@ -73,13 +73,16 @@ def main() -> int:
         for _ in range(warmup):
             con.run()
         torch.cuda.synchronize()
-        beg, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        beg.record()
-        for _ in range(steps):
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        marks[0].record()
+        for i in range(steps):
             con.run()
-        end.record()
+            marks[i + 1].record()   # an event between steps costs nothing the stream waits for
         torch.cuda.synchronize()
-        return beg.elapsed_time(end) / steps
+        per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
+        timed.stats = {"median": float(np.median(per_step)), "std": float(per_step.std()),
+                       "min": float(per_step.min()), "max": float(per_step.max())}
+        return marks[0].elapsed_time(marks[steps]) / steps
 
     def kernel_times(con, steps):
         """Average per-kernel milliseconds over `steps` profiled executions (HIP events
@@ -104,6 +107,7 @@ def main() -> int:
     t_plan = time.time() - t0
     flops, bytes_fused = sc.plan_model(fused.plan)
     ms = timed(fused, args.steps, args.warmup)
+    ms_stats = dict(timed.stats)
     kt = kernel_times(fused, min(args.steps, 20))
     dom_name = max(kt, key=kt.get)
     dom_ms = kt[dom_name]
@@ -146,6 +150,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms,
+        "ms_per_step_stats": ms_stats,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

@@ -119,7 +119,12 @@ typedef struct {
  *                    the on-chip granularity actually used.
  *   deterministic    0: partial sums of rows that span work tiles are combined with
  *                    floating-point atomics (order may vary from run to run).
- *                    1: not available yet (SC_ERR_SCHED_UNSUPPORTED). */
+ *                    1: every tile stores its piece of such a row in the workspace and a last
+ *                    kernel adds the pieces in tile order, so two executions of a plan give
+ *                    bit-identical results.  Available for the FUSED schedules of the MTTKRP
+ *                    (any supported rank, fp32 / fp64) and of the order-3 (fp32, L = M = 16)
+ *                    and order-4 (fp32, M = N = 8) TTM chains; SC_ERR_SCHED_UNSUPPORTED
+ *                    otherwise.  sc_plan_workspace_bytes then includes the pieces. */
 typedef struct {
     sc_sched_kind kind;
     int32_t n_intermediates;

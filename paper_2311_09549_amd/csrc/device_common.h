@@ -187,13 +187,18 @@ sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *po
 // or the consumer kernel of the FISSIONED one.
 size_t ttmc3_mfma_lds_bytes(const sc_plan *p);
 bool ttmc3_mfma_caps_ok(const sc_plan *p);
-sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out);
+// `partials`: deterministic schedules only (else null): slots for the pieces of rows that span tiles.
+sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
+                            void *partials);
+
+// Last kernel of a deterministic schedule: adds the stored pieces of every row that spans tiles.
+sc_status launch_fixup(const sc_plan *p, Launcher &ln, void *workspace, void *out);
 
 // Order-4 TTM chain on matrix cores (fp32, M = N = 8, L <= 16; its own kernel file): mode 0 the FUSED schedule,
 // modes 1 and 2 the second and third kernel of the FISSIONED one.
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p);
 bool ttmc4_mfma_caps_ok(const sc_plan *p);
 sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
-                            void *T2, void *out);
+                            void *T2, void *out, void *partials);
 
 }  // namespace sck

@@ -378,6 +378,52 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
     }
 }
 
+// Deterministic schedules: numbers the pieces of every output row that spans several tiles
+// (consecutive slots in tile order) and lists those rows.  The top level is "b" for order 3
+// and "c" for order 4; its flag bits say whether the tile's first / last slice continues
+// from the previous / into the next tile.  A tile whose only slice does both holds one piece.
+void assign_piece_slots(sc_plan *p, const HostCsf &h)
+{
+    const bool o4 = p->order == 4;
+    const int32_t in_bit = o4 ? 16 : 4, out_bit = o4 ? 32 : 8;
+    int32_t next = 0;
+    p->fix.clear();
+    for (TileRec &t : p->tiles) {
+        const int32_t top0 = o4 ? t.c0 : t.b0, ntop = o4 ? t.nc : t.nb;
+        const bool in = (t.flags & in_bit) != 0, out = (t.flags & out_bit) != 0;
+        t.pad[0] = t.pad[1] = -1;
+        if (in) {   // a piece of the row that the previous tile left open
+            t.pad[0] = next++;
+            p->fix.back().count++;
+        }
+        if (out && !(in && ntop == 1)) {   // the tile's last slice starts here and goes on
+            FixRec f;
+            f.row = h.crd[0][top0 + ntop - 1];
+            f.first = next;
+            f.count = 1;
+            f.pad = 0;
+            p->fix.push_back(f);
+            t.pad[1] = next++;
+        }
+    }
+    p->n_slots = next;
+    // segments of the first pass; a row's segments are consecutive
+    p->segs.clear();
+    for (FixRec &f : p->fix) {
+        const int32_t slot0 = f.first, pieces = f.count;
+        f.first = (int32_t)p->segs.size();
+        f.count = (pieces + kFixSegment - 1) / kFixSegment;
+        for (int32_t s0 = 0; s0 < pieces; s0 += kFixSegment) {
+            FixRec g;
+            g.row = (int32_t)p->segs.size();
+            g.first = slot0 + s0;
+            g.count = std::min<int32_t>(kFixSegment, pieces - s0);
+            g.pad = 0;
+            p->segs.push_back(g);
+        }
+    }
+}
+
 void appendf(std::string &s, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 void appendf(std::string &s, const char *fmt, ...)
 {
@@ -565,7 +611,8 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
 
     // ---- schedule ----
     if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
-    if (sched->deterministic != 0) return SC_ERR_SCHED_UNSUPPORTED;
+    if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
+    p->deterministic = sched->deterministic == 1;
     p->sched = sched->kind;
     p->n_inter = (int32_t)fam.temp_idx.size();
     if (sched->n_intermediates != 0 && sched->n_intermediates != p->n_inter) return SC_ERR_SCHED_UNSUPPORTED;
@@ -608,6 +655,10 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     if (lds_bytes_needed(p) > 64 * 1024) return SC_ERR_SCHED_UNSUPPORTED;
     try {
         build_tiles(sparse, h, p->caps, p->tiles);
+        if (p->deterministic) {
+            if (!plan_supports_deterministic(p)) return SC_ERR_SCHED_UNSUPPORTED;
+            assign_piece_slots(p, h);
+        }
     } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
 
     // ---- workspace, model, text ----
@@ -669,6 +720,12 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         p->ws_bytes = 0;
         for (int t = 0; t < p->n_inter; ++t) p->inter[t].offset = 0;
     }
+    if (p->deterministic && p->n_slots) {
+        const size_t row_bytes = (size_t)p->out_row_elems * esize(p->dtype);
+        p->det_offset = (p->ws_bytes + 255) & ~(size_t)255;
+        p->seg_offset = (p->det_offset + (size_t)p->n_slots * row_bytes + 255) & ~(size_t)255;
+        p->ws_bytes = p->seg_offset + p->segs.size() * row_bytes;
+    }
     p->model_flops = flops;
     p->model_bytes = bytes;
 
@@ -712,6 +769,9 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     appendf(tx, "\ntiles: %zu (<= %d leaves, <= %d level-a nodes", p->tiles.size(), p->caps.tn, p->caps.ta);
     if (d == 4) appendf(tx, ", <= %d level-b nodes", p->caps.tb);
     appendf(tx, ")\nmodel: %.6g flops, %.6g compulsory HBM bytes, workspace %zu bytes\n", flops, bytes, p->ws_bytes);
+    if (p->deterministic)
+        appendf(tx, "deterministic: %zu output rows span several tiles; their %lld pieces are stored in the workspace and added in tile order (%zu segments of at most %d)\n",
+                p->fix.size(), (long long)p->n_slots, p->segs.size(), kFixSegment);
 
     // ---- device tables ----
     int ndev = 0;
@@ -731,6 +791,14 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             for (size_t r = 0; r < stride; ++r)
                 for (size_t t = r; t < nt; t += stride) order.push_back(p->tiles[t]);
             if (hipMemcpy(p->d_tiles, order.data(), sizeof(TileRec) * nt, hipMemcpyHostToDevice) != hipSuccess)
+                return SC_ERR_DEVICE;
+        }
+        if (!p->fix.empty()) {
+            if (hipMalloc((void **)&p->d_fix, sizeof(FixRec) * p->fix.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(p->d_fix, p->fix.data(), sizeof(FixRec) * p->fix.size(), hipMemcpyHostToDevice) != hipSuccess)
+                return SC_ERR_DEVICE;
+            if (hipMalloc((void **)&p->d_segs, sizeof(FixRec) * p->segs.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(p->d_segs, p->segs.data(), sizeof(FixRec) * p->segs.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
         p->has_device = true;
@@ -863,6 +931,8 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
 {
     if (!plan) return SC_OK;
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
+    if (plan->d_fix) (void)hipFree(plan->d_fix);
+    if (plan->d_segs) (void)hipFree(plan->d_segs);
     if (plan->events_made)
         for (int i = 0; i < kMaxLaunches; ++i) {
             (void)hipEventDestroy(plan->ev_begin[i]);

@@ -49,6 +49,7 @@ struct Order3Args {
     int32_t L;      // columns of C (outer only)
     void *T;        // temporary rows (MODE 1 writes, MODE 2 reads)
     void *A;
+    void *partials; // deterministic schedules: slots for the pieces of rows that span tiles, else null
     int32_t tn, ta, tb;  // caps used to carve LDS
 };
 
@@ -481,6 +482,11 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
         T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
         if (!slice_shared(ls)) {
             *reinterpret_cast<P *>(dst) = row;
+        } else if (a.partials) {
+            // deterministic: the tile's one piece of this row goes to its slot (a tile whose only
+            // slice continues on both sides has one piece, numbered as its first)
+            const int slot = (ls == 0 && (t.flags & 4)) ? t.pad[0] : t.pad[1];
+            *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
@@ -748,6 +754,47 @@ int64_t producer_width(const sc_plan *p)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Deterministic schedules, last two kernels: add rows of `src` in a fixed order and write the
+// sum to a row of `dst` (nothing else writes it).  First pass: the pieces of every output row
+// that spans several tiles, in segments (dst = segment sums); second pass: the segment sums of
+// each such row, into the output.  One workgroup per record; when a row is narrower than the
+// workgroup, NT / rowlen lanes share the source rows round robin and their sums are added in
+// lane order, so the order of additions is fixed by the plan.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(NT) fixup_rows_kernel(const FixRec *__restrict__ fix, const T *__restrict__ srcbase, T *dstbase, int rowlen)
+{
+    __shared__ T lane_sum[NT];
+    const FixRec f = fix[blockIdx.x];
+    const int tid = threadIdx.x;
+    const T *src = srcbase + (int64_t)f.first * rowlen;
+    T *dst = dstbase + (int64_t)f.row * rowlen;
+    if (rowlen <= NT / 2) {
+        const int lanes = NT / rowlen;
+        const int lane = tid / rowlen, e = tid % rowlen;
+        T s = T(0);
+        if (lane < lanes) {
+#pragma unroll 4
+            for (int p = lane; p < f.count; p += lanes) s += src[(int64_t)p * rowlen + e];
+        }
+        lane_sum[tid] = s;
+        __syncthreads();
+        if (tid < rowlen) {
+            T tot = lane_sum[tid];
+            for (int l = 1; l < lanes; ++l) tot += lane_sum[l * rowlen + tid];
+            dst[tid] = tot;
+        }
+    } else {
+        for (int e = tid; e < rowlen; e += NT) {
+            T s = T(0);
+#pragma unroll 8
+            for (int p = 0; p < f.count; ++p) s += src[(int64_t)p * rowlen + e];
+            dst[e] = s;
+        }
+    }
+}
+
 template <typename T, int W>
 sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
@@ -764,6 +811,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.L = (int32_t)p->fcols[0];
     a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
     a.A = out;
+    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
     const bool had = p->kind == K_MTTKRP3;
@@ -776,13 +824,15 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.begin("mttkrp3_fused");
             mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(W, a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
-            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out);
-            return ln.status;
+            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out, a.partials);
+            if (ln.status != SC_OK) return ln.status;
+            return launch_fixup(p, ln, ws, out);
         } else {
             ln.begin("ttmc3_fused_valu");
             order3_kernel<T, W, 0, 1><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
+        if (had) return launch_fixup(p, ln, ws, out);
     } else {
         const sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse");
         if (st != SC_OK) return st;
@@ -791,7 +841,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.begin("mttkrp3_consume");
             hadamard_consume_kernel<T, W><<<ntiles, NT, hadamard_lds_bytes<T>(a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
-            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out);
+            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out, nullptr);
             return ln.status;
         } else {
             ln.begin("ttmc3_consume_valu");
@@ -857,6 +907,37 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
     case K_TTMC4: return order4_caps(dtype, fcols);
     }
     return c;
+}
+
+bool plan_supports_deterministic(const sc_plan *p)
+{
+    if (p->sched != SC_SCHED_FUSED) return false;
+    return p->kind == K_MTTKRP3 || plan_wants_tensor_order(p);
+}
+
+sc_status launch_fixup(const sc_plan *p, Launcher &ln, void *ws, void *out)
+{
+    if (!p->deterministic || p->fix.empty()) return ln.status;
+    const int rowlen = (int)p->out_row_elems;
+    char *slots = static_cast<char *>(ws) + p->det_offset;
+    char *segs = static_cast<char *>(ws) + p->seg_offset;
+    ln.begin("fixup_segments");
+    if (p->dtype == SC_F64)
+        fixup_rows_kernel<double><<<(int)p->segs.size(), NT, 0, ln.stream>>>(p->d_segs, reinterpret_cast<const double *>(slots),
+                                                                             reinterpret_cast<double *>(segs), rowlen);
+    else
+        fixup_rows_kernel<float><<<(int)p->segs.size(), NT, 0, ln.stream>>>(p->d_segs, reinterpret_cast<const float *>(slots),
+                                                                            reinterpret_cast<float *>(segs), rowlen);
+    ln.end();
+    ln.begin("fixup_rows");
+    if (p->dtype == SC_F64)
+        fixup_rows_kernel<double><<<(int)p->fix.size(), NT, 0, ln.stream>>>(p->d_fix, reinterpret_cast<const double *>(segs),
+                                                                            static_cast<double *>(out), rowlen);
+    else
+        fixup_rows_kernel<float><<<(int)p->fix.size(), NT, 0, ln.stream>>>(p->d_fix, reinterpret_cast<const float *>(segs),
+                                                                           static_cast<float *>(out), rowlen);
+    ln.end();
+    return ln.status;
 }
 
 bool plan_wants_tensor_order(const sc_plan *p)

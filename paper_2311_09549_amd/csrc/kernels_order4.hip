@@ -350,8 +350,10 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
-            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 0, nullptr, nullptr, out);   // dedicated matrix-core kernel
-            return ln.status;
+            void *partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
+            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 0, nullptr, nullptr, out, partials);   // dedicated matrix-core kernel
+            if (ln.status != SC_OK) return ln.status;
+            return launch_fixup(p, ln, ws, out);
         } else {
             ln.begin("ttmc4_fused_valu");
             order4_kernel<T, N, M, 0, 1><<<ntiles, NT, lds, stream>>>(a);
@@ -364,9 +366,9 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 1, static_cast<T *>(a.T2), M * N);
         ln.end();
         if (mfma) {
-            st = launch_ttmc4_mfma(p, ln, sp, fac, 1, a.T1, a.T2, out);
+            st = launch_ttmc4_mfma(p, ln, sp, fac, 1, a.T1, a.T2, out, nullptr);
             if (st != SC_OK) return st;
-            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 2, a.T1, a.T2, out);
+            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 2, a.T1, a.T2, out, nullptr);
             return ln.status;
         }
         ln.begin("ttmc4_middle");

@@ -37,6 +37,7 @@ struct Ttmc3Args {
     int64_t ldC, ldD;
     const float *T;   // FISSIONED consumer: the materialised temporary, one 16-wide row per fiber
     float *A;
+    float *partials;   // deterministic schedules: slots for the pieces of rows that span tiles (runs are single tiles then), else null
     int32_t tn, ta, tb;
     int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
 };
@@ -262,6 +263,11 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
             float *dst = a.A + (int64_t)uni(crdb_s[ls]) * 256 + lane * 4;
             if (!atomic) {
                 *reinterpret_cast<t3_floatx4 *>(dst) = v;
+            } else if (a.partials) {
+                // deterministic: this tile's piece of the row goes to its slot (a tile whose only
+                // slice continues on both sides has one piece, numbered as its first)
+                const int slot = (ls == 0 && in_f) ? t.pad[0] : t.pad[1];
+                *reinterpret_cast<t3_floatx4 *>(a.partials + (int64_t)slot * 256 + lane * 4) = v;
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) atomic_add(dst + r, v[r]);
@@ -304,7 +310,8 @@ bool ttmc3_mfma_caps_ok(const sc_plan *p)
     return p->caps.tn <= T3_MAXR * NT && p->caps.ta + 1 <= T3_MAXB * NT && p->caps.ta <= NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
 }
 
-sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out)
+sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
+                            void *partials)
 {
     // T == nullptr: FUSED schedule; otherwise the consumer kernel of the FISSIONED schedule
     const int ntiles = (int)p->tiles.size();
@@ -326,7 +333,9 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     const int fit = lds_workgroups_per_cu(lds);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
-    const int want = std::min(ntiles, 256 * per_cu);
+    // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
+    const int want = partials ? ntiles : std::min(ntiles, 256 * per_cu);
+    a.partials = static_cast<float *>(partials);
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
     const int blocks = (ntiles + a.run - 1) / a.run;

@@ -34,6 +34,7 @@ struct Ttmc4Args {
     const float *T1;   // MODE 1: materialised T1, one 8-wide row per f3 fiber
     float *T2;         // MODE 1 writes, MODE 2 reads: one 64-wide row per f2 fiber
     float *A;
+    float *partials;   // deterministic schedules: slots for the pieces of rows that span tiles (runs are single tiles then), else null
     int32_t L;
     int32_t tn, ta, tb;
     int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
@@ -349,6 +350,11 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                 float *dst = a.A + (int64_t)uni(crdc_s[ls]) * rowA + col * T4_W2 + wave * 16 + 4 * kk;
                 if (!atomic) {
                     *reinterpret_cast<t4_floatx4 *>(dst) = v;
+                } else if (a.partials) {
+                    // deterministic: this tile's piece of the row goes to its slot (a tile whose only
+                    // slice continues on both sides has one piece, numbered as its first)
+                    const int slot = (ls == 0 && in_f) ? t.pad[0] : t.pad[1];
+                    *reinterpret_cast<t4_floatx4 *>(a.partials + (int64_t)slot * rowA + col * T4_W2 + wave * 16 + 4 * kk) = v;
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) atomic_add(dst + r, v[r]);
@@ -401,7 +407,7 @@ bool ttmc4_mfma_caps_ok(const sc_plan *p)
 }
 
 sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
-                            void *T2, void *out)
+                            void *T2, void *out, void *partials)
 {
     // mode 0: FUSED schedule; 1: T1 -> T2 and 2: T2 -> A of the FISSIONED schedule
     const int ntiles = (int)p->tiles.size();
@@ -428,7 +434,9 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     const int fit = lds_workgroups_per_cu(lds);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
-    const int want = std::min(ntiles, 256 * per_cu);
+    // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
+    const int want = partials ? ntiles : std::min(ntiles, 256 * per_cu);
+    a.partials = static_cast<float *>(partials);
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
     const int blocks = (ntiles + a.run - 1) / a.run;

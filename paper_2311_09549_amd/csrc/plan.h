@@ -43,6 +43,20 @@ struct TileCaps {
 
 constexpr int kMaxLaunches = 8;
 
+// Deterministic schedules: an output row whose slice spans several tiles is not updated with
+// atomics; every tile stores its piece of the row in a slot of the workspace (the two slot
+// numbers of a tile are in TileRec::pad[0] / pad[1], -1 = none; the pieces of one row occupy
+// consecutive slots in tile order) and two last kernels add the pieces of each row in that
+// order: first in segments of kFixSegment pieces (many workgroups per heavy row), then the
+// segment sums.  Both are described by the same record.
+struct FixRec {
+    int32_t row;     // destination row: segment number (first pass) or coordinate of the slice (second pass)
+    int32_t first;   // first source row: slot (first pass) or segment (second pass)
+    int32_t count;   // number of source rows
+    int32_t pad;
+};
+constexpr int kFixSegment = 64;
+
 struct Intermediate {
     std::string name;   // e.g. "T(i,j,m)"
     size_t offset = 0;  // byte offset inside the workspace (FISSIONED only)
@@ -75,6 +89,14 @@ struct sc_plan {
     bool has_device = false;
 
     size_t ws_bytes = 0;
+    bool deterministic = false;
+    std::vector<sck::FixRec> fix;     // rows spanning several tiles (deterministic schedules only): second pass
+    std::vector<sck::FixRec> segs;    // their pieces in segments: first pass
+    sck::FixRec *d_fix = nullptr;     // plan-owned device copies
+    sck::FixRec *d_segs = nullptr;
+    int64_t n_slots = 0;              // pieces in the workspace
+    size_t det_offset = 0;            // byte offset of the slots inside the workspace
+    size_t seg_offset = 0;            // byte offset of the segment sums
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 
@@ -103,6 +125,10 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 // True when the plan's kernels walk contiguous runs of tiles and therefore want the device tile
 // table in tensor order rather than interleaved.
 bool plan_wants_tensor_order(const sc_plan *plan);
+
+// True when the kernels of the plan can run without floating-point atomics (FUSED schedules of
+// the kernels that emit one piece per tile and shared row).
+bool plan_supports_deterministic(const sc_plan *plan);
 
 // Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
 size_t lds_bytes_needed(const sc_plan *plan);

@@ -1,0 +1,49 @@
+"""GPU checks of the deterministic schedules: the result meets the same parity bar as the
+atomic schedules, two executions of one plan and two plans of one problem give bit-identical
+outputs, and rows that span many tiles (one heavy slice) are summed correctly."""
+import numpy as np
+import pytest
+
+from paper_2311_09549_amd import binding as sc
+from paper_2311_09549_amd import synth
+from paper_2311_09549_amd.driver import Contraction
+
+from helpers import assert_parity
+from test_gpu_parity_edges import _case
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_twice(cfg, data):
+    outs = []
+    for _ in range(2):   # two plans, two executions each
+        con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                          sc.schedule("fused", deterministic=True), synth.output_shape(cfg))
+        con.run()
+        outs.append(con.result().copy())
+        con.out.fill_(float("nan"))
+        con.run()
+        outs.append(con.result().copy())
+    return outs
+
+
+@pytest.mark.parametrize("cid,scale", [(2, 0.004), (2, 0.02), (3, 0.003), (3, 0.01), (5, 0.004)])
+def test_deterministic_parity_and_repeatability(oracle, cid, scale):
+    cfg = synth.config(cid, scale)
+    data = synth.generate(cfg)
+    print(f"config {cid} scale {scale} deterministic nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data)
+    assert_parity(oracle, cfg, data, outs[0])
+    for o in outs[1:]:
+        assert o.tobytes() == outs[0].tobytes()
+
+
+@pytest.mark.parametrize("name", ["one_slice", "one_fiber", "count_3072", "single"])
+@pytest.mark.parametrize("kind", ["mttkrp3", "ttmc3", "ttmc4"])
+def test_deterministic_degenerate_structures(oracle, kind, name):
+    cfg, data = _case(kind, name)
+    print(f"{kind} {name} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data)
+    assert_parity(oracle, cfg, data, outs[0])
+    for o in outs[1:]:
+        assert o.tobytes() == outs[0].tobytes()

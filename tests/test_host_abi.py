@@ -148,7 +148,7 @@ def test_expression_family():
     assert _status(sc.plan_create, cfg["expr"], csf, [f[1], f[0]], ok) == "SC_ERR_SHAPE_MISMATCH"   # rows != dims
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0].astype(np.float64), f[1]], ok) == "SC_ERR_BAD_DTYPE"
     assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("linear")) == "SC_ERR_SCHED_UNSUPPORTED"
-    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("fused", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("fissioned", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
     odd = np.ones((cfg["dims"][2], 12), np.float32)   # a rank no kernel is instantiated for
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0], odd], ok) == "SC_ERR_SCHED_UNSUPPORTED"
 
@@ -289,3 +289,42 @@ def test_built_in_tile_caps_fit_every_supported_rank(cid, dtype, ranks, which):
     csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
     plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule(which))
     assert sc.plan_tile_count(plan) > 0
+
+
+@pytest.mark.parametrize("cid,scale", [(2, 0.004), (3, 0.003), (5, 0.004)])
+def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scale):
+    """Host side of the deterministic schedules: slots are consecutive per row, in tile order,
+    and the workspace holds exactly the pieces."""
+    cfg, data, csf = _small(cid, scale)
+    plain = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+    det = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused", deterministic=True))
+    assert sc.plan_tile_count(det) == sc.plan_tile_count(plain)
+    assert sc.plan_workspace_bytes(plain) == 0
+    text = sc.plan_describe(det)
+    assert "deterministic:" in text
+    rows, pieces = (int(x) for x in re.search(r"deterministic: (\d+) output rows span several tiles; their (\d+) pieces", text).groups())
+    # count them again from the tile table: a tile's first top-level node continues from the
+    # previous tile (one piece), its last continues into the next (one piece, unless it is that same node)
+    in_bit, out_bit, ntop_i = (16, 32, 7) if cfg["kind"] == "ttmc4" else (4, 8, 5)
+    want_pieces = want_rows = 0
+    for i in range(sc.plan_tile_count(det)):
+        rec = sc.plan_tile(det, i)
+        fl, ntop = rec[8], rec[ntop_i]
+        if fl & in_bit:
+            want_pieces += 1
+        if (fl & out_bit) and not ((fl & in_bit) and ntop == 1):
+            want_pieces += 1
+            want_rows += 1
+    assert (rows, pieces) == (want_rows, want_pieces) and pieces >= 2 * rows > 0
+    elem = 8 if cfg["dtype"] == "f64" else 4
+    row_bytes = int(np.prod(synth.output_shape(cfg)[1:])) * elem
+    segments = int(re.search(r"\((\d+) segments of at most 64\)", text).group(1))
+    assert rows <= segments <= rows + pieces // 64
+    # the pieces, then (256-byte aligned) one partial sum per segment
+    assert sc.plan_workspace_bytes(det) == ((pieces * row_bytes + 255) & ~255) + segments * row_bytes
+
+
+def test_deterministic_is_refused_where_no_kernel_provides_it():
+    for cid, scale, which in [(1, 1.0, "fused"), (4, 0.003, "fused"), (2, 0.004, "fissioned")]:
+        cfg, data, csf = _small(cid, scale)
+        assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
