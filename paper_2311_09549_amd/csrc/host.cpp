@@ -379,17 +379,17 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
 }
 
 // Deterministic schedules: numbers the pieces of every output row that spans several tiles
-// (consecutive slots in tile order) and lists those rows.  The top level is "b" for order 3
-// and "c" for order 4; its flag bits say whether the tile's first / last slice continues
+// (consecutive slots in tile order) and lists those rows.  The top level is "a" for order 2, "b"
+// for order 3 and "c" for order 4; its flag bits say whether the tile's first / last slice continues
 // from the previous / into the next tile.  A tile whose only slice does both holds one piece.
 void assign_piece_slots(sc_plan *p, const HostCsf &h)
 {
-    const bool o4 = p->order == 4;
-    const int32_t in_bit = o4 ? 16 : 4, out_bit = o4 ? 32 : 8;
+    const bool o4 = p->order == 4, o2 = p->order == 2;
+    const int32_t in_bit = o4 ? 16 : o2 ? 1 : 4, out_bit = o4 ? 32 : o2 ? 2 : 8;
     int32_t next = 0;
     p->fix.clear();
     for (TileRec &t : p->tiles) {
-        const int32_t top0 = o4 ? t.c0 : t.b0, ntop = o4 ? t.nc : t.nb;
+        const int32_t top0 = o4 ? t.c0 : o2 ? t.a0 : t.b0, ntop = o4 ? t.nc : o2 ? t.na : t.nb;
         const bool in = (t.flags & in_bit) != 0, out = (t.flags & out_bit) != 0;
         t.pad[0] = t.pad[1] = -1;
         if (in) {   // a piece of the row that the previous tile left open

@@ -911,6 +911,7 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 
 bool plan_supports_deterministic(const sc_plan *p)
 {
+    if (p->kind == K_SDDMM_SPMM) return true;   // both schedules: the sampled values have one writer each
     if (p->sched != SC_SCHED_FUSED) return false;
     return p->kind == K_MTTKRP3 || plan_wants_tensor_order(p);
 }

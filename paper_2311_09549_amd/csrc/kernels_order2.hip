@@ -24,6 +24,7 @@ struct Order2Args {
     int64_t ldX, ldY, ldZ;
     void *T;   // sampled values, one per stored entry (MODE 1 writes, MODE 2 reads)
     void *A;
+    void *partials;   // deterministic schedules: slots for the pieces of rows that span tiles, else null
     int32_t tn, ta;
 };
 
@@ -138,29 +139,41 @@ __global__ void __launch_bounds__(NT) sddmm_spmm_kernel(Order2Args a)
         T *dst = A + (int64_t)crda_s[lr] * W + li * VEC;
         if (!row_shared(lr)) {
             *reinterpret_cast<P *>(dst) = row;
+        } else if (a.partials) {
+            // deterministic: the tile's one piece of this row goes to its slot (a tile whose only
+            // row continues on both sides has one piece, numbered as its first)
+            const int slot = (lr == 0 && (t.flags & 1)) ? t.pad[0] : t.pad[1];
+            *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
         }
     };
 
+    // A lane group whose chunk starts inside a row keeps that row's piece ("head") in registers
+    // when the row ends; a chunk that ends inside a row parks its running sum ("tail") in its
+    // LDS row together with a flag telling whether the row began in this chunk.  After the
+    // barrier the group holding a head adds the tails of the chunks before it, back to the one
+    // in which the row began, and issues the tile's single update of that output row: no LDS
+    // atomics, and a fixed order of additions.
     const int gs = g * q, ge = min(gs + q, nchild);
+    int head_lr = -1;
+    P headv;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) headv.v[i] = T(0);
     if (gs < ge) {
         bool started = (gs == 0) || (end_s[pidx(gs - 1)] >= 0);  // the current row starts in this chunk
         Acc asum;
         asum.clear();
         auto emit = [&](int lr, bool whole) {
-            if (whole) {
-                P o;
+            P o;
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            if (whole) {
                 direct(lr, o);
             } else {
-                const int slot = ba_s[lr] / q;
-                T *dst = slot_s + slot * W + li * VEC;
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, asum.v[i]);
-                if (li == 0) slot_id[slot] = lr;
+                headv = o;
+                head_lr = lr;
             }
         };
         for (int c = gs; c < ge; c += U) {
@@ -204,15 +217,25 @@ __global__ void __launch_bounds__(NT) sddmm_spmm_kernel(Order2Args a)
                 }
             }
         }
-        if (MODE != 1) {
-            const int cs = chunk_ls[g];
-            if (cs >= 0) emit(cs, false);  // the chunk ends inside a row
+        if (MODE != 1 && chunk_ls[g] >= 0) {  // the chunk ends inside a row: park the tail
+            P o;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) o.v[i] = asum.v[i];
+            *reinterpret_cast<P *>(slot_s + g * W + li * VEC) = o;
+            if (li == 0) slot_id[g] = started ? 1 : 0;
         }
     }
     if (MODE == 1) return;
     __syncthreads();
-    const int lr = slot_id[g];
-    if (lr >= 0) direct(lr, *reinterpret_cast<const P *>(slot_s + g * W + li * VEC));
+    if (head_lr >= 0) {
+        for (int h = g - 1; h >= 0; --h) {
+            const P tl = *reinterpret_cast<const P *>(slot_s + h * W + li * VEC);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) headv.v[i] += tl.v[i];
+            if (slot_id[h] != 0) break;   // the row began in chunk h
+        }
+        direct(head_lr, headv);
+    }
 }
 
 namespace {
@@ -236,6 +259,7 @@ sc_status run_order2(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.Z = fac[2].data; a.ldZ = fac[2].ld;
     a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
     a.A = out;
+    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta;
     const size_t lds = order2_lds_bytes<T>(a.tn, a.ta);
     if (p->sched == SC_SCHED_FUSED) {
@@ -250,7 +274,7 @@ sc_status run_order2(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         sddmm_spmm_kernel<T, W, 2><<<ntiles, NT, lds, stream>>>(a);
         ln.end();
     }
-    return ln.status;
+    return launch_fixup(p, ln, ws, out);
 }
 
 template <typename T>

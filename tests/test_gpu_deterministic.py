@@ -14,11 +14,11 @@ from test_gpu_parity_edges import _case
 pytestmark = pytest.mark.gpu
 
 
-def _run_twice(cfg, data):
+def _run_twice(cfg, data, which="fused"):
     outs = []
     for _ in range(2):   # two plans, two executions each
         con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
-                          sc.schedule("fused", deterministic=True), synth.output_shape(cfg))
+                          sc.schedule(which, deterministic=True), synth.output_shape(cfg))
         con.run()
         outs.append(con.result().copy())
         con.out.fill_(float("nan"))
@@ -27,19 +27,20 @@ def _run_twice(cfg, data):
     return outs
 
 
-@pytest.mark.parametrize("cid,scale", [(2, 0.004), (2, 0.02), (3, 0.003), (3, 0.01), (5, 0.004)])
-def test_deterministic_parity_and_repeatability(oracle, cid, scale):
+@pytest.mark.parametrize("cid,scale,which", [(2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
+                                             (4, 0.003, "fused"), (4, 0.01, "fissioned"), (5, 0.004, "fused")])
+def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
     cfg = synth.config(cid, scale)
     data = synth.generate(cfg)
-    print(f"config {cid} scale {scale} deterministic nnz={cfg['nnz']}", flush=True)
-    outs = _run_twice(cfg, data)
+    print(f"config {cid} scale {scale} {which} deterministic nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data, which)
     assert_parity(oracle, cfg, data, outs[0])
     for o in outs[1:]:
         assert o.tobytes() == outs[0].tobytes()
 
 
 @pytest.mark.parametrize("name", ["one_slice", "one_fiber", "count_3072", "single"])
-@pytest.mark.parametrize("kind", ["mttkrp3", "ttmc3", "ttmc4"])
+@pytest.mark.parametrize("kind", ["mttkrp3", "ttmc3", "sddmm_spmm", "ttmc4"])
 def test_deterministic_degenerate_structures(oracle, kind, name):
     cfg, data = _case(kind, name)
     print(f"{kind} {name} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)

@@ -69,7 +69,7 @@ def test_parity_full(oracle, cid, n_heavy, n_random, which):
     del con
 
 
-@pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000), (5, 10, 500)])
+@pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000), (4, None, None), (5, 10, 500)])
 def test_parity_full_deterministic(oracle, cid, n_heavy, n_random):
     """The deterministic FUSED schedules at full size: same bar, and a second execution of the
     plan reproduces the first bit for bit (the heaviest slices span thousands of tiles)."""

@@ -291,7 +291,7 @@ def test_built_in_tile_caps_fit_every_supported_rank(cid, dtype, ranks, which):
     assert sc.plan_tile_count(plan) > 0
 
 
-@pytest.mark.parametrize("cid,scale", [(2, 0.004), (3, 0.003), (5, 0.004)])
+@pytest.mark.parametrize("cid,scale", [(2, 0.004), (3, 0.003), (4, 0.003), (5, 0.004)])
 def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scale):
     """Host side of the deterministic schedules: slots are consecutive per row, in tile order,
     and the workspace holds exactly the pieces."""
@@ -305,7 +305,7 @@ def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scal
     rows, pieces = (int(x) for x in re.search(r"deterministic: (\d+) output rows span several tiles; their (\d+) pieces", text).groups())
     # count them again from the tile table: a tile's first top-level node continues from the
     # previous tile (one piece), its last continues into the next (one piece, unless it is that same node)
-    in_bit, out_bit, ntop_i = (16, 32, 7) if cfg["kind"] == "ttmc4" else (4, 8, 5)
+    in_bit, out_bit, ntop_i = {"ttmc4": (16, 32, 7), "sddmm_spmm": (1, 2, 3)}.get(cfg["kind"], (4, 8, 5))
     want_pieces = want_rows = 0
     for i in range(sc.plan_tile_count(det)):
         rec = sc.plan_tile(det, i)
@@ -325,6 +325,6 @@ def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scal
 
 
 def test_deterministic_is_refused_where_no_kernel_provides_it():
-    for cid, scale, which in [(1, 1.0, "fused"), (4, 0.003, "fused"), (2, 0.004, "fissioned")]:
+    for cid, scale, which in [(1, 1.0, "fused"), (3, 0.003, "fissioned"), (2, 0.004, "fissioned"), (5, 0.004, "fissioned")]:
         cfg, data, csf = _small(cid, scale)
         assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
