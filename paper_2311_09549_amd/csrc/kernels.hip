@@ -370,7 +370,9 @@ __host__ __device__ constexpr size_t mttkrp_lds_bytes(int W, int tn, int ta, int
     return (size_t)NT * 16 + (size_t)pn * (sizeof(T) + 8) + (size_t)((tn + 8 + 31) / 32 + 1) * 4 + (size_t)(2 * tb + 4 * groups) * 4 + 64;
 }
 
-template <typename T, int W>
+// DET: the deterministic variant (pieces of rows that span tiles go to plan-numbered slots).  A
+// separate instantiation, so that the atomic variant keeps its 64 registers (8 waves per SIMD).
+template <typename T, int W, bool DET>
 __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
 {
     constexpr int VEC = VecWidth<T>::value;
@@ -482,7 +484,7 @@ __global__ void __launch_bounds__(NT) mttkrp3_fused_kernel(Order3Args a)
         T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
         if (!slice_shared(ls)) {
             *reinterpret_cast<P *>(dst) = row;
-        } else if (a.partials) {
+        } else if (DET) {
             // deterministic: the tile's one piece of this row goes to its slot (a tile whose only
             // slice continues on both sides has one piece, numbered as its first)
             const int slot = (ls == 0 && (t.flags & 4)) ? t.pad[0] : t.pad[1];
@@ -822,7 +824,10 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
             ln.begin("mttkrp3_fused");
-            mttkrp3_fused_kernel<T, W><<<ntiles, NT, mttkrp_lds_bytes<T>(W, a.tn, a.ta, a.tb), stream>>>(a);
+            if (a.partials)
+                mttkrp3_fused_kernel<T, W, true><<<ntiles, NT, mttkrp_lds_bytes<T>(W, a.tn, a.ta, a.tb), stream>>>(a);
+            else
+                mttkrp3_fused_kernel<T, W, false><<<ntiles, NT, mttkrp_lds_bytes<T>(W, a.tn, a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
             ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out, a.partials);
             if (ln.status != SC_OK) return ln.status;

@@ -70,7 +70,9 @@ __host__ __device__ constexpr size_t ttmc3_lds_bytes(int tn, int ta, int tb)
 
 typedef float t3_floatx4 __attribute__((ext_vector_type(4)));
 
-template <bool FUSED>
+// DET: the deterministic variant (pieces of rows that span tiles go to plan-numbered slots), a
+// separate instantiation so that the atomic variant keeps its register budget.
+template <bool FUSED, bool DET>
 __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
 {
     constexpr int U = 8;
@@ -263,7 +265,7 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
             float *dst = a.A + (int64_t)uni(crdb_s[ls]) * 256 + lane * 4;
             if (!atomic) {
                 *reinterpret_cast<t3_floatx4 *>(dst) = v;
-            } else if (a.partials) {
+            } else if (DET) {
                 // deterministic: this tile's piece of the row goes to its slot (a tile whose only
                 // slice continues on both sides has one piece, numbered as its first)
                 const int slot = (ls == 0 && in_f) ? t.pad[0] : t.pad[1];
@@ -341,10 +343,13 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     const int blocks = (ntiles + a.run - 1) / a.run;
     if (T == nullptr) {
         ln.begin("ttmc3_fused_mfma");
-        ttmc3_mfma_kernel<true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        if (partials)
+            ttmc3_mfma_kernel<true, true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        else
+            ttmc3_mfma_kernel<true, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else {
         ln.begin("ttmc3_consume_mfma");
-        ttmc3_mfma_kernel<false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        ttmc3_mfma_kernel<false, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     }
     ln.end();
     return ln.status;

@@ -77,7 +77,8 @@ __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb, int
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
 
-template <int MODE>
+// DET: the deterministic variant of MODE 0 (pieces of rows that span tiles go to plan-numbered slots).
+template <int MODE, bool DET>
 __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileRec *__restrict__ tiles)
 {
     using P = Pack<float, 4>;
@@ -350,7 +351,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                 float *dst = a.A + (int64_t)uni(crdc_s[ls]) * rowA + col * T4_W2 + wave * 16 + 4 * kk;
                 if (!atomic) {
                     *reinterpret_cast<t4_floatx4 *>(dst) = v;
-                } else if (a.partials) {
+                } else if (DET) {
                     // deterministic: this tile's piece of the row goes to its slot (a tile whose only
                     // slice continues on both sides has one piece, numbered as its first)
                     const int slot = (ls == 0 && in_f) ? t.pad[0] : t.pad[1];
@@ -442,13 +443,16 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     const int blocks = (ntiles + a.run - 1) / a.run;
     if (mode == 0) {
         ln.begin("ttmc4_fused_mfma");
-        ttmc4_mfma_kernel<0><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        if (partials)
+            ttmc4_mfma_kernel<0, true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        else
+            ttmc4_mfma_kernel<0, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else if (mode == 1) {
         ln.begin("ttmc4_middle");
-        ttmc4_mfma_kernel<1><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        ttmc4_mfma_kernel<1, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else {
         ln.begin("ttmc4_consume_mfma");
-        ttmc4_mfma_kernel<2><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        ttmc4_mfma_kernel<2, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     }
     ln.end();
     return ln.status;
