@@ -4,8 +4,9 @@
 // together with the CSF nodes above them (plan.h, TileRec).  Tiles are cut at plan time so
 // that each holds about the same number of nonzeros whatever the slice / fiber lengths;
 // heavy slices and fibers are therefore split across workgroups, and the pieces are
-// recombined at the end (LDS atomics inside a workgroup, one global atomic per tile on
-// pre-zeroed output rows between workgroups).
+// recombined at the end (inside a workgroup: parked in LDS and added by one owner in a fixed
+// order; between workgroups: atomic adds on pre-zeroed output rows, or plan-numbered slots
+// added by a last kernel under a deterministic schedule).
 //
 // Inside a tile the nests of Table 2 run as a chain of segmented reductions, one per CSF
 // level, each of the form
@@ -27,17 +28,15 @@ namespace sck {
 // Order-3 kernels:  T(f, x) = sum_{k' in fiber f} B * D(k, x)   then
 //   hadamard:  A(i, r)    += C(j, r) * T(f, r)                      (MTTKRP)
 //   outer:     A(i, l, m) += C(j, l) * T(f, m)                      (kernel 6 of Table 2)
-// MODE 0: fused (T lives in LDS for the tile)      -- FUSED schedule
-// MODE 1: producer only, T written to HBM          -- FISSIONED, first kernel
-// MODE 2: consumer only, T read back from HBM      -- FISSIONED, second kernel
-// CONS 0: hadamard; 1: outer product on the vector ALU (any L); 2: outer product on MFMA
-//         (fp32, L = W = 16)
-//
-// Output rows: a slice that lies entirely inside one lane group's chunk (or wave's chunk
-// for MFMA) and inside the tile is written with plain stores.  Pieces of a slice that is
-// split between lane groups are first summed in an LDS "slot" (one per lane group, keyed
-// by the group in which the slice starts), so that a tile issues at most one global
-// update per slice; that update is an atomic add if the slice is shared with another tile.
+// The MTTKRP and the fp32 16 x 16 outer product have kernels of their own (below and in
+// kernels_ttmc3.hip); order3_kernel is the general outer-product kernel for every other rank
+// and for fp64:
+//   MODE 0: fused (T lives in LDS for the tile)      -- FUSED schedule
+//   MODE 2: consumer only, T read back from HBM      -- FISSIONED, second kernel (the first is
+//           the leaf traversal of kernels_traverse.hip)
+// Its consumer gives every thread a set of output elements (l, m) and lets it run over the
+// tile's slices and fibers in order: one global update per tile, slice and element, an atomic
+// add if the slice is shared with another tile.
 // ------------------------------------------------------------------------------------------
 struct Order3Args {
     const TileRec *tiles;
@@ -47,7 +46,7 @@ struct Order3Args {
     const void *D;  // factor on mode 2 (rows = K)
     int64_t ldC, ldD;
     int32_t L;      // columns of C (outer only)
-    void *T;        // temporary rows (MODE 1 writes, MODE 2 reads)
+    void *T;        // temporary rows (the traversal kernel writes them, the consumers read them)
     void *A;
     void *partials; // deterministic schedules: slots for the pieces of rows that span tiles, else null
     int32_t tn, ta, tb;  // caps used to carve LDS
@@ -56,12 +55,10 @@ struct Order3Args {
 template <typename T>
 __host__ __device__ constexpr size_t order3_lds_bytes(int W, int tn, int ta)
 {
-    return (size_t)ta * W * sizeof(T) + (size_t)NT * 16 + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + NT * 4 + 64;
+    return (size_t)ta * W * sizeof(T) + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + 64;
 }
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-template <typename T, int W, int MODE, int CONS>
+template <typename T, int W, int MODE>
 __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 {
     constexpr int VEC = VecWidth<T>::value;
@@ -73,14 +70,12 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     T *T_s = reinterpret_cast<T *>(smem);                   // ta * W
-    T *slot_s = T_s + (size_t)a.ta * W;                     // NT * VEC  (16 bytes per thread)
-    T *val_s = slot_s + NT * VEC;                           // padded(tn)
+    T *val_s = T_s + (size_t)a.ta * W;                      // padded(tn)
     int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
     int *ba_s = crd_s + padded(a.tn);    // ta + 2
     int *crda_s = ba_s + a.ta + 2;       // ta
     int *bb_s = crda_s + a.ta;           // ta + 2
     int *crdb_s = bb_s + a.ta + 2;       // ta
-    int *slot_id = crdb_s + a.ta;        // up to NT
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
@@ -100,7 +95,7 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
         }
         if (tid == 0) ba_s[na + 1] = INT_MAX;
     }
-    if (MODE != 1) {
+    {
         for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
         for (int i = tid; i <= nb; i += NT) {
             const int b = a.pos2[t.b0 + i];
@@ -113,11 +108,6 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
             if (MODE == 2 && (t.flags & 1)) bb_s[0] = 1;
         }
         for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
-        P z;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
-        reinterpret_cast<P *>(slot_s)[tid] = z;
-        slot_id[tid] = -1;
     }
     if (MODE == 2) {
         const P *Tg = reinterpret_cast<const P *>(static_cast<const T *>(a.T) + (int64_t)t.a0 * W);
@@ -164,23 +154,6 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
         __syncthreads();
     }
 
-    if (MODE == 1) {
-        // write the tile's rows of T; rows shared with a neighbouring tile are added atomically
-        T *Tg = static_cast<T *>(a.T) + (int64_t)t.a0 * W;
-        for (int i = tid; i < na * LG; i += NT) {
-            const int lf = i / LG;
-            const bool shared = (lf == 0 && (t.flags & 1)) || (lf == na - 1 && (t.flags & 2));
-            const P v = reinterpret_cast<const P *>(T_s)[i];
-            if (!shared) {
-                reinterpret_cast<P *>(Tg)[i] = v;
-            } else {
-#pragma unroll
-                for (int x = 0; x < VEC; ++x) atomic_add(Tg + (int64_t)i * VEC + x, v.v[x]);
-            }
-        }
-        return;
-    }
-
     // ---- consumer: T_s -> A ----
     // In the consumer-only kernel a fiber that continues from the previous tile belongs to
     // the tile it starts in; skip it here.
@@ -189,50 +162,7 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     T *A = static_cast<T *>(a.A);
     auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
 
-    if (CONS == 0) {
-        const int nfib = na - cf0;
-        const int q = max((nfib + G - 1) / G, 1);
-        const int gs = cf0 + g * q, ge = min(gs + q, na);
-        auto direct = [&](int ls, const P &row) {
-            T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
-            if (!slice_shared(ls)) {
-                *reinterpret_cast<P *>(dst) = row;
-            } else {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
-            }
-        };
-        struct Item { P c; P tt; };
-        seg_walk<4, Acc, Item>(
-            gs, ge, bb_s, nb,
-            [&](int lf) {
-                Item it;
-                it.c = *reinterpret_cast<const P *>(C + (int64_t)crda_s[lf] * a.ldC + li * VEC);
-                it.tt = *reinterpret_cast<const P *>(T_s + lf * W + li * VEC);
-                return it;
-            },
-            [&](Acc &acc, const Item &it) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc.v[i] += it.c.v[i] * it.tt.v[i];
-            },
-            [&](int ls, const Acc &acc, bool whole) {
-                if (whole) {
-                    P o;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) o.v[i] = acc.v[i];
-                    direct(ls, o);
-                } else {
-                    const int slot = (max(bb_s[ls], cf0) - cf0) / q;
-                    T *dst = slot_s + slot * W + li * VEC;
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) atomic_add(dst + i, acc.v[i]);
-                    if (li == 0) slot_id[slot] = ls;
-                }
-            });
-        __syncthreads();
-        const int ls = slot_id[g];
-        if (ls >= 0) direct(ls, *reinterpret_cast<const P *>(slot_s + g * W + li * VEC));
-    } else if (CONS == 1) {
+    {
         // generic outer product on the vector ALU: every thread owns output elements (l, m)
         // and runs over the tile's slices and fibers in order
         const int L = a.L;
@@ -245,91 +175,6 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
                 for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crda_s[lf] * a.ldC + l] * T_s[lf * W + m];
                 T *dst = A + (int64_t)crdb_s[ls] * L * W + e;
                 if (!slice_shared(ls)) *dst = acc; else atomic_add(dst, acc);
-            }
-        }
-    } else {
-        // MFMA outer product, fp32, L = W = 16:  A(i, 16x16) += Csel^T (16 x Kf) * T (Kf x 16),
-        // Kf = fibers of the slice, four fibers per v_mfma_f32_16x16x4_f32.
-        if constexpr (sizeof(T) == 4 && W == 16) {
-            const int wave = tid / 64, lane = tid % 64;
-            const int nfib = na - cf0;
-            const int qf = max((((nfib + 3) / 4) + 3) / 4 * 4, 4);  // fibers per wave, multiple of 4
-            const int ws = cf0 + wave * qf, we = min(ws + qf, na);
-            float *Af = reinterpret_cast<float *>(A);
-            float *slotf = reinterpret_cast<float *>(slot_s);
-            if (ws < we) {
-                const int kk = lane / 16, col = lane % 16;
-                int ls = find_segment(bb_s, nb, ws);
-                int send = bb_s[ls + 1];
-                bool whole = bb_s[ls] >= ws;
-                floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                auto emit = [&](int s, bool wh) {
-                    if (wh) {
-                        float *dst = Af + (int64_t)crdb_s[s] * 256 + col;
-                        if (!slice_shared(s)) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) dst[(4 * kk + r) * 16] = acc[r];
-                        } else {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) atomic_add(dst + (4 * kk + r) * 16, acc[r]);
-                        }
-                    } else {
-                        const int slot = (max(bb_s[s], cf0) - cf0) / qf;
-                        float *dst = slotf + slot * 256 + col;
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) atomic_add(dst + (4 * kk + r) * 16, acc[r]);
-                        if (lane == 0) slot_id[slot] = s;
-                    }
-                };
-                constexpr int UB = 4;  // 4-fiber blocks whose operand gathers are issued together
-                for (int fb0 = ws; fb0 < we; fb0 += 4 * UB) {
-                    float cvs[UB], tvs[UB];
-#pragma unroll
-                    for (int ub = 0; ub < UB; ++ub) {
-                        // lanes past the chunk end read a valid fiber; they are masked below
-                        const int lfc = min(fb0 + 4 * ub + kk, we - 1);
-                        cvs[ub] = reinterpret_cast<const float *>(C)[(int64_t)crda_s[lfc] * a.ldC + col];
-                        tvs[ub] = reinterpret_cast<const float *>(T_s)[lfc * 16 + col];
-                    }
-#pragma unroll
-                    for (int ub = 0; ub < UB; ++ub) {
-                        const int fb = fb0 + 4 * ub;
-                        if (fb >= we) break;
-                        const int bend = min(fb + 4, we);
-                        const int lf = fb + kk;
-                        const float cv = cvs[ub], tv = tvs[ub];
-                        int from = fb;  // fibers of this block in [from, bend) are not yet consumed
-                        for (;;) {
-                            const int upto = min(send, bend);
-                            const bool mine = lf >= from && lf < upto;
-                            acc = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv : 0.f, acc, 0, 0, 0);
-                            if (send <= bend) {
-                                emit(ls, whole);
-                                acc = floatx4{0.f, 0.f, 0.f, 0.f};
-                                whole = true;
-                                from = send;
-                                ++ls;
-                                send = bb_s[ls + 1];
-                                if (from >= bend) break;
-                            } else {
-                                break;
-                            }
-                        }
-                    }
-                }
-                if (bb_s[ls] < we) emit(ls, false);
-            }
-            __syncthreads();
-            const int s = slot_id[wave];
-            if (s >= 0) {
-                float *dst = Af + (int64_t)crdb_s[s] * 256;
-                const bool sh = slice_shared(s);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int e = lane + 64 * r;
-                    const float v = slotf[wave * 256 + e];
-                    if (!sh) dst[e] = v; else atomic_add(dst + e, v);
-                }
             }
         }
     }
@@ -834,7 +679,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             return launch_fixup(p, ln, ws, out);
         } else {
             ln.begin("ttmc3_fused_valu");
-            order3_kernel<T, W, 0, 1><<<ntiles, NT, lds, stream>>>(a);
+            order3_kernel<T, W, 0><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
         if (had) return launch_fixup(p, ln, ws, out);
@@ -850,7 +695,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             return ln.status;
         } else {
             ln.begin("ttmc3_consume_valu");
-            order3_kernel<T, W, 2, 1><<<ntiles, NT, lds, stream>>>(a);
+            order3_kernel<T, W, 2><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
     }

@@ -5,13 +5,14 @@
 //     T2(f2, m, n) = sum_{f3 in f2} D(k, m) * T1(f3, n)      f2 = (i,j) fiber
 //     A(i, l, m, n) = sum_{f2 in slice i} C(j, l) * T2(f2, m, n)
 //
+// The fp32 case has a matrix-core kernel of its own (kernels_ttmc4.hip); order4_kernel is the
+// general kernel for fp64:
 // MODE 0 (FUSED):      all three stages per tile, T1 and T2 live in LDS.
 // MODE 2 (FISSIONED):  T1 rows (from the workspace) -> T2 rows (to the workspace).
 // MODE 3 (FISSIONED):  T2 rows (from the workspace) -> A.
-// (The first FISSIONED kernel, leaves -> T1, is the order-3 producer with W = N.)
-// CONS 1: last stage on the vector ALU; CONS 2: last stage on MFMA (fp32, L <= 16,
-//         M*N a multiple of 16): A(i, L x MN) += Csel^T (L x Kf) * T2 (Kf x MN), rows padded
-//         to 16, four f2 fibers per v_mfma_f32_16x16x4_f32 and MN/16 column blocks.
+// (The first FISSIONED kernel, leaves -> T1, is the leaf traversal with W = N.)
+// The last stage gives every thread a set of output elements and lets it run over the tile's
+// slices and f2 fibers in order.
 #include "device_common.h"
 
 namespace sck {
@@ -31,13 +32,11 @@ struct Order4Args {
 template <typename T>
 __host__ __device__ constexpr size_t order4_lds_bytes(int N, int W2, int L, int tn, int ta, int tb)
 {
-    return (size_t)ta * N * sizeof(T) + (size_t)tb * W2 * sizeof(T) + (size_t)4 * L * W2 * sizeof(T) +
-           (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(2 * ta + 4 * tb + 16) * 4 + 64;
+    return (size_t)ta * N * sizeof(T) + (size_t)tb * W2 * sizeof(T) + (size_t)padded(tn) * (4 + sizeof(T)) +
+           (size_t)(2 * ta + 4 * tb + 16) * 4 + 64;
 }
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-template <typename T, int N, int M, int MODE, int CONS>
+template <typename T, int N, int M, int MODE>
 __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
 {
     constexpr int VEC = VecWidth<T>::value;
@@ -53,8 +52,7 @@ __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
     const int L = a.L;
     T *T1_s = reinterpret_cast<T *>(smem);              // ta * N
     T *T2_s = T1_s + (size_t)a.ta * N;                  // tb * W2
-    T *slot_s = T2_s + (size_t)a.tb * W2;               // 4 * L * W2
-    T *val_s = slot_s + (size_t)4 * L * W2;             // padded(tn)
+    T *val_s = T2_s + (size_t)a.tb * W2;                // padded(tn)
     int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
     int *ba_s = crd_s + padded(a.tn);   // ta + 2   f3 boundaries (leaf offsets)
     int *crda_s = ba_s + a.ta + 2;      // ta       k of each f3
@@ -62,7 +60,6 @@ __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
     int *crdb_s = bb_s + a.tb + 2;      // tb       j of each f2
     int *bc_s = crdb_s + a.tb;          // tb + 2   slice boundaries (f2 offsets)
     int *crdc_s = bc_s + a.tb + 2;      // tb       i of each slice
-    int *slot_id = crdc_s + a.tb;       // 4
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
@@ -97,8 +94,6 @@ __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
             if (MODE == 3 && (t.flags & 4)) bc_s[0] = 1;   // likewise for f2 fibers in the T2 -> A kernel
         }
         for (int i = tid; i < nc; i += NT) crdc_s[i] = a.crd1[t.c0 + i];
-        for (int i = tid; i < 4 * L * W2; i += NT) slot_s[i] = T(0);
-        if (tid < 4) slot_id[tid] = -1;
     }
     {
         P z;
@@ -210,116 +205,15 @@ __global__ void __launch_bounds__(NT) order4_kernel(Order4Args a)
     const int rowA = L * W2;
     auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 16)) || (ls == nc - 1 && (t.flags & 32)); };
 
-    if (CONS == 1) {
-        for (int e = tid; e < rowA; e += NT) {
-            const int l = e / W2, x = e % W2;
-            for (int ls = 0; ls < nc; ++ls) {
-                const int f0 = max(bc_s[ls], cf0), f1 = bc_s[ls + 1];
-                if (f0 >= f1) continue;
-                T acc = T(0);
-                for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crdb_s[lf] * a.ldC + l] * T2_s[lf * W2 + x];
-                T *dst = A + (int64_t)crdc_s[ls] * rowA + e;
-                if (!slice_shared(ls)) *dst = acc; else atomic_add(dst, acc);
-            }
-        }
-    } else {
-        if constexpr (sizeof(T) == 4 && W2 % 16 == 0) {
-            constexpr int NB = W2 / 16;
-            const int wave = tid / 64, lane = tid % 64;
-            const int nfib = nb - cf0;
-            const int qf = max((((nfib + 3) / 4) + 3) / 4 * 4, 4);
-            const int ws = cf0 + wave * qf, we = min(ws + qf, nb);
-            float *Af = reinterpret_cast<float *>(A);
-            float *slotf = reinterpret_cast<float *>(slot_s);
-            const int kk = lane / 16, col = lane % 16;
-            if (ws < we) {
-                int ls = find_segment(bc_s, nc, ws);
-                int send = bc_s[ls + 1];
-                bool whole = bc_s[ls] >= ws;
-                floatx4 acc[NB];
-#pragma unroll
-                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-                auto emit = [&](int s, bool wh) {
-                    // accumulator rows are the L output rows l = 4*kk + r (rows >= L are padding)
-                    if (wh) {
-                        float *dst = Af + (int64_t)crdc_s[s] * rowA + col;
-                        const bool sh = slice_shared(s);
-#pragma unroll
-                        for (int b = 0; b < NB; ++b)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const int l = 4 * kk + r;
-                                if (l < L) {
-                                    if (!sh) dst[l * W2 + b * 16] = acc[b][r]; else atomic_add(dst + l * W2 + b * 16, acc[b][r]);
-                                }
-                            }
-                    } else {
-                        const int slot = (max(bc_s[s], cf0) - cf0) / qf;
-                        float *dst = slotf + slot * rowA + col;
-#pragma unroll
-                        for (int b = 0; b < NB; ++b)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const int l = 4 * kk + r;
-                                if (l < L) atomic_add(dst + l * W2 + b * 16, acc[b][r]);
-                            }
-                        if (lane == 0) slot_id[slot] = s;
-                    }
-                };
-                constexpr int UB = 4;  // 4-fiber blocks whose C gathers are issued together
-                const int colc = min(col, L - 1);
-                for (int fb0 = ws; fb0 < we; fb0 += 4 * UB) {
-                    float cvs[UB];
-#pragma unroll
-                    for (int ub = 0; ub < UB; ++ub) {
-                        const int lfc = min(fb0 + 4 * ub + kk, we - 1);   // masked below when past the end
-                        cvs[ub] = reinterpret_cast<const float *>(C)[(int64_t)crdb_s[lfc] * a.ldC + colc];
-                    }
-#pragma unroll
-                    for (int ub = 0; ub < UB; ++ub) {
-                        const int fb = fb0 + 4 * ub;
-                        if (fb >= we) break;
-                        const int bend = min(fb + 4, we);
-                        const int lf = fb + kk;
-                        const int lfc = min(lf, we - 1);
-                        const float cv = col < L ? cvs[ub] : 0.f;
-                        float tv[NB];
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) tv[b] = reinterpret_cast<const float *>(T2_s)[lfc * W2 + b * 16 + col];
-                        int from = fb;
-                        for (;;) {
-                            const int upto = min(send, bend);
-                            const bool mine = lf >= from && lf < upto;
-#pragma unroll
-                            for (int b = 0; b < NB; ++b)
-                                acc[b] = __builtin_amdgcn_mfma_f32_16x16x4f32(mine ? cv : 0.f, mine ? tv[b] : 0.f, acc[b], 0, 0, 0);
-                            if (send <= bend) {
-                                emit(ls, whole);
-#pragma unroll
-                                for (int b = 0; b < NB; ++b) acc[b] = floatx4{0.f, 0.f, 0.f, 0.f};
-                                whole = true;
-                                from = send;
-                                ++ls;
-                                send = bc_s[ls + 1];
-                                if (from >= bend) break;
-                            } else {
-                                break;
-                            }
-                        }
-                    }
-                }
-                if (bc_s[ls] < we) emit(ls, false);
-            }
-            __syncthreads();
-            const int s = slot_id[wave];
-            if (s >= 0) {
-                float *dst = Af + (int64_t)crdc_s[s] * rowA;
-                const bool sh = slice_shared(s);
-                for (int e = lane; e < rowA; e += 64) {
-                    const float v = slotf[wave * rowA + e];
-                    if (!sh) dst[e] = v; else atomic_add(dst + e, v);
-                }
-            }
+    for (int e = tid; e < rowA; e += NT) {
+        const int l = e / W2, x = e % W2;
+        for (int ls = 0; ls < nc; ++ls) {
+            const int f0 = max(bc_s[ls], cf0), f1 = bc_s[ls + 1];
+            if (f0 >= f1) continue;
+            T acc = T(0);
+            for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crdb_s[lf] * a.ldC + l] * T2_s[lf * W2 + x];
+            T *dst = A + (int64_t)crdc_s[ls] * rowA + e;
+            if (!slice_shared(ls)) *dst = acc; else atomic_add(dst, acc);
         }
     }
 }
@@ -347,7 +241,7 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.A = out;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order4_lds_bytes<T>(N, M * N, a.L, a.tn, a.ta, a.tb);
-    const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;
+    const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;   // the matrix-core kernel (fp32)
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
             void *partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
@@ -356,7 +250,7 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             return launch_fixup(p, ln, ws, out);
         } else {
             ln.begin("ttmc4_fused_valu");
-            order4_kernel<T, N, M, 0, 1><<<ntiles, NT, lds, stream>>>(a);
+            order4_kernel<T, N, M, 0><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
     } else {
@@ -372,15 +266,10 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             return ln.status;
         }
         ln.begin("ttmc4_middle");
-        order4_kernel<T, N, M, 2, 1><<<ntiles, NT, lds, stream>>>(a);
+        order4_kernel<T, N, M, 2><<<ntiles, NT, lds, stream>>>(a);
         ln.end();
-        if (mfma) {
-            ln.begin("ttmc4_consume_mfma");
-            order4_kernel<T, N, M, 3, 2><<<ntiles, NT, lds, stream>>>(a);
-        } else {
-            ln.begin("ttmc4_consume_valu");
-            order4_kernel<T, N, M, 3, 1><<<ntiles, NT, lds, stream>>>(a);
-        }
+        ln.begin("ttmc4_consume_valu");
+        order4_kernel<T, N, M, 3><<<ntiles, NT, lds, stream>>>(a);
         ln.end();
     }
     return ln.status;
