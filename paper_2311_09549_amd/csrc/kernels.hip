@@ -20,7 +20,7 @@
 // Because every stage is linear in its input, a node that is cut by a chunk or tile
 // boundary is simply treated as two nodes: each piece is pushed through the consumer
 // separately and only the final output rows need recombining.
-#include "device_common.h"
+#include "leaf_walk.h"
 
 namespace sck {
 
@@ -34,9 +34,10 @@ namespace sck {
 //   MODE 0: fused (T lives in LDS for the tile)      -- FUSED schedule
 //   MODE 2: consumer only, T read back from HBM      -- FISSIONED, second kernel (the first is
 //           the leaf traversal of kernels_traverse.hip)
-// Its consumer gives every thread a set of output elements (l, m) and lets it run over the
-// tile's slices and fibers in order: one global update per tile, slice and element, an atomic
-// add if the slice is shared with another tile.
+// Its producer is the shared leaf walk (leaf_walk.h); its consumer gives every thread a set of
+// output elements (l, m) and lets it run over the tile's slices and fibers in order: one
+// global update per tile, slice and element, an atomic add (or, under a deterministic
+// schedule, a store to the tile's slot) if the slice is shared with another tile.
 // ------------------------------------------------------------------------------------------
 struct Order3Args {
     const TileRec *tiles;
@@ -55,7 +56,7 @@ struct Order3Args {
 template <typename T>
 __host__ __device__ constexpr size_t order3_lds_bytes(int W, int tn, int ta)
 {
-    return (size_t)ta * W * sizeof(T) + (size_t)padded(tn) * (4 + sizeof(T)) + (size_t)(4 * ta + 8) * 4 + 64;
+    return leaf_walk_lds_bytes<T>(W, tn, ta, NT) + (size_t)(3 * ta + 8) * 4 + 64;
 }
 
 template <typename T, int W, int MODE>
@@ -64,117 +65,91 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     constexpr int VEC = VecWidth<T>::value;
     constexpr int LG = W / VEC;   // lanes per row
     constexpr int G = NT / LG;    // lane groups per workgroup
+    constexpr int U = 4;          // gathers in flight per lane
+    constexpr int RS = leaf_row_stride<T>(W);
     static_assert(W % VEC == 0 && (LG & (LG - 1)) == 0 && LG <= 64, "row width");
     using P = Pack<T, VEC>;
-    using Acc = AccVec<T, VEC>;
+    using Rec = LeafRec<T>;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T *T_s = reinterpret_cast<T *>(smem);                   // ta * W
-    T *val_s = T_s + (size_t)a.ta * W;                      // padded(tn)
-    int *crd_s = reinterpret_cast<int *>(val_s + padded(a.tn));
-    int *ba_s = crd_s + padded(a.tn);    // ta + 2
-    int *crda_s = ba_s + a.ta + 2;       // ta
-    int *bb_s = crda_s + a.ta;           // ta + 2
-    int *crdb_s = bb_s + a.ta + 2;       // ta
+    T *row_s = reinterpret_cast<T *>(smem);                                    // (ta + 1) rows of RS: T
+    T *carry_s = row_s + (size_t)(a.ta + 1) * RS;                              // G rows of RS
+    Rec *rec_s = reinterpret_cast<Rec *>(carry_s + (size_t)G * RS);            // padded(tn + 8)
+    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));             // ta + 2: first nonzero of each fiber (tile-local)
+    int *chunk_lr = ba_s + a.ta + 2;                                           // G
+    int *crda_s = chunk_lr + G;          // ta: j of each fiber
+    int *bb_s = crda_s + a.ta;           // ta + 2: first fiber of each slice (tile-local)
+    int *crdb_s = bb_s + a.ta + 2;       // ta: output row of each slice
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
     const int nchild = t.n1 - t.n0;
     const int na = t.na, nb = t.nb;
+    const int g = tid / LG, li = tid % LG;
+    const int q = leaf_chunk<U>(nchild, G);
 
     // ---- stage ----
-    if (MODE != 2) {
+    if (MODE == 0) {
         const T *vals = static_cast<const T *>(a.vals);
-        for (int i = tid; i < nchild; i += NT) {
-            crd_s[pidx(i)] = a.crd3[t.n0 + i];
-            val_s[pidx(i)] = vals[t.n0 + i];
+        const uint32_t rowD = (uint32_t)(a.ldD * sizeof(T));
+        for (int c = tid; c < nchild; c += NT) {
+            Rec rec;
+            rec.koff = (uint32_t)a.crd3[t.n0 + c] * rowD;
+            rec.v = vals[t.n0 + c];
+            rec_s[pidx(c)] = rec;
         }
-        for (int i = tid; i <= na; i += NT) {
-            const int b = a.pos3[t.a0 + i];
-            ba_s[i] = min(max(b, t.n0), t.n1) - t.n0;
+        if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
+            Rec rec;
+            rec.koff = 0;
+            rec.v = T(0);
+            rec_s[pidx(nchild + tid)] = rec;
         }
-        if (tid == 0) ba_s[na + 1] = INT_MAX;
-    }
-    {
-        for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
-        for (int i = tid; i <= nb; i += NT) {
-            const int b = a.pos2[t.b0 + i];
-            bb_s[i] = min(max(b, t.a0), t.a0 + na) - t.a0;
-        }
-        if (tid == 0) {
-            bb_s[nb + 1] = INT_MAX;
-            // consumer-only kernel: the first fiber is skipped when it continues from the
-            // previous tile, so the first slice starts at fiber 1 as far as this tile goes
-            if (MODE == 2 && (t.flags & 1)) bb_s[0] = 1;
-        }
-        for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
-    }
-    if (MODE == 2) {
-        const P *Tg = reinterpret_cast<const P *>(static_cast<const T *>(a.T) + (int64_t)t.a0 * W);
-        for (int i = tid; i < na * LG; i += NT) reinterpret_cast<P *>(T_s)[i] = Tg[i];
+        for (int i = tid; i <= na; i += NT) ba_s[i] = min(max(a.pos3[t.a0 + i], t.n0), t.n1) - t.n0;
     } else {
-        P z;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
-        for (int i = tid; i < na * LG; i += NT) reinterpret_cast<P *>(T_s)[i] = z;
+        // A fiber cut by a tile boundary has one complete row in the workspace; the tile in which
+        // it starts consumes it, the tiles it continues into skip it (cf0 below).
+        const T *Tg = static_cast<const T *>(a.T) + (int64_t)t.a0 * W;
+        for (int r = g; r < na; r += G)
+            *reinterpret_cast<P *>(row_s + r * RS + li * VEC) = *reinterpret_cast<const P *>(Tg + (int64_t)r * W + li * VEC);
     }
+    for (int i = tid; i < na; i += NT) crda_s[i] = a.crd2[t.a0 + i];
+    for (int i = tid; i <= nb; i += NT) bb_s[i] = min(max(a.pos2[t.b0 + i], t.a0), t.a0 + na) - t.a0;
+    for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
     __syncthreads();
 
-    const int g = tid / LG, li = tid % LG;
-
-    // ---- producer: leaves -> T_s ----
-    if (MODE != 2) {
-        const T *D = static_cast<const T *>(a.D);
-        const int q = (nchild + G - 1) / G;
-        const int gs = g * q, ge = min(gs + q, nchild);
-        struct Item { T v; P d; };
-        seg_walk<8, Acc, Item>(
-            gs, ge, ba_s, na,
-            [&](int c) {
-                Item it;
-                const int k = crd_s[pidx(c)];
-                it.v = val_s[pidx(c)];
-                it.d = *reinterpret_cast<const P *>(D + (int64_t)k * a.ldD + li * VEC);
-                return it;
-            },
-            [&](Acc &acc, const Item &it) {
-#pragma unroll
-                for (int i = 0; i < VEC; ++i) acc.v[i] += it.v * it.d.v[i];
-            },
-            [&](int lp, const Acc &acc, bool whole) {
-                T *dst = T_s + lp * W + li * VEC;
-                if (whole) {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) dst[i] = acc.v[i];
-                } else {
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i) atomic_add(dst + i, acc.v[i]);
-                }
-            });
+    // ---- producer: the shared leaf walk, leaves -> rows of T in LDS ----
+    if (MODE == 0) {
+        leaf_mark(rec_s, ba_s, chunk_lr, tid, NT, na, q);
+        __syncthreads();
+        const LeafCarry st = leaf_walk<T, W, U>(row_s, carry_s, rec_s, ba_s, chunk_lr, a.D, g, li, q, nchild);
+        __syncthreads();
+        leaf_combine<T, W>(row_s, carry_s, ba_s, chunk_lr, st, g, li, q);
         __syncthreads();
     }
 
-    // ---- consumer: T_s -> A ----
-    // In the consumer-only kernel a fiber that continues from the previous tile belongs to
-    // the tile it starts in; skip it here.
+    // ---- consumer: rows of T -> A.  Every thread owns output elements (l, m) and runs over the
+    // tile's slices and fibers in order: one update per tile, slice and element. ----
     const int cf0 = (MODE == 2 && (t.flags & 1)) ? 1 : 0;
     const T *C = static_cast<const T *>(a.C);
     T *A = static_cast<T *>(a.A);
-    auto slice_shared = [&](int ls) { return (ls == 0 && (t.flags & 4)) || (ls == nb - 1 && (t.flags & 8)); };
-
-    {
-        // generic outer product on the vector ALU: every thread owns output elements (l, m)
-        // and runs over the tile's slices and fibers in order
-        const int L = a.L;
-        for (int e = tid; e < L * W; e += NT) {
-            const int l = e / W, m = e % W;
-            for (int ls = 0; ls < nb; ++ls) {
-                const int f0 = max(bb_s[ls], cf0), f1 = bb_s[ls + 1];
-                if (f0 >= f1) continue;
-                T acc = T(0);
-                for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crda_s[lf] * a.ldC + l] * T_s[lf * W + m];
-                T *dst = A + (int64_t)crdb_s[ls] * L * W + e;
-                if (!slice_shared(ls)) *dst = acc; else atomic_add(dst, acc);
+    const int L = a.L;
+    for (int e = tid; e < L * W; e += NT) {
+        const int l = e / W, m = e % W;
+        for (int ls = 0; ls < nb; ++ls) {
+            const int f0 = max(bb_s[ls], ls == 0 ? cf0 : 0), f1 = bb_s[ls + 1];
+            if (f0 >= f1) continue;
+            T acc = T(0);
+            for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crda_s[lf] * a.ldC + l] * row_s[lf * RS + m];
+            const bool first_shared = ls == 0 && (t.flags & 4), last_shared = ls == nb - 1 && (t.flags & 8);
+            T *dst = A + (int64_t)crdb_s[ls] * L * W + e;
+            if (!first_shared && !last_shared) {
+                *dst = acc;
+            } else if (a.partials) {
+                // deterministic: the tile's piece of this row goes to its slot (a tile whose only
+                // slice continues on both sides has one piece, numbered as its first)
+                static_cast<T *>(a.partials)[(int64_t)(first_shared ? t.pad[0] : t.pad[1]) * L * W + e] = acc;
+            } else {
+                atomic_add(dst, acc);
             }
         }
     }
@@ -678,11 +653,13 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             if (ln.status != SC_OK) return ln.status;
             return launch_fixup(p, ln, ws, out);
         } else {
+            // the leaf walk marks fiber ends in bit 31 of the factor-row byte offsets
+            if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * sizeof(T) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
             ln.begin("ttmc3_fused_valu");
             order3_kernel<T, W, 0><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
-        if (had) return launch_fixup(p, ln, ws, out);
+        return launch_fixup(p, ln, ws, out);
     } else {
         const sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse");
         if (st != SC_OK) return st;
@@ -763,7 +740,7 @@ bool plan_supports_deterministic(const sc_plan *p)
 {
     if (p->kind == K_SDDMM_SPMM) return true;   // both schedules: the sampled values have one writer each
     if (p->sched != SC_SCHED_FUSED) return false;
-    return p->kind == K_MTTKRP3 || plan_wants_tensor_order(p);
+    return p->kind == K_MTTKRP3 || p->kind == K_TTMC3 || plan_wants_tensor_order(p);
 }
 
 sc_status launch_fixup(const sc_plan *p, Launcher &ln, void *ws, void *out)
@@ -815,13 +792,19 @@ size_t lds_bytes_needed(const sc_plan *p)
             if (p->sched != SC_SCHED_FISSIONED) return ttmc3_mfma_lds_bytes(p);
             return std::max(ttmc3_mfma_lds_bytes(p), leaf_traverse_lds_bytes(p, 16));
         }
+        if (p->kind == K_MTTKRP3) {
+            // FISSIONED MTTKRP: leaf traversal, then the Hadamard consumer (two fibers and one slice staged per thread)
+            if (p->caps.ta > 2 * NT - 4 || p->caps.tb > NT) return SIZE_MAX;
+            const size_t cons = p->dtype == SC_F64 ? hadamard_lds_bytes<double>(p->caps.ta, p->caps.tb)
+                                                   : hadamard_lds_bytes<float>(p->caps.ta, p->caps.tb);
+            return std::max(cons, leaf_traverse_lds_bytes(p, (int)producer_width(p)));
+        }
         {
+            // general outer-product kernel, fused or as the consumer behind the leaf traversal
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
                                                   : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
             if (p->sched != SC_SCHED_FISSIONED) return own;
-            // the Hadamard consumer stages two fibers and one slice per thread
-            if (p->kind == K_MTTKRP3 && (p->caps.ta > 2 * NT - 4 || p->caps.tb > NT)) return SIZE_MAX;
-            return std::max(own, leaf_traverse_lds_bytes(p, (int)producer_width(p)));  // first FISSIONED kernel
+            return std::max(own, leaf_traverse_lds_bytes(p, (int)producer_width(p)));
         }
     case K_SDDMM_SPMM: return order2_lds_bytes_needed(p);
     case K_TTMC4: return order4_lds_bytes_needed(p);

@@ -27,7 +27,7 @@ def _run_twice(cfg, data, which="fused"):
     return outs
 
 
-@pytest.mark.parametrize("cid,scale,which", [(2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
+@pytest.mark.parametrize("cid,scale,which", [(1, 1.0, "fused"), (2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
                                              (4, 0.003, "fused"), (4, 0.01, "fissioned"), (5, 0.004, "fused")])
 def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
     cfg = synth.config(cid, scale)
@@ -44,6 +44,18 @@ def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
 def test_deterministic_degenerate_structures(oracle, kind, name):
     cfg, data = _case(kind, name)
     print(f"{kind} {name} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data)
+    assert_parity(oracle, cfg, data, outs[0])
+    for o in outs[1:]:
+        assert o.tobytes() == outs[0].tobytes()
+
+
+@pytest.mark.parametrize("dtype,ranks", [("f32", (8, 32)), ("f32", (32, 8)), ("f64", (16, 16)), ("f64", (4, 64))])
+def test_deterministic_general_outer_product_kernel(oracle, dtype, ranks):
+    """The order-3 chain at ranks / precisions the matrix-core kernel does not cover."""
+    cfg = dict(synth.config(3, 0.003), dtype=dtype, ranks=ranks)
+    data = synth.generate(cfg)
+    print(f"order-3 chain {dtype} ranks {ranks} deterministic nnz={cfg['nnz']}", flush=True)
     outs = _run_twice(cfg, data)
     assert_parity(oracle, cfg, data, outs[0])
     for o in outs[1:]:

@@ -291,7 +291,7 @@ def test_built_in_tile_caps_fit_every_supported_rank(cid, dtype, ranks, which):
     assert sc.plan_tile_count(plan) > 0
 
 
-@pytest.mark.parametrize("cid,scale", [(2, 0.004), (3, 0.003), (4, 0.003), (5, 0.004)])
+@pytest.mark.parametrize("cid,scale", [(1, 1.0), (2, 0.004), (3, 0.003), (4, 0.003), (5, 0.004)])
 def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scale):
     """Host side of the deterministic schedules: slots are consecutive per row, in tile order,
     and the workspace holds exactly the pieces."""
@@ -325,6 +325,6 @@ def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scal
 
 
 def test_deterministic_is_refused_where_no_kernel_provides_it():
-    for cid, scale, which in [(1, 1.0, "fused"), (3, 0.003, "fissioned"), (2, 0.004, "fissioned"), (5, 0.004, "fissioned")]:
+    for cid, scale, which in [(1, 1.0, "fissioned"), (3, 0.003, "fissioned"), (2, 0.004, "fissioned"), (5, 0.004, "fissioned")]:
         cfg, data, csf = _small(cid, scale)
         assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
