@@ -101,3 +101,51 @@ def test_parity_stored_zeros(oracle, kind, which):
     print(f"{kind} stored zeros {which} nnz={cfg['nnz']}", flush=True)
     con, got = run_library(cfg, data, which)
     assert_parity(oracle, cfg, data, got)
+
+
+@pytest.mark.parametrize("which", ["fused", "fissioned"])
+@pytest.mark.parametrize("kind", list(KINDS))
+def test_parity_padded_leading_dimension(oracle, kind, which):
+    """Factor rows longer than the rank (ld > cols): the padding holds NaN, so any read outside the
+    first `cols` elements of a row shows up in the result."""
+    import torch
+    from paper_2311_09549_amd import binding as sc
+    from paper_2311_09549_amd.driver import Contraction
+    from helpers import default_schedule
+
+    cfg, data = _case(kind, "count_3072")
+    print(f"{kind} ld > cols {which} nnz={cfg['nnz']}", flush=True)
+    con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                      default_schedule(cfg["kind"], which), synth.output_shape(cfg))
+    padded = []
+    for n, f in enumerate(con.factors):
+        big = torch.full((f.shape[0], f.shape[1] + 4 * (n + 1)), float("nan"), dtype=f.dtype, device=f.device)
+        big[:, : f.shape[1]] = f
+        padded.append(big[:, : f.shape[1]])
+        assert sc.dense_view(padded[-1]).ld == f.shape[1] + 4 * (n + 1)
+    con.factors = padded
+    con.run()
+    assert_parity(oracle, cfg, data, con.result())
+
+
+@pytest.mark.parametrize("kind", list(KINDS))
+def test_parity_on_a_side_stream(oracle, kind):
+    """All launches of an execution go to the caller's stream: queued behind a long fill on a side
+    stream, the result is complete once that stream (and only that stream) has been waited for."""
+    import torch
+    from paper_2311_09549_amd.driver import Contraction
+    from helpers import default_schedule
+
+    cfg, data = _case(kind, "count_3072")
+    con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                      default_schedule(cfg["kind"], "fissioned"), synth.output_shape(cfg))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()   # default priority
+    with torch.cuda.stream(side):
+        ballast = torch.empty(64 << 20, dtype=torch.float32, device="cuda:0")
+        for _ in range(4):
+            ballast.fill_(1.0)   # keeps the side stream busy ahead of the library's kernels
+        con.run(stream=side.cuda_stream)
+    side.synchronize()
+    got = con.out.cpu().numpy()
+    assert_parity(oracle, cfg, data, got)
