@@ -177,6 +177,40 @@ inline void launch_fill(Launcher &ln, T *p, int64_t n, const char *name)
     ln.end();
 }
 
+// Zeroes the listed rows of the output (16-byte stores; rows are a multiple of 16 bytes long).
+template <typename T>
+__global__ void __launch_bounds__(NT) zero_rows_kernel(const int32_t *__restrict__ rows, int64_t nvec, int vec_per_row, T *out, int64_t rowlen)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    Pack<T, VEC> z;
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) z.v[i] = T(0);
+    for (int64_t i = (int64_t)blockIdx.x * NT + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * NT) {
+        const int64_t r = rows[i / vec_per_row];
+        reinterpret_cast<Pack<T, VEC> *>(out + r * rowlen)[i % vec_per_row] = z;
+    }
+}
+
+// First launch of every execution: the output rows that the kernels do not overwrite completely
+// become zero (the rows the plan lists, or the whole output when they are many).
+template <typename T>
+inline void launch_output_zero(Launcher &ln, const sc_plan *p, T *out)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    if (!p->zero_selective || p->out_row_elems % VEC != 0) {
+        launch_fill<T>(ln, out, p->out_elems, "fill_output");
+        return;
+    }
+    const int vpr = (int)(p->out_row_elems / VEC);
+    const int64_t nvec = (int64_t)p->zero_rows.size() * vpr;
+    ln.begin("zero_output_rows");
+    if (nvec > 0) {
+        const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, 256 * 16);
+        zero_rows_kernel<T><<<blocks, NT, 0, ln.stream>>>(p->d_zero_rows, nvec, vpr, out, p->out_row_elems);
+    }
+    ln.end();
+}
+
 // Leaf traversal of the FISSIONED schedules of order >= 3 (its own kernel file); W = row width of
 // the temporary it writes.
 size_t leaf_traverse_lds_bytes(const sc_plan *p, int W);

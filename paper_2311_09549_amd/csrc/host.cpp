@@ -378,19 +378,55 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
     }
 }
 
+// Top level of a tile record ("a" for order 2, "b" for order 3, "c" for order 4): whether its
+// first / last slice continues from the previous / into the next tile, first slice, slice count.
+struct TopLevel {
+    bool in, out;
+    int32_t top0, ntop;
+};
+TopLevel top_level(int order, const TileRec &t)
+{
+    const bool o4 = order == 4, o2 = order == 2;
+    const int32_t in_bit = o4 ? 16 : o2 ? 1 : 4, out_bit = o4 ? 32 : o2 ? 2 : 8;
+    return {(t.flags & in_bit) != 0, (t.flags & out_bit) != 0, o4 ? t.c0 : o2 ? t.a0 : t.b0, o4 ? t.nc : o2 ? t.na : t.nb};
+}
+
+// Lists the output rows that the kernels do not overwrite completely and that therefore have
+// to be zero before they run: rows of empty slices and, unless the schedule is deterministic
+// (then a last kernel writes them), rows whose slice spans several tiles and is accumulated
+// atomically.  Every other row is stored whole by the one tile that holds its slice.
+void list_rows_to_zero(sc_plan *p, const HostCsf &h)
+{
+    const int64_t rows = p->dims[0];
+    std::vector<char> stored((size_t)rows, 0);
+    for (int64_t s = 0; s < p->nfib[0]; ++s) stored[(size_t)h.crd[0][s]] = 1;
+    p->zero_rows.clear();
+    for (int64_t r = 0; r < rows; ++r)
+        if (!stored[(size_t)r]) p->zero_rows.push_back((int32_t)r);
+    if (!p->deterministic)
+        for (const TileRec &t : p->tiles) {
+            const TopLevel tl = top_level(p->order, t);
+            if (tl.out && !(tl.in && tl.ntop == 1)) p->zero_rows.push_back(h.crd[0][tl.top0 + tl.ntop - 1]);   // a spanning slice, listed where it starts
+        }
+    p->zero_selective = (int64_t)p->zero_rows.size() * 2 <= rows;
+    if (!p->zero_selective) {
+        p->zero_rows.clear();
+        p->zero_rows.shrink_to_fit();
+    }
+}
+
 // Deterministic schedules: numbers the pieces of every output row that spans several tiles
 // (consecutive slots in tile order) and lists those rows.  The top level is "a" for order 2, "b"
 // for order 3 and "c" for order 4; its flag bits say whether the tile's first / last slice continues
 // from the previous / into the next tile.  A tile whose only slice does both holds one piece.
 void assign_piece_slots(sc_plan *p, const HostCsf &h)
 {
-    const bool o4 = p->order == 4, o2 = p->order == 2;
-    const int32_t in_bit = o4 ? 16 : o2 ? 1 : 4, out_bit = o4 ? 32 : o2 ? 2 : 8;
     int32_t next = 0;
     p->fix.clear();
     for (TileRec &t : p->tiles) {
-        const int32_t top0 = o4 ? t.c0 : o2 ? t.a0 : t.b0, ntop = o4 ? t.nc : o2 ? t.na : t.nb;
-        const bool in = (t.flags & in_bit) != 0, out = (t.flags & out_bit) != 0;
+        const TopLevel tl = top_level(p->order, t);
+        const int32_t top0 = tl.top0, ntop = tl.ntop;
+        const bool in = tl.in, out = tl.out;
         t.pad[0] = t.pad[1] = -1;
         if (in) {   // a piece of the row that the previous tile left open
             t.pad[0] = next++;
@@ -659,6 +695,7 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             if (!plan_supports_deterministic(p)) return SC_ERR_SCHED_UNSUPPORTED;
             assign_piece_slots(p, h);
         }
+        list_rows_to_zero(p, h);
     } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
 
     // ---- workspace, model, text ----
@@ -791,6 +828,11 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             for (size_t r = 0; r < stride; ++r)
                 for (size_t t = r; t < nt; t += stride) order.push_back(p->tiles[t]);
             if (hipMemcpy(p->d_tiles, order.data(), sizeof(TileRec) * nt, hipMemcpyHostToDevice) != hipSuccess)
+                return SC_ERR_DEVICE;
+        }
+        if (p->zero_selective && !p->zero_rows.empty()) {
+            if (hipMalloc((void **)&p->d_zero_rows, sizeof(int32_t) * p->zero_rows.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(p->d_zero_rows, p->zero_rows.data(), sizeof(int32_t) * p->zero_rows.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
         if (!p->fix.empty()) {
@@ -932,6 +974,7 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
     if (!plan) return SC_OK;
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
     if (plan->d_fix) (void)hipFree(plan->d_fix);
+    if (plan->d_zero_rows) (void)hipFree(plan->d_zero_rows);
     if (plan->d_segs) (void)hipFree(plan->d_segs);
     if (plan->events_made)
         for (int i = 0; i < kMaxLaunches; ++i) {

@@ -224,7 +224,7 @@ template <typename T, int N, int M>
 sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
     Launcher ln{p, stream};
-    launch_fill<T>(ln, static_cast<T *>(out), p->out_elems, "fill_output");
+    launch_output_zero<T>(ln, p, static_cast<T *>(out));
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return ln.status;
     Order4Args a;

@@ -88,6 +88,13 @@ struct sc_plan {
     sck::TileRec *d_tiles = nullptr;  // plan-owned device copy
     bool has_device = false;
 
+    // Output rows that no kernel overwrites completely: rows of empty slices, and (atomic
+    // schedules) rows whose slice spans several tiles.  When they are few, only they are zeroed
+    // before the kernels run; otherwise the whole output is.
+    std::vector<int32_t> zero_rows;
+    int32_t *d_zero_rows = nullptr;   // plan-owned device copy
+    bool zero_selective = false;
+
     size_t ws_bytes = 0;
     bool deterministic = false;
     std::vector<sck::FixRec> fix;     // rows spanning several tiles (deterministic schedules only): second pass
