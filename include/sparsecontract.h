@@ -122,8 +122,9 @@ typedef struct {
  *                    1: every tile stores its piece of such a row in the workspace and a last
  *                    kernel adds the pieces in tile order, so two executions of a plan give
  *                    bit-identical results.  Available for both schedules of the SDDMM -> SpMM
- *                    pair and for the FUSED schedules of the MTTKRP and of the order-3 TTM chain
- *                    (any supported rank, fp32 / fp64) and of the fp32 order-4 TTM chain;
+ *                    pair, of the MTTKRP and of the order-3 TTM chain (any supported rank, fp32 /
+ *                    fp64; under FISSIONED the rows of the temporary that span tiles are treated
+ *                    the same way), and for the FUSED schedule of the fp32 order-4 TTM chain;
  *                    SC_ERR_SCHED_UNSUPPORTED otherwise.  sc_plan_workspace_bytes then includes the pieces. */
 typedef struct {
     sc_sched_kind kind;

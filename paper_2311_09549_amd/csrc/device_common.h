@@ -214,8 +214,9 @@ inline void launch_output_zero(Launcher &ln, const sc_plan *p, T *out)
 // Leaf traversal of the FISSIONED schedules of order >= 3 (its own kernel file); W = row width of
 // the temporary it writes.
 size_t leaf_traverse_lds_bytes(const sc_plan *p, int W);
+// `partials`: deterministic schedules only (else null): slots for the pieces of rows that span tiles.
 sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name);
+                               const sc_dense_view &F, void *Tout, int W, const char *name, void *partials);
 
 // Order-3 TTM chain on matrix cores (fp32, L = M = 16; its own kernel file): the FUSED schedule (T == nullptr)
 // or the consumer kernel of the FISSIONED one.
@@ -225,8 +226,9 @@ bool ttmc3_mfma_caps_ok(const sc_plan *p);
 sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
                             void *partials);
 
-// Last kernel of a deterministic schedule: adds the stored pieces of every row that spans tiles.
-sc_status launch_fixup(const sc_plan *p, Launcher &ln, void *workspace, void *out);
+// Last kernels of a deterministic stage: add the stored pieces of every row of the level that spans tiles
+// (dst = the output for the top level, the temporary for level a).
+sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void *workspace, void *dst);
 
 // Order-4 TTM chain on matrix cores (fp32, M = N = 8, L <= 16; its own kernel file): mode 0 the FUSED schedule,
 // modes 1 and 2 the second and third kernel of the FISSIONED one.

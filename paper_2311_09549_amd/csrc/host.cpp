@@ -419,44 +419,78 @@ void list_rows_to_zero(sc_plan *p, const HostCsf &h)
 // (consecutive slots in tile order) and lists those rows.  The top level is "a" for order 2, "b"
 // for order 3 and "c" for order 4; its flag bits say whether the tile's first / last slice continues
 // from the previous / into the next tile.  A tile whose only slice does both holds one piece.
-void assign_piece_slots(sc_plan *p, const HostCsf &h)
+// Cuts the pieces of every spanning row into the segments of the first fix-up pass; a row's
+// segments are consecutive.  On entry a record holds {row, first slot, pieces}.
+void make_segments(FixLevel &lv)
 {
-    int32_t next = 0;
-    p->fix.clear();
-    for (TileRec &t : p->tiles) {
-        const TopLevel tl = top_level(p->order, t);
-        const int32_t top0 = tl.top0, ntop = tl.ntop;
-        const bool in = tl.in, out = tl.out;
-        t.pad[0] = t.pad[1] = -1;
-        if (in) {   // a piece of the row that the previous tile left open
-            t.pad[0] = next++;
-            p->fix.back().count++;
-        }
-        if (out && !(in && ntop == 1)) {   // the tile's last slice starts here and goes on
-            FixRec f;
-            f.row = h.crd[0][top0 + ntop - 1];
-            f.first = next;
-            f.count = 1;
-            f.pad = 0;
-            p->fix.push_back(f);
-            t.pad[1] = next++;
-        }
-    }
-    p->n_slots = next;
-    // segments of the first pass; a row's segments are consecutive
-    p->segs.clear();
-    for (FixRec &f : p->fix) {
+    lv.segs.clear();
+    for (FixRec &f : lv.fix) {
         const int32_t slot0 = f.first, pieces = f.count;
-        f.first = (int32_t)p->segs.size();
+        f.first = (int32_t)lv.segs.size();
         f.count = (pieces + kFixSegment - 1) / kFixSegment;
         for (int32_t s0 = 0; s0 < pieces; s0 += kFixSegment) {
             FixRec g;
-            g.row = (int32_t)p->segs.size();
+            g.row = (int32_t)lv.segs.size();
             g.first = slot0 + s0;
             g.count = std::min<int32_t>(kFixSegment, pieces - s0);
             g.pad = 0;
-            p->segs.push_back(g);
+            lv.segs.push_back(g);
         }
+    }
+}
+
+void assign_piece_slots(sc_plan *p, const HostCsf &h)
+{
+    // output rows
+    FixLevel &top = p->det_top;
+    top.rowlen = p->out_row_elems;
+    int32_t next = 0;
+    top.fix.clear();
+    for (TileRec &t : p->tiles) {
+        const TopLevel tl = top_level(p->order, t);
+        t.pad[0] = t.pad[1] = t.pad[2] = -1;
+        if (tl.in) {   // a piece of the row that the previous tile left open
+            t.pad[0] = next++;
+            top.fix.back().count++;
+        }
+        if (tl.out && !(tl.in && tl.ntop == 1)) {   // the tile's last slice starts here and goes on
+            FixRec f;
+            f.row = h.crd[0][tl.top0 + tl.ntop - 1];
+            f.first = next;
+            f.count = 1;
+            f.pad = 0;
+            top.fix.push_back(f);
+            t.pad[1] = next++;
+        }
+    }
+    top.n_slots = next;
+    make_segments(top);
+
+    // FISSIONED, order 3: rows of the temporary, one per leaf fiber (level "a", flag bits 1 / 2)
+    FixLevel &la = p->det_a;
+    la.fix.clear();
+    la.n_slots = 0;
+    if (p->sched == SC_SCHED_FISSIONED && p->order == 3) {
+        la.rowlen = p->kind == K_TTMC3 ? p->fcols[1] : p->fcols[0];   // width of the temporary's rows
+        next = 0;
+        for (TileRec &t : p->tiles) {
+            const bool in = (t.flags & 1) != 0, out = (t.flags & 2) != 0;
+            t.pad[2] = next;
+            if (in) {
+                ++next;
+                la.fix.back().count++;
+            }
+            if (out && !(in && t.na == 1)) {
+                FixRec f;
+                f.row = t.a0 + t.na - 1;   // position of the fiber = row of the temporary
+                f.first = next++;
+                f.count = 1;
+                f.pad = 0;
+                la.fix.push_back(f);
+            }
+        }
+        la.n_slots = next;
+        make_segments(la);
     }
 }
 
@@ -757,11 +791,14 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         p->ws_bytes = 0;
         for (int t = 0; t < p->n_inter; ++t) p->inter[t].offset = 0;
     }
-    if (p->deterministic && p->n_slots) {
-        const size_t row_bytes = (size_t)p->out_row_elems * esize(p->dtype);
-        p->det_offset = (p->ws_bytes + 255) & ~(size_t)255;
-        p->seg_offset = (p->det_offset + (size_t)p->n_slots * row_bytes + 255) & ~(size_t)255;
-        p->ws_bytes = p->seg_offset + p->segs.size() * row_bytes;
+    if (p->deterministic) {
+        for (FixLevel *lv : {&p->det_top, &p->det_a}) {
+            if (!lv->n_slots) continue;
+            const size_t row_bytes = (size_t)lv->rowlen * esize(p->dtype);
+            lv->slot_offset = (p->ws_bytes + 255) & ~(size_t)255;
+            lv->seg_offset = (lv->slot_offset + (size_t)lv->n_slots * row_bytes + 255) & ~(size_t)255;
+            p->ws_bytes = lv->seg_offset + lv->segs.size() * row_bytes;
+        }
     }
     p->model_flops = flops;
     p->model_bytes = bytes;
@@ -806,9 +843,13 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     appendf(tx, "\ntiles: %zu (<= %d leaves, <= %d level-a nodes", p->tiles.size(), p->caps.tn, p->caps.ta);
     if (d == 4) appendf(tx, ", <= %d level-b nodes", p->caps.tb);
     appendf(tx, ")\nmodel: %.6g flops, %.6g compulsory HBM bytes, workspace %zu bytes\n", flops, bytes, p->ws_bytes);
-    if (p->deterministic)
+    if (p->deterministic) {
         appendf(tx, "deterministic: %zu output rows span several tiles; their %lld pieces are stored in the workspace and added in tile order (%zu segments of at most %d)\n",
-                p->fix.size(), (long long)p->n_slots, p->segs.size(), kFixSegment);
+                p->det_top.fix.size(), (long long)p->det_top.n_slots, p->det_top.segs.size(), kFixSegment);
+        if (p->det_a.n_slots)
+            appendf(tx, "deterministic: %zu rows of %s span several tiles; %lld pieces (%zu segments)\n", p->det_a.fix.size(),
+                    p->inter[0].name.c_str(), (long long)p->det_a.n_slots, p->det_a.segs.size());
+    }
 
     // ---- device tables ----
     int ndev = 0;
@@ -835,12 +876,13 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             if (hipMemcpy(p->d_zero_rows, p->zero_rows.data(), sizeof(int32_t) * p->zero_rows.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
-        if (!p->fix.empty()) {
-            if (hipMalloc((void **)&p->d_fix, sizeof(FixRec) * p->fix.size()) != hipSuccess) return SC_ERR_DEVICE;
-            if (hipMemcpy(p->d_fix, p->fix.data(), sizeof(FixRec) * p->fix.size(), hipMemcpyHostToDevice) != hipSuccess)
+        for (FixLevel *lv : {&p->det_top, &p->det_a}) {
+            if (lv->fix.empty()) continue;
+            if (hipMalloc((void **)&lv->d_fix, sizeof(FixRec) * lv->fix.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(lv->d_fix, lv->fix.data(), sizeof(FixRec) * lv->fix.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
-            if (hipMalloc((void **)&p->d_segs, sizeof(FixRec) * p->segs.size()) != hipSuccess) return SC_ERR_DEVICE;
-            if (hipMemcpy(p->d_segs, p->segs.data(), sizeof(FixRec) * p->segs.size(), hipMemcpyHostToDevice) != hipSuccess)
+            if (hipMalloc((void **)&lv->d_segs, sizeof(FixRec) * lv->segs.size()) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(lv->d_segs, lv->segs.data(), sizeof(FixRec) * lv->segs.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
         p->has_device = true;
@@ -973,9 +1015,11 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
 {
     if (!plan) return SC_OK;
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
-    if (plan->d_fix) (void)hipFree(plan->d_fix);
+    for (sck::FixLevel *lv : {&plan->det_top, &plan->det_a}) {
+        if (lv->d_fix) (void)hipFree(lv->d_fix);
+        if (lv->d_segs) (void)hipFree(lv->d_segs);
+    }
     if (plan->d_zero_rows) (void)hipFree(plan->d_zero_rows);
-    if (plan->d_segs) (void)hipFree(plan->d_segs);
     if (plan->events_made)
         for (int i = 0; i < kMaxLaunches; ++i) {
             (void)hipEventDestroy(plan->ev_begin[i]);

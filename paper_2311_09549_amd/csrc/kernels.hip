@@ -137,10 +137,12 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
         const int l = e / W, m = e % W;
         for (int ls = 0; ls < nb; ++ls) {
             const int f0 = max(bb_s[ls], ls == 0 ? cf0 : 0), f1 = bb_s[ls + 1];
-            if (f0 >= f1) continue;
+            const bool first_shared = ls == 0 && (t.flags & 4), last_shared = ls == nb - 1 && (t.flags & 8);
+            // nothing of this slice is consumed here (only the fiber that an earlier tile owns): no
+            // update, except that a deterministic schedule still expects the tile's (zero) piece
+            if (f0 >= f1 && !(a.partials && (first_shared || last_shared))) continue;
             T acc = T(0);
             for (int lf = f0; lf < f1; ++lf) acc += C[(int64_t)crda_s[lf] * a.ldC + l] * row_s[lf * RS + m];
-            const bool first_shared = ls == 0 && (t.flags & 4), last_shared = ls == nb - 1 && (t.flags & 8);
             T *dst = A + (int64_t)crdb_s[ls] * L * W + e;
             if (!first_shared && !last_shared) {
                 *dst = acc;
@@ -423,7 +425,7 @@ __host__ __device__ constexpr size_t hadamard_lds_bytes(int ta, int tb)
     return (size_t)NT * 16 + (size_t)padded(ta + 8) * sizeof(FibRec) + (size_t)(2 * tb + 2 * (NT / 2)) * 4 + 64;
 }
 
-template <typename T, int W>
+template <typename T, int W, bool DET>
 __global__ void __launch_bounds__(NT) hadamard_consume_kernel(Order3Args a)
 {
     constexpr int VEC = VecWidth<T>::value;
@@ -485,6 +487,15 @@ __global__ void __launch_bounds__(NT) hadamard_consume_kernel(Order3Args a)
             rec_s[pidx(s_hi - 1)].s = tid;
             for (int m = s_lo / q + 1; m * q < s_hi; ++m) chunk_ls[m - 1] = tid;
         }
+        if (DET && tid < nb && s_hi == s_lo) {
+            // Nothing of this slice is consumed here (its only fiber in the tile belongs to an earlier
+            // tile), so the walk emits nothing for it; the plan still counts a piece of this tile.
+            const bool first_shared = tid == 0 && (t.flags & 4), last_shared = tid == nb - 1 && (t.flags & 8);
+            if (first_shared || last_shared) {
+                T *slot = static_cast<T *>(a.partials) + (int64_t)(first_shared ? t.pad[0] : t.pad[1]) * W;
+                for (int i = 0; i < W; ++i) slot[i] = T(0);
+            }
+        }
     }
     __syncthreads();
 
@@ -498,6 +509,9 @@ __global__ void __launch_bounds__(NT) hadamard_consume_kernel(Order3Args a)
         T *dst = A + (int64_t)crdb_s[ls] * W + li * VEC;
         if (!slice_shared(ls)) {
             *reinterpret_cast<P *>(dst) = row;
+        } else if (DET) {
+            const int slot = (ls == 0 && (t.flags & 4)) ? t.pad[0] : t.pad[1];
+            *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
         } else {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
@@ -633,7 +647,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.L = (int32_t)p->fcols[0];
     a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
     a.A = out;
-    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
+    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
     const bool had = p->kind == K_MTTKRP3;
@@ -651,7 +665,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         } else if (mfma) {
             ln.status = launch_ttmc3_mfma(p, ln, sp, fac, nullptr, out, a.partials);
             if (ln.status != SC_OK) return ln.status;
-            return launch_fixup(p, ln, ws, out);
+            return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
             // the leaf walk marks fiber ends in bit 31 of the factor-row byte offsets
             if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * sizeof(T) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
@@ -659,22 +673,30 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             order3_kernel<T, W, 0><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
-        return launch_fixup(p, ln, ws, out);
+        return launch_fixup(p, ln, p->det_top, ws, out);
     } else {
-        const sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse");
+        void *partials_a = p->deterministic && ws ? static_cast<char *>(ws) + p->det_a.slot_offset : nullptr;
+        sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse", partials_a);
+        if (st != SC_OK) return st;
+        st = launch_fixup(p, ln, p->det_a, ws, a.T);   // deterministic: the rows of T that span tiles
         if (st != SC_OK) return st;
         if (had) {
             if (a.ta > 2 * NT - 4 || a.tb > NT) return SC_ERR_SCHED_UNSUPPORTED;   // staging registers of the consumer
             ln.begin("mttkrp3_consume");
-            hadamard_consume_kernel<T, W><<<ntiles, NT, hadamard_lds_bytes<T>(a.ta, a.tb), stream>>>(a);
+            if (a.partials)
+                hadamard_consume_kernel<T, W, true><<<ntiles, NT, hadamard_lds_bytes<T>(a.ta, a.tb), stream>>>(a);
+            else
+                hadamard_consume_kernel<T, W, false><<<ntiles, NT, hadamard_lds_bytes<T>(a.ta, a.tb), stream>>>(a);
         } else if (mfma) {
-            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out, nullptr);
-            return ln.status;
+            ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out, a.partials);
+            if (ln.status != SC_OK) return ln.status;
+            return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
             ln.begin("ttmc3_consume_valu");
             order3_kernel<T, W, 2><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
+        return launch_fixup(p, ln, p->det_top, ws, out);
     }
     return ln.status;
 }
@@ -739,31 +761,31 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 bool plan_supports_deterministic(const sc_plan *p)
 {
     if (p->kind == K_SDDMM_SPMM) return true;   // both schedules: the sampled values have one writer each
-    if (p->sched != SC_SCHED_FUSED) return false;
-    return p->kind == K_MTTKRP3 || p->kind == K_TTMC3 || plan_wants_tensor_order(p);
+    if (p->kind == K_MTTKRP3 || p->kind == K_TTMC3) return true;   // both schedules
+    return p->sched == SC_SCHED_FUSED && plan_wants_tensor_order(p);   // order 4: the fp32 FUSED kernel
 }
 
-sc_status launch_fixup(const sc_plan *p, Launcher &ln, void *ws, void *out)
+sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void *ws, void *dst)
 {
-    if (!p->deterministic || p->fix.empty()) return ln.status;
-    const int rowlen = (int)p->out_row_elems;
-    char *slots = static_cast<char *>(ws) + p->det_offset;
-    char *segs = static_cast<char *>(ws) + p->seg_offset;
+    if (!p->deterministic || lv.fix.empty()) return ln.status;
+    const int rowlen = (int)lv.rowlen;
+    char *slots = static_cast<char *>(ws) + lv.slot_offset;
+    char *segs = static_cast<char *>(ws) + lv.seg_offset;
     ln.begin("fixup_segments");
     if (p->dtype == SC_F64)
-        fixup_rows_kernel<double><<<(int)p->segs.size(), NT, 0, ln.stream>>>(p->d_segs, reinterpret_cast<const double *>(slots),
-                                                                             reinterpret_cast<double *>(segs), rowlen);
+        fixup_rows_kernel<double><<<(int)lv.segs.size(), NT, 0, ln.stream>>>(lv.d_segs, reinterpret_cast<const double *>(slots),
+                                                                            reinterpret_cast<double *>(segs), rowlen);
     else
-        fixup_rows_kernel<float><<<(int)p->segs.size(), NT, 0, ln.stream>>>(p->d_segs, reinterpret_cast<const float *>(slots),
-                                                                            reinterpret_cast<float *>(segs), rowlen);
+        fixup_rows_kernel<float><<<(int)lv.segs.size(), NT, 0, ln.stream>>>(lv.d_segs, reinterpret_cast<const float *>(slots),
+                                                                           reinterpret_cast<float *>(segs), rowlen);
     ln.end();
     ln.begin("fixup_rows");
     if (p->dtype == SC_F64)
-        fixup_rows_kernel<double><<<(int)p->fix.size(), NT, 0, ln.stream>>>(p->d_fix, reinterpret_cast<const double *>(segs),
-                                                                            static_cast<double *>(out), rowlen);
+        fixup_rows_kernel<double><<<(int)lv.fix.size(), NT, 0, ln.stream>>>(lv.d_fix, reinterpret_cast<const double *>(segs),
+                                                                           static_cast<double *>(dst), rowlen);
     else
-        fixup_rows_kernel<float><<<(int)p->fix.size(), NT, 0, ln.stream>>>(p->d_fix, reinterpret_cast<const float *>(segs),
-                                                                           static_cast<float *>(out), rowlen);
+        fixup_rows_kernel<float><<<(int)lv.fix.size(), NT, 0, ln.stream>>>(lv.d_fix, reinterpret_cast<const float *>(segs),
+                                                                          static_cast<float *>(dst), rowlen);
     ln.end();
     return ln.status;
 }

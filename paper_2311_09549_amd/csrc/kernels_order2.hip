@@ -259,7 +259,7 @@ sc_status run_order2(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.Z = fac[2].data; a.ldZ = fac[2].ld;
     a.T = ws ? static_cast<char *>(ws) + p->inter[0].offset : nullptr;
     a.A = out;
-    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
+    a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta;
     const size_t lds = order2_lds_bytes<T>(a.tn, a.ta);
     if (p->sched == SC_SCHED_FUSED) {
@@ -274,7 +274,7 @@ sc_status run_order2(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         sddmm_spmm_kernel<T, W, 2><<<ntiles, NT, lds, stream>>>(a);
         ln.end();
     }
-    return launch_fixup(p, ln, ws, out);
+    return launch_fixup(p, ln, p->det_top, ws, out);
 }
 
 template <typename T>

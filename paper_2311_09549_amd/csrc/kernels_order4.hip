@@ -244,17 +244,17 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;   // the matrix-core kernel (fp32)
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
-            void *partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_offset : nullptr;
+            void *partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
             ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 0, nullptr, nullptr, out, partials);   // dedicated matrix-core kernel
             if (ln.status != SC_OK) return ln.status;
-            return launch_fixup(p, ln, ws, out);
+            return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
             ln.begin("ttmc4_fused_valu");
             order4_kernel<T, N, M, 0><<<ntiles, NT, lds, stream>>>(a);
         }
         ln.end();
     } else {
-        sc_status st = launch_leaf_producer(p, ln, sp->pos[3], sp->crd[3], sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse");
+        sc_status st = launch_leaf_producer(p, ln, sp->pos[3], sp->crd[3], sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse", nullptr);
         if (st != SC_OK) return st;
         ln.begin("zero_shared_rows_t2");
         zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 1, static_cast<T *>(a.T2), M * N);

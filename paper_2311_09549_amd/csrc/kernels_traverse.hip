@@ -39,6 +39,7 @@ struct LeafArgs {
     const void *F;
     int64_t ldF;
     void *Tout;
+    void *partials;   // deterministic schedules: slots for the pieces of rows that span tiles, else null
     int32_t tn, ta;
     int32_t ntiles;
 };
@@ -79,7 +80,9 @@ __device__ __forceinline__ void leaf_issue(const LeafArgs &a, const TileRec &t, 
 // Persistent workgroups: workgroup b handles tiles b, b + gridDim.x, ...  While one tile is
 // walked, the staging reads of the next are already in flight, and the row stores of the
 // previous tile drain behind them, so the three phases of consecutive tiles overlap.
-template <typename T, int W>
+// DET: the deterministic variant (the pieces of a row shared with a neighbouring tile go to the
+// tile's slots instead of being added atomically).
+template <typename T, int W, bool DET>
 __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const TileRec *__restrict__ tiles)
 {
     // `tiles` is a separate restrict-qualified argument so that the tile records stay scalar
@@ -171,6 +174,10 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
             const bool shared = (r == 0 && (t.flags & 1)) || (r == na - 1 && (t.flags & 2));
             if (!shared) {
                 nt_store16(dst, row);
+            } else if (DET) {
+                // the piece of the tile's first fiber is numbered pad[2], that of its last fiber follows
+                const int slot = t.pad[2] + ((r == 0 && (t.flags & 1)) ? 0 : (t.flags & 1));
+                *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
             } else {
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
@@ -187,7 +194,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
 namespace {
 template <typename T, int W>
 sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                        const sc_dense_view &F, void *Tout, const char *name)
+                        const sc_dense_view &F, void *Tout, void *partials, const char *name)
 {
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return SC_OK;
@@ -200,10 +207,13 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
     a.F = F.data;
     a.ldF = F.ld;
     a.Tout = Tout;
+    a.partials = partials;
     a.tn = p->caps.tn; a.ta = p->caps.ta;
-    ln.begin("zero_shared_rows");
-    zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
-    ln.end();
+    if (!partials) {   // rows shared between tiles are added atomically: they start from zero
+        ln.begin("zero_shared_rows");
+        zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, ln.stream>>>(p->d_tiles, ntiles, 0, static_cast<T *>(Tout), W);
+        ln.end();
+    }
     ln.begin(name);
     // persistent launch: as many workgroups as fit on the chip at once (LDS-limited), never more than tiles
     a.ntiles = ntiles;
@@ -211,7 +221,10 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
     const int fit = lds_workgroups_per_cu(lds);
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 16) : fit;
     const int blocks = std::min(ntiles, 256 * per_cu);
-    leaf_traverse_kernel<T, W><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
+    if (partials)
+        leaf_traverse_kernel<T, W, true><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
+    else
+        leaf_traverse_kernel<T, W, false><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
     ln.end();
     return ln.status;
 }
@@ -224,13 +237,13 @@ size_t leaf_traverse_lds_bytes(const sc_plan *p, int W)
 }
 
 sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name)
+                               const sc_dense_view &F, void *Tout, int W, const char *name, void *partials)
 {
     const bool f64 = p->dtype == SC_F64;
 #define SC_LEAF(WW)                                                                                   \
     case WW:                                                                                          \
-        return f64 ? leaf_traverse<double, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name)        \
-                   : leaf_traverse<float, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, name);
+        return f64 ? leaf_traverse<double, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, partials, name) \
+                   : leaf_traverse<float, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, partials, name);
     switch (W) {
         SC_LEAF(8)
         SC_LEAF(16)

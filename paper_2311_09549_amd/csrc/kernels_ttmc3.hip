@@ -349,7 +349,10 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
             ttmc3_mfma_kernel<true, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else {
         ln.begin("ttmc3_consume_mfma");
-        ttmc3_mfma_kernel<false, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        if (partials)
+            ttmc3_mfma_kernel<false, true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        else
+            ttmc3_mfma_kernel<false, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     }
     ln.end();
     return ln.status;

@@ -45,7 +45,7 @@ constexpr int kMaxLaunches = 8;
 
 // Deterministic schedules: an output row whose slice spans several tiles is not updated with
 // atomics; every tile stores its piece of the row in a slot of the workspace (the two slot
-// numbers of a tile are in TileRec::pad[0] / pad[1], -1 = none; the pieces of one row occupy
+// numbers of a tile for output rows are in TileRec::pad[0] / pad[1], -1 = none; the pieces of one row occupy
 // consecutive slots in tile order) and two last kernels add the pieces of each row in that
 // order: first in segments of kFixSegment pieces (many workgroups per heavy row), then the
 // segment sums.  Both are described by the same record.
@@ -56,6 +56,18 @@ struct FixRec {
     int32_t pad;
 };
 constexpr int kFixSegment = 64;
+
+// The rows of one level that span several tiles under a deterministic schedule.
+struct FixLevel {
+    std::vector<FixRec> fix;      // second pass: one record per spanning row
+    std::vector<FixRec> segs;     // first pass: its pieces in segments
+    FixRec *d_fix = nullptr;      // plan-owned device copies
+    FixRec *d_segs = nullptr;
+    int64_t n_slots = 0;          // pieces in the workspace
+    int64_t rowlen = 0;           // elements per row
+    size_t slot_offset = 0;       // byte offsets inside the workspace: the pieces ...
+    size_t seg_offset = 0;        // ... and the segment sums
+};
 
 struct Intermediate {
     std::string name;   // e.g. "T(i,j,m)"
@@ -97,13 +109,10 @@ struct sc_plan {
 
     size_t ws_bytes = 0;
     bool deterministic = false;
-    std::vector<sck::FixRec> fix;     // rows spanning several tiles (deterministic schedules only): second pass
-    std::vector<sck::FixRec> segs;    // their pieces in segments: first pass
-    sck::FixRec *d_fix = nullptr;     // plan-owned device copies
-    sck::FixRec *d_segs = nullptr;
-    int64_t n_slots = 0;              // pieces in the workspace
-    size_t det_offset = 0;            // byte offset of the slots inside the workspace
-    size_t seg_offset = 0;            // byte offset of the segment sums
+    sck::FixLevel det_top;   // output rows (slices) that span tiles; slot numbers in TileRec::pad[0] / pad[1]
+    sck::FixLevel det_a;     // FISSIONED, order 3: rows of the temporary (leaf fibers) that span tiles; a tile's
+                             // pieces are numbered TileRec::pad[2] (first fiber, if it continues from the
+                             // previous tile) and the next number (last fiber, if it continues into the next)
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 

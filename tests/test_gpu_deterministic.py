@@ -27,7 +27,8 @@ def _run_twice(cfg, data, which="fused"):
     return outs
 
 
-@pytest.mark.parametrize("cid,scale,which", [(1, 1.0, "fused"), (2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
+@pytest.mark.parametrize("cid,scale,which", [(1, 1.0, "fused"), (1, 1.0, "fissioned"), (2, 0.004, "fissioned"), (2, 0.02, "fissioned"),
+                                             (3, 0.003, "fissioned"), (3, 0.01, "fissioned"), (2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
                                              (4, 0.003, "fused"), (4, 0.01, "fissioned"), (5, 0.004, "fused")])
 def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
     cfg = synth.config(cid, scale)
@@ -40,23 +41,25 @@ def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
 
 
 @pytest.mark.parametrize("name", ["one_slice", "one_fiber", "count_3072", "single"])
-@pytest.mark.parametrize("kind", ["mttkrp3", "ttmc3", "sddmm_spmm", "ttmc4"])
-def test_deterministic_degenerate_structures(oracle, kind, name):
+@pytest.mark.parametrize("kind,which", [("mttkrp3", "fused"), ("mttkrp3", "fissioned"), ("ttmc3", "fused"), ("ttmc3", "fissioned"),
+                                        ("sddmm_spmm", "fused"), ("sddmm_spmm", "fissioned"), ("ttmc4", "fused")])
+def test_deterministic_degenerate_structures(oracle, kind, which, name):
     cfg, data = _case(kind, name)
-    print(f"{kind} {name} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)
-    outs = _run_twice(cfg, data)
+    print(f"{kind} {name} {which} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data, which)
     assert_parity(oracle, cfg, data, outs[0])
     for o in outs[1:]:
         assert o.tobytes() == outs[0].tobytes()
 
 
+@pytest.mark.parametrize("which", ["fused", "fissioned"])
 @pytest.mark.parametrize("dtype,ranks", [("f32", (8, 32)), ("f32", (32, 8)), ("f64", (16, 16)), ("f64", (4, 64))])
-def test_deterministic_general_outer_product_kernel(oracle, dtype, ranks):
+def test_deterministic_general_outer_product_kernel(oracle, dtype, ranks, which):
     """The order-3 chain at ranks / precisions the matrix-core kernel does not cover."""
     cfg = dict(synth.config(3, 0.003), dtype=dtype, ranks=ranks)
     data = synth.generate(cfg)
-    print(f"order-3 chain {dtype} ranks {ranks} deterministic nnz={cfg['nnz']}", flush=True)
-    outs = _run_twice(cfg, data)
+    print(f"order-3 chain {dtype} ranks {ranks} {which} deterministic nnz={cfg['nnz']}", flush=True)
+    outs = _run_twice(cfg, data, which)
     assert_parity(oracle, cfg, data, outs[0])
     for o in outs[1:]:
         assert o.tobytes() == outs[0].tobytes()

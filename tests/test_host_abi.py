@@ -148,7 +148,7 @@ def test_expression_family():
     assert _status(sc.plan_create, cfg["expr"], csf, [f[1], f[0]], ok) == "SC_ERR_SHAPE_MISMATCH"   # rows != dims
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0].astype(np.float64), f[1]], ok) == "SC_ERR_BAD_DTYPE"
     assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("linear")) == "SC_ERR_SCHED_UNSUPPORTED"
-    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("fissioned", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.Schedule(kind=sc.SC_SCHED_FUSED, deterministic=2)) == "SC_ERR_SCHED_UNSUPPORTED"
     odd = np.ones((cfg["dims"][2], 12), np.float32)   # a rank no kernel is instantiated for
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0], odd], ok) == "SC_ERR_SCHED_UNSUPPORTED"
 
@@ -325,6 +325,31 @@ def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scal
 
 
 def test_deterministic_is_refused_where_no_kernel_provides_it():
-    for cid, scale, which in [(1, 1.0, "fissioned"), (3, 0.003, "fissioned"), (2, 0.004, "fissioned"), (5, 0.004, "fissioned")]:
-        cfg, data, csf = _small(cid, scale)
-        assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    cfg, data, csf = _small(5, 0.004)
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fissioned", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    cfg = synth.config(5, 0.004)
+    cfg["dtype"] = "f64"
+    data = synth.generate(cfg)
+    csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+
+
+@pytest.mark.parametrize("cid,scale", [(1, 1.0), (2, 0.004), (3, 0.003)])
+def test_deterministic_fissioned_plan_also_numbers_the_rows_of_the_temporary(cid, scale):
+    cfg, data, csf = _small(cid, scale)
+    det = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned", deterministic=True))
+    plain = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned"))
+    text = sc.plan_describe(det)
+    m = re.search(r"deterministic: (\d+) rows of T\S* span several tiles; (\d+) pieces \((\d+) segments\)", text)
+    rows, pieces, segments = (int(x) for x in m.groups()) if m else (0, 0, 0)   # no line when no fiber spans tiles
+    want_rows = want_pieces = 0
+    for i in range(sc.plan_tile_count(det)):
+        rec = sc.plan_tile(det, i)
+        fl, na = rec[8], rec[3]
+        if fl & 1:
+            want_pieces += 1
+        if (fl & 2) and not ((fl & 1) and na == 1):
+            want_pieces += 1
+            want_rows += 1
+    assert (rows, pieces) == (want_rows, want_pieces)
+    assert sc.plan_workspace_bytes(det) > sc.plan_workspace_bytes(plain) > 0
