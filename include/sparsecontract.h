@@ -123,9 +123,10 @@ typedef struct {
  *                    kernel adds the pieces in tile order, so two executions of a plan give
  *                    bit-identical results.  Available for both schedules of the SDDMM -> SpMM
  *                    pair, of the MTTKRP and of the order-3 TTM chain (any supported rank, fp32 /
- *                    fp64; under FISSIONED the rows of the temporary that span tiles are treated
- *                    the same way), and for the FUSED schedule of the fp32 order-4 TTM chain;
- *                    SC_ERR_SCHED_UNSUPPORTED otherwise.  sc_plan_workspace_bytes then includes the pieces. */
+ *                    fp64) and of the fp32 order-4 TTM chain; under FISSIONED the rows of the
+ *                    temporaries that span tiles are treated the same way.  The fp64 order-4
+ *                    chain returns SC_ERR_SCHED_UNSUPPORTED.  sc_plan_workspace_bytes then
+ *                    includes the pieces. */
 typedef struct {
     sc_sched_kind kind;
     int32_t n_intermediates;

@@ -466,12 +466,12 @@ void assign_piece_slots(sc_plan *p, const HostCsf &h)
     top.n_slots = next;
     make_segments(top);
 
-    // FISSIONED, order 3: rows of the temporary, one per leaf fiber (level "a", flag bits 1 / 2)
+    // FISSIONED, order >= 3: rows of the first temporary, one per leaf fiber (level "a", flag bits 1 / 2)
     FixLevel &la = p->det_a;
     la.fix.clear();
     la.n_slots = 0;
-    if (p->sched == SC_SCHED_FISSIONED && p->order == 3) {
-        la.rowlen = p->kind == K_TTMC3 ? p->fcols[1] : p->fcols[0];   // width of the temporary's rows
+    if (p->sched == SC_SCHED_FISSIONED && p->order >= 3) {
+        la.rowlen = p->kind == K_TTMC4 ? p->fcols[2] : p->kind == K_TTMC3 ? p->fcols[1] : p->fcols[0];   // width of the temporary's rows
         next = 0;
         for (TileRec &t : p->tiles) {
             const bool in = (t.flags & 1) != 0, out = (t.flags & 2) != 0;
@@ -491,6 +491,34 @@ void assign_piece_slots(sc_plan *p, const HostCsf &h)
         }
         la.n_slots = next;
         make_segments(la);
+    }
+
+    // FISSIONED, order 4: rows of the second temporary, one per level-b node (flag bits 4 / 8)
+    FixLevel &lb = p->det_b;
+    lb.fix.clear();
+    lb.n_slots = 0;
+    p->slot_b.clear();
+    if (p->sched == SC_SCHED_FISSIONED && p->order == 4) {
+        lb.rowlen = p->fcols[1] * p->fcols[2];
+        next = 0;
+        for (const TileRec &t : p->tiles) {
+            const bool in = (t.flags & 4) != 0, out = (t.flags & 8) != 0;
+            p->slot_b.push_back(next);
+            if (in) {
+                ++next;
+                lb.fix.back().count++;
+            }
+            if (out && !(in && t.nb == 1)) {
+                FixRec f;
+                f.row = t.b0 + t.nb - 1;   // position of the node = row of the temporary
+                f.first = next++;
+                f.count = 1;
+                f.pad = 0;
+                lb.fix.push_back(f);
+            }
+        }
+        lb.n_slots = next;
+        make_segments(lb);
     }
 }
 
@@ -792,7 +820,7 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         for (int t = 0; t < p->n_inter; ++t) p->inter[t].offset = 0;
     }
     if (p->deterministic) {
-        for (FixLevel *lv : {&p->det_top, &p->det_a}) {
+        for (FixLevel *lv : {&p->det_top, &p->det_a, &p->det_b}) {
             if (!lv->n_slots) continue;
             const size_t row_bytes = (size_t)lv->rowlen * esize(p->dtype);
             lv->slot_offset = (p->ws_bytes + 255) & ~(size_t)255;
@@ -849,6 +877,9 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         if (p->det_a.n_slots)
             appendf(tx, "deterministic: %zu rows of %s span several tiles; %lld pieces (%zu segments)\n", p->det_a.fix.size(),
                     p->inter[0].name.c_str(), (long long)p->det_a.n_slots, p->det_a.segs.size());
+        if (p->det_b.n_slots)
+            appendf(tx, "deterministic: %zu rows of %s span several tiles; %lld pieces (%zu segments)\n", p->det_b.fix.size(),
+                    p->inter[1].name.c_str(), (long long)p->det_b.n_slots, p->det_b.segs.size());
     }
 
     // ---- device tables ----
@@ -870,13 +901,23 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
                 for (size_t t = r; t < nt; t += stride) order.push_back(p->tiles[t]);
             if (hipMemcpy(p->d_tiles, order.data(), sizeof(TileRec) * nt, hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
+            if (p->deterministic && p->slot_b.size() == nt) {   // same order as the tile table
+                std::vector<int32_t> sb;
+                try {
+                    sb.reserve(nt);
+                } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
+                for (size_t r = 0; r < stride; ++r)
+                    for (size_t t = r; t < nt; t += stride) sb.push_back(p->slot_b[t]);
+                if (hipMalloc((void **)&p->d_slot_b, sizeof(int32_t) * nt) != hipSuccess) return SC_ERR_DEVICE;
+                if (hipMemcpy(p->d_slot_b, sb.data(), sizeof(int32_t) * nt, hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
+            }
         }
         if (p->zero_selective && !p->zero_rows.empty()) {
             if (hipMalloc((void **)&p->d_zero_rows, sizeof(int32_t) * p->zero_rows.size()) != hipSuccess) return SC_ERR_DEVICE;
             if (hipMemcpy(p->d_zero_rows, p->zero_rows.data(), sizeof(int32_t) * p->zero_rows.size(), hipMemcpyHostToDevice) != hipSuccess)
                 return SC_ERR_DEVICE;
         }
-        for (FixLevel *lv : {&p->det_top, &p->det_a}) {
+        for (FixLevel *lv : {&p->det_top, &p->det_a, &p->det_b}) {
             if (lv->fix.empty()) continue;
             if (hipMalloc((void **)&lv->d_fix, sizeof(FixRec) * lv->fix.size()) != hipSuccess) return SC_ERR_DEVICE;
             if (hipMemcpy(lv->d_fix, lv->fix.data(), sizeof(FixRec) * lv->fix.size(), hipMemcpyHostToDevice) != hipSuccess)
@@ -1015,7 +1056,8 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
 {
     if (!plan) return SC_OK;
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
-    for (sck::FixLevel *lv : {&plan->det_top, &plan->det_a}) {
+    if (plan->d_slot_b) (void)hipFree(plan->d_slot_b);
+    for (sck::FixLevel *lv : {&plan->det_top, &plan->det_a, &plan->det_b}) {
         if (lv->d_fix) (void)hipFree(lv->d_fix);
         if (lv->d_segs) (void)hipFree(lv->d_segs);
     }

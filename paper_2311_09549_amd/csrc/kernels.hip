@@ -762,7 +762,7 @@ bool plan_supports_deterministic(const sc_plan *p)
 {
     if (p->kind == K_SDDMM_SPMM) return true;   // both schedules: the sampled values have one writer each
     if (p->kind == K_MTTKRP3 || p->kind == K_TTMC3) return true;   // both schedules
-    return p->sched == SC_SCHED_FUSED && plan_wants_tensor_order(p);   // order 4: the fp32 FUSED kernel
+    return plan_wants_tensor_order(p);   // order 4: the fp32 matrix-core kernels, both schedules
 }
 
 sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void *ws, void *dst)

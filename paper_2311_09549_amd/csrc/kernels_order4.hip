@@ -254,16 +254,31 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         }
         ln.end();
     } else {
-        sc_status st = launch_leaf_producer(p, ln, sp->pos[3], sp->crd[3], sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse", nullptr);
+        // deterministic (matrix-core kernels): each kernel stores its pieces of the rows that span tiles
+        // in slots, and a fix-up adds them in tile order before the next kernel reads the rows
+        const bool det = p->deterministic && ws && mfma;
+        char *wsb = static_cast<char *>(ws);
+        sc_status st = launch_leaf_producer(p, ln, sp->pos[3], sp->crd[3], sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse",
+                                            det ? wsb + p->det_a.slot_offset : nullptr);
         if (st != SC_OK) return st;
-        ln.begin("zero_shared_rows_t2");
-        zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 1, static_cast<T *>(a.T2), M * N);
-        ln.end();
-        if (mfma) {
-            st = launch_ttmc4_mfma(p, ln, sp, fac, 1, a.T1, a.T2, out, nullptr);
+        if (det) {
+            st = launch_fixup(p, ln, p->det_a, ws, a.T1);
             if (st != SC_OK) return st;
-            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 2, a.T1, a.T2, out, nullptr);
-            return ln.status;
+        } else {
+            ln.begin("zero_shared_rows_t2");
+            zero_shared_rows_kernel<T><<<(ntiles + 3) / 4, NT, 0, stream>>>(p->d_tiles, ntiles, 1, static_cast<T *>(a.T2), M * N);
+            ln.end();
+        }
+        if (mfma) {
+            st = launch_ttmc4_mfma(p, ln, sp, fac, 1, a.T1, a.T2, out, det ? wsb + p->det_b.slot_offset : nullptr);
+            if (st != SC_OK) return st;
+            if (det) {
+                st = launch_fixup(p, ln, p->det_b, ws, a.T2);
+                if (st != SC_OK) return st;
+            }
+            ln.status = launch_ttmc4_mfma(p, ln, sp, fac, 2, a.T1, a.T2, out, det ? wsb + p->det_top.slot_offset : nullptr);
+            if (ln.status != SC_OK || !det) return ln.status;
+            return launch_fixup(p, ln, p->det_top, ws, out);
         }
         ln.begin("ttmc4_middle");
         order4_kernel<T, N, M, 2><<<ntiles, NT, lds, stream>>>(a);

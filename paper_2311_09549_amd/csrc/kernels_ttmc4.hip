@@ -35,6 +35,7 @@ struct Ttmc4Args {
     float *T2;         // MODE 1 writes, MODE 2 reads: one 64-wide row per f2 fiber
     float *A;
     float *partials;   // deterministic schedules: slots for the pieces of rows that span tiles (runs are single tiles then), else null
+    const int32_t *slot_b;   // deterministic MODE 1: first slot of each tile's pieces of T2 rows
     int32_t L;
     int32_t tn, ta, tb;
     int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
@@ -77,7 +78,8 @@ __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb, int
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
 
-// DET: the deterministic variant of MODE 0 (pieces of rows that span tiles go to plan-numbered slots).
+// DET: the deterministic variants (pieces of rows that span tiles go to plan-numbered slots: rows of A in
+// MODE 0 and 2, rows of T2 in MODE 1).
 template <int MODE, bool DET>
 __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileRec *__restrict__ tiles)
 {
@@ -333,6 +335,10 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                 if (!shared) {
                     // written once, read by the next kernel only: non-temporal
                     __builtin_nontemporal_store(__builtin_bit_cast(t4_floatx4, row), reinterpret_cast<t4_floatx4 *>(dst));
+                } else if (DET) {
+                    // the piece of the tile's first node is numbered slot_b[tile], that of its last node follows
+                    const int slot = a.slot_b[tile] + ((r == 0 && (t.flags & 4)) ? 0 : ((t.flags & 4) >> 2));
+                    *reinterpret_cast<P *>(a.partials + (int64_t)slot * T4_W2 + li * 4) = row;
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) atomic_add(dst + i, row.v[i]);
@@ -438,6 +444,8 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
     const int want = partials ? ntiles : std::min(ntiles, 256 * per_cu);
     a.partials = static_cast<float *>(partials);
+    a.slot_b = p->d_slot_b;
+    if (partials && mode == 1 && !p->d_slot_b) return SC_ERR_SCHED_UNSUPPORTED;
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;
     const int blocks = (ntiles + a.run - 1) / a.run;
@@ -449,10 +457,16 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
             ttmc4_mfma_kernel<0, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else if (mode == 1) {
         ln.begin("ttmc4_middle");
-        ttmc4_mfma_kernel<1, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        if (partials)
+            ttmc4_mfma_kernel<1, true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        else
+            ttmc4_mfma_kernel<1, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     } else {
         ln.begin("ttmc4_consume_mfma");
-        ttmc4_mfma_kernel<2, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        if (partials)
+            ttmc4_mfma_kernel<2, true><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
+        else
+            ttmc4_mfma_kernel<2, false><<<blocks, NT, lds, ln.stream>>>(a, p->d_tiles);
     }
     ln.end();
     return ln.status;

@@ -41,7 +41,7 @@ struct TileCaps {
     int32_t tb;  // level-b nodes (order 4 only; for order 3 the slice count is bounded by ta)
 };
 
-constexpr int kMaxLaunches = 8;
+constexpr int kMaxLaunches = 12;
 
 // Deterministic schedules: an output row whose slice spans several tiles is not updated with
 // atomics; every tile stores its piece of the row in a slot of the workspace (the two slot
@@ -110,9 +110,13 @@ struct sc_plan {
     size_t ws_bytes = 0;
     bool deterministic = false;
     sck::FixLevel det_top;   // output rows (slices) that span tiles; slot numbers in TileRec::pad[0] / pad[1]
-    sck::FixLevel det_a;     // FISSIONED, order 3: rows of the temporary (leaf fibers) that span tiles; a tile's
-                             // pieces are numbered TileRec::pad[2] (first fiber, if it continues from the
+    sck::FixLevel det_a;     // FISSIONED, order >= 3: rows of the first temporary (leaf fibers) that span tiles; a
+                             // tile's pieces are numbered TileRec::pad[2] (first fiber, if it continues from the
                              // previous tile) and the next number (last fiber, if it continues into the next)
+    sck::FixLevel det_b;     // FISSIONED, order 4: rows of the second temporary (level-b nodes) that span tiles,
+                             // numbered the same way from slot_b[tile]
+    std::vector<int32_t> slot_b;
+    int32_t *d_slot_b = nullptr;   // plan-owned device copy, in the order of the device tile table
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 

@@ -29,7 +29,7 @@ def _run_twice(cfg, data, which="fused"):
 
 @pytest.mark.parametrize("cid,scale,which", [(1, 1.0, "fused"), (1, 1.0, "fissioned"), (2, 0.004, "fissioned"), (2, 0.02, "fissioned"),
                                              (3, 0.003, "fissioned"), (3, 0.01, "fissioned"), (2, 0.004, "fused"), (2, 0.02, "fused"), (3, 0.003, "fused"), (3, 0.01, "fused"),
-                                             (4, 0.003, "fused"), (4, 0.01, "fissioned"), (5, 0.004, "fused")])
+                                             (4, 0.003, "fused"), (4, 0.01, "fissioned"), (5, 0.004, "fused"), (5, 0.004, "fissioned"), (5, 0.02, "fissioned")])
 def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
     cfg = synth.config(cid, scale)
     data = synth.generate(cfg)
@@ -42,7 +42,7 @@ def test_deterministic_parity_and_repeatability(oracle, cid, scale, which):
 
 @pytest.mark.parametrize("name", ["one_slice", "one_fiber", "count_3072", "single"])
 @pytest.mark.parametrize("kind,which", [("mttkrp3", "fused"), ("mttkrp3", "fissioned"), ("ttmc3", "fused"), ("ttmc3", "fissioned"),
-                                        ("sddmm_spmm", "fused"), ("sddmm_spmm", "fissioned"), ("ttmc4", "fused")])
+                                        ("sddmm_spmm", "fused"), ("sddmm_spmm", "fissioned"), ("ttmc4", "fused"), ("ttmc4", "fissioned")])
 def test_deterministic_degenerate_structures(oracle, kind, which, name):
     cfg, data = _case(kind, name)
     print(f"{kind} {name} {which} deterministic dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)

@@ -69,17 +69,18 @@ def test_parity_full(oracle, cid, n_heavy, n_random, which):
     del con
 
 
+@pytest.mark.parametrize("which", ["fused", "fissioned"])
 @pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000), (4, None, None), (5, 10, 500)])
-def test_parity_full_deterministic(oracle, cid, n_heavy, n_random):
-    """The deterministic FUSED schedules at full size: same bar, and a second execution of the
-    plan reproduces the first bit for bit (the heaviest slices span thousands of tiles)."""
+def test_parity_full_deterministic(oracle, cid, n_heavy, n_random, which):
+    """The deterministic schedules at full size: same bar, and a second execution of the plan
+    reproduces the first bit for bit (the heaviest slices span thousands of tiles)."""
     from paper_2311_09549_amd import binding as sc
     from paper_2311_09549_amd.driver import Contraction
 
     cfg, data = _get(cid)
-    print(f"config {cid} full size deterministic nnz={cfg['nnz']}", flush=True)
+    print(f"config {cid} full size {which} deterministic nnz={cfg['nnz']}", flush=True)
     con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
-                      sc.schedule("fused", deterministic=True), synth.output_shape(cfg))
+                      sc.schedule(which, deterministic=True), synth.output_shape(cfg))
     con.run()
     got = con.result().copy()
     con.out.fill_(float("nan"))

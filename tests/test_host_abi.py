@@ -325,13 +325,34 @@ def test_deterministic_plan_numbers_the_pieces_of_rows_that_span_tiles(cid, scal
 
 
 def test_deterministic_is_refused_where_no_kernel_provides_it():
-    cfg, data, csf = _small(5, 0.004)
-    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fissioned", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
     cfg = synth.config(5, 0.004)
-    cfg["dtype"] = "f64"
+    cfg["dtype"] = "f64"   # the fp64 order-4 kernel sums with LDS atomics
     data = synth.generate(cfg)
     csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
-    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    for which in ("fused", "fissioned"):
+        assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+
+
+def test_deterministic_fissioned_order4_plan_numbers_the_rows_of_both_temporaries():
+    cfg, data, csf = _small(5, 0.004)
+    det = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned", deterministic=True))
+    plain = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fissioned"))
+    text = sc.plan_describe(det)
+    found = {name: (int(r), int(p)) for r, name, p in re.findall(r"deterministic: (\d+) rows of (T\d)\S* span several tiles; (\d+) pieces", text)}
+    want = {"T1": [0, 0], "T2": [0, 0]}
+    for i in range(sc.plan_tile_count(det)):
+        rec = sc.plan_tile(det, i)
+        fl, na, nb = rec[8], rec[3], rec[5]
+        for name, bit_in, bit_out, n in (("T1", 1, 2, na), ("T2", 4, 8, nb)):
+            if fl & bit_in:
+                want[name][1] += 1
+            if (fl & bit_out) and not ((fl & bit_in) and n == 1):
+                want[name][1] += 1
+                want[name][0] += 1
+    for name in ("T1", "T2"):
+        assert found.get(name, (0, 0)) == tuple(want[name])
+    assert want["T2"][0] > 0   # the skewed tensor has level-b nodes cut by tile boundaries
+    assert sc.plan_workspace_bytes(det) > sc.plan_workspace_bytes(plain) > 0
 
 
 @pytest.mark.parametrize("cid,scale", [(1, 1.0), (2, 0.004), (3, 0.003)])
