@@ -77,9 +77,9 @@ __device__ __forceinline__ void leaf_issue(const LeafArgs &a, const TileRec &t, 
     for (int r = 0; r < LeafStage<T>::MAXB; ++r) s.bb[r] = a.pos[t.a0 + min(tid + r * LNT, t.na)];
 }
 
-// Persistent workgroups: workgroup b handles tiles b, b + gridDim.x, ...  While one tile is
-// walked, the staging reads of the next are already in flight, and the row stores of the
-// previous tile drain behind them, so the three phases of consecutive tiles overlap.
+// Workgroup b handles tiles b, b + gridDim.x, ... (the launch is persistent for wide rows and
+// has one workgroup per tile for narrow ones).  While one tile is walked, the staging reads of
+// the next are already in flight, and the row stores of the previous tile drain behind them.
 // DET: the deterministic variant (the pieces of a row shared with a neighbouring tile go to the
 // tile's slots instead of being added atomically).
 template <typename T, int W, bool DET>
@@ -215,12 +215,16 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
         ln.end();
     }
     ln.begin(name);
-    // persistent launch: as many workgroups as fit on the chip at once (LDS-limited), never more than tiles
+    // Wide rows (LDS lets at most three workgroups reside on a compute unit): persistent launch, as
+    // many workgroups as fit on the chip at once, each looping over tiles.  Narrow rows: one
+    // workgroup per tile, which lets the dispatcher even out tiles of different cost (measured 5 to
+    // 9 % faster on the order-3 chain with 16-wide rows and the order-4 chain with 8-wide rows, 10 %
+    // slower on the 32-wide rows of the MTTKRP).
     a.ntiles = ntiles;
     const size_t lds = leaf_lds_bytes<T>(W, a.tn, a.ta);
     const int fit = lds_workgroups_per_cu(lds);
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 16) : fit;
-    const int blocks = std::min(ntiles, 256 * per_cu);
+    const int blocks = (tuning().per_cu == 0 && fit > 3) ? ntiles : std::min(ntiles, 256 * per_cu);
     if (partials)
         leaf_traverse_kernel<T, W, true><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
     else
