@@ -80,6 +80,10 @@ def lib():
             raise ImportError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2311_09549_amd.build` "
                 "(there is no CPU fallback)")
+        # torch ships a HIP runtime of its own and must load it before this library does: the
+        # library then binds to that copy.  In the other order the process ends up with two
+        # runtimes and torch finds no device.
+        import torch  # noqa: F401
         _lib = ctypes.CDLL(LIB_PATH)
         _lib.sc_status_string.restype = ctypes.c_char_p
         _lib.sc_status_string.argtypes = [ctypes.c_int]
