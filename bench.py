@@ -43,6 +43,7 @@ def main() -> int:
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
+    ap.add_argument("--no-linear", action="store_true", help="skip the LINEAR (unfactored) nest, the baseline the paper's speedups are quoted against")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also queue and time the library's plain copy kernel (1 GiB), for counter runs")
     args = ap.parse_args()
@@ -190,6 +191,17 @@ def main() -> int:
                                                 "frac": tb / (kt_f[n] * 1e-3) / 1e9 / HBM_PEAK_GBS}
         result["fused_vs_fissioned_speedup"] = ms_f / ms
         del fis
+        torch.cuda.empty_cache()
+
+    if not args.no_linear:
+        # the unfactored nest on the same GPU: what the fused schedule is a rewrite of (few steps: it is slow by design)
+        lin = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                          sc.schedule("linear"), out_shape)
+        flops_lin, _ = sc.plan_model(lin.plan)
+        ms_l = timed(lin, max(3, min(args.steps, 10)), 1)
+        result["linear"] = {"ms_per_step": ms_l, "nest_flops": flops_lin, "gflops": flops_lin / (ms_l * 1e-3) / 1e9}
+        result["fused_vs_linear_speedup"] = ms_l / ms
+        del lin
         torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:

@@ -60,7 +60,10 @@ typedef enum {
 
 typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
 
-/* Schedule classes of Section 4.2: LINEAR = the perfectly nested default nest;
+/* Schedule classes of Section 4.2: LINEAR = the perfectly nested default nest, run
+ * unfactored (every stored entry times one element of every factor for every combination
+ * of the dense output indices): the baseline of the other two, any rank, fp32 / fp64, no
+ * temporary, no workspace, sums combined with atomics (deterministic must be 0);
  * FISSIONED = producer and consumer split, the temporary fully materialised (in the
  * workspace, in HBM); FUSED = producer and consumer fused under their common outer
  * loops, the live temporary kept on chip (registers / LDS). */

@@ -397,6 +397,9 @@ TopLevel top_level(int order, const TileRec &t)
 // atomically.  Every other row is stored whole by the one tile that holds its slice.
 void list_rows_to_zero(sc_plan *p, const HostCsf &h)
 {
+    p->zero_rows.clear();
+    p->zero_selective = false;
+    if (p->sched == SC_SCHED_LINEAR) return;   // every row is accumulated atomically: the whole output starts at zero
     const int64_t rows = p->dims[0];
     std::vector<char> stored((size_t)rows, 0);
     for (int64_t s = 0; s < p->nfib[0]; ++s) stored[(size_t)h.crd[0][s]] = 1;
@@ -708,11 +711,14 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     p->out_elems = p->dims[0] * p->out_row_elems;
 
     // ---- schedule ----
-    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    if (sched->kind != SC_SCHED_LINEAR && sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
     p->deterministic = sched->deterministic == 1;
     p->sched = sched->kind;
-    p->n_inter = (int32_t)fam.temp_idx.size();
+    const bool linear = sched->kind == SC_SCHED_LINEAR;
+    // LINEAR: the unfactored nest has no temporary, and its row sums are combined with atomics only
+    if (linear && (sched->n_intermediates != 0 || p->deterministic)) return SC_ERR_SCHED_UNSUPPORTED;
+    p->n_inter = linear ? 0 : (int32_t)fam.temp_idx.size();
     if (sched->n_intermediates != 0 && sched->n_intermediates != p->n_inter) return SC_ERR_SCHED_UNSUPPORTED;
     for (int t = 0; t < p->n_inter; ++t) {
         p->inter[t].name = join(fam.temp_name[t], fam.temp_idx[t]);
@@ -744,7 +750,8 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     }
 
     // ---- tiles ----
-    p->caps = default_caps(p->kind, p->dtype, p->sched, p->fcols);
+    p->caps = linear ? TileCaps{1024, 1024, 1024}   // node caps that never bind: the kernel keeps no per-node state
+                     : default_caps(p->kind, p->dtype, p->sched, p->fcols);
     if (p->caps.tn <= 0) return SC_ERR_SCHED_UNSUPPORTED;  // no kernel instantiated for these ranks
     const Tuning &tu = tuning();
     if (tu.tn) p->caps.tn = tu.tn;
@@ -812,6 +819,10 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         break;
     }
     }
+    if (linear) {   // every stored entry times every combination of the dense output indices (and of k for the SDDMM)
+        const double per = p->kind == K_SDDMM_SPMM ? 4.0 * (double)p->fcols[0] : (double)(p->nfactors + 1);
+        flops = per * (double)p->out_row_elems * nnz;
+    }
     if (p->sched == SC_SCHED_FISSIONED) {
         bytes += extra;
         p->ws_bytes = off;
@@ -833,9 +844,13 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
 
     std::string &tx = p->text;
     appendf(tx, "expression: %s\n", expr);
-    appendf(tx, "schedule: %s\n", p->sched == SC_SCHED_FUSED ? "FUSED (temporaries on chip)" : "FISSIONED (temporaries in the workspace)");
+    appendf(tx, "schedule: %s\n", linear ? "LINEAR (the unfactored nest, no temporary)"
+                                  : p->sched == SC_SCHED_FUSED ? "FUSED (temporaries on chip)" : "FISSIONED (temporaries in the workspace)");
     const std::vector<std::string> &si = rhs[0].idx;
-    switch (p->kind) {
+    if (linear)
+        appendf(tx, "nest: forall(entries of %s, forall(dense indices, %s += product of one element of every operand))\n", rhs[0].name.c_str(),
+                join(lhs.name, lhs.idx).c_str());
+    else switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3: {
         const std::string x = fam.temp_idx[0][2];

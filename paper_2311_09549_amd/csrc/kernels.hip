@@ -799,6 +799,7 @@ bool plan_wants_tensor_order(const sc_plan *p)
 
 size_t lds_bytes_needed(const sc_plan *p)
 {
+    if (p->sched == SC_SCHED_LINEAR) return linear_lds_bytes(p);
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:
@@ -837,6 +838,7 @@ size_t lds_bytes_needed(const sc_plan *p)
 sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
     p->n_launch = 0;
+    if (p->sched == SC_SCHED_LINEAR) return launch_linear(p, sp, fac, out, stream);
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:

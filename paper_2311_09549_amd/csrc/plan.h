@@ -159,6 +159,9 @@ sc_status launch_plan(const sc_plan *plan, const sc_csf_view *sp, const sc_dense
 // Per-family pieces behind the three functions above (one kernel file each).
 TileCaps order2_caps(sc_dtype dtype, const int64_t *fcols);
 size_t order2_lds_bytes_needed(const sc_plan *plan);
+// LINEAR schedule (kernels_linear.hip): the unfactored nest, every expression family.
+size_t linear_lds_bytes(const sc_plan *plan);
+sc_status launch_linear(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, hipStream_t stream);
 sc_status launch_order2(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,
                         hipStream_t stream);
 TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols);

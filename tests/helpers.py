@@ -11,6 +11,8 @@ TOL = {"f32": 1e-5, "f64": 1e-12}   # |gpu - oracle| <= TOL * sum|partial produc
 def default_schedule(kind, which):
     names = {"ttmc3": ["T(i,j,m)"], "mttkrp3": ["T(i,j,r)"], "sddmm_spmm": ["T(i,j)"],
              "ttmc4": ["T1(i,j,k,n)", "T2(i,j,m,n)"]}[kind]
+    if which == "linear":
+        return sc.schedule("linear")
     if which == "fused":
         return sc.schedule("fused", names, [0] * len(names))
     return sc.schedule("fissioned", names, [0] * len(names))

@@ -147,7 +147,8 @@ def test_expression_family():
     assert _status(sc.plan_create, cfg["expr"], csf, f[:1], ok) == "SC_ERR_SHAPE_MISMATCH"
     assert _status(sc.plan_create, cfg["expr"], csf, [f[1], f[0]], ok) == "SC_ERR_SHAPE_MISMATCH"   # rows != dims
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0].astype(np.float64), f[1]], ok) == "SC_ERR_BAD_DTYPE"
-    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("linear")) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.schedule("linear", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, f, sc.Schedule(kind=7)) == "SC_ERR_SCHED_UNSUPPORTED"
     assert _status(sc.plan_create, cfg["expr"], csf, f, sc.Schedule(kind=sc.SC_SCHED_FUSED, deterministic=2)) == "SC_ERR_SCHED_UNSUPPORTED"
     odd = np.ones((cfg["dims"][2], 12), np.float32)   # a rank no kernel is instantiated for
     assert _status(sc.plan_create, cfg["expr"], csf, [f[0], odd], ok) == "SC_ERR_SCHED_UNSUPPORTED"
@@ -374,3 +375,23 @@ def test_deterministic_fissioned_plan_also_numbers_the_rows_of_the_temporary(cid
             want_rows += 1
     assert (rows, pieces) == (want_rows, want_pieces)
     assert sc.plan_workspace_bytes(det) > sc.plan_workspace_bytes(plain) > 0
+
+
+@pytest.mark.parametrize("cid,scale", [(1, 1.0), (2, 0.002), (3, 0.002), (4, 0.002), (5, 0.002)])
+def test_linear_plan_counts_the_unfactored_nest(cid, scale):
+    """LINEAR plans: no temporary, no workspace, and the flop model is the unfactored count
+    (a multiply per operand and an add, for every stored entry and every combination of the
+    dense output indices; Section 1 gives nnz * L * M for the order-3 chain)."""
+    cfg, data, csf = _small(cid, scale)
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("linear"))
+    ranks = [f.shape[1] for f in data["factors"]]
+    nnz = csf.nnz
+    want = {"ttmc3": 3 * ranks[0] * ranks[1] * nnz, "mttkrp3": 3 * ranks[0] * nnz,
+            "sddmm_spmm": 4 * ranks[0] * ranks[2] * nnz if cfg["kind"] == "sddmm_spmm" else 0,
+            "ttmc4": 4 * int(np.prod(ranks)) * nnz}[cfg["kind"]]
+    assert sc.plan_model(plan)[0] == want
+    assert sc.plan_workspace_bytes(plan) == 0
+    text = sc.plan_describe(plan)
+    assert "LINEAR" in text and "temporary 0" not in text
+    fused = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+    assert sc.plan_model(fused)[0] < want or cfg["dims"][0] < 300
