@@ -50,7 +50,7 @@ def _sample_rows(data, dims0, n_heavy, n_random, seed):
     return np.unique(np.concatenate([heavy, rest]))
 
 
-@pytest.mark.parametrize("which", ["fused", "fissioned"])
+@pytest.mark.parametrize("which", ["fused", "fissioned", "linear"])
 @pytest.mark.parametrize("cid,n_heavy,n_random", [(2, None, None), (3, 40, 3000), (4, None, None), (5, 10, 500)])
 def test_parity_full(oracle, cid, n_heavy, n_random, which):
     cfg, data = _get(cid)
