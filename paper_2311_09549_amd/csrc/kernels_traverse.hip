@@ -168,19 +168,43 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
 
         // ---- flush ----
         T *Tout = static_cast<T *>(a.Tout) + (int64_t)t.a0 * W;
-        for (int r = g; r < na; r += G) {
-            const P row = *reinterpret_cast<const P *>(row_s + r * RS + li * VEC);
-            T *dst = Tout + (int64_t)r * W + li * VEC;
-            const bool shared = (r == 0 && (t.flags & 1)) || (r == na - 1 && (t.flags & 2));
-            if (!shared) {
-                nt_store16(dst, row);
-            } else if (DET) {
-                // the piece of the tile's first fiber is numbered pad[2], that of its last fiber follows
-                const int slot = t.pad[2] + ((r == 0 && (t.flags & 1)) ? 0 : (t.flags & 1));
-                *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
-            } else {
+        // Rows that only this tile holds leave in batches: the LDS reads of a batch are issued
+        // together, then its stores (no branch inside).  The at most two rows shared with a
+        // neighbouring tile are handled after the loop.
+        const bool sh0 = (t.flags & 1) != 0, sh1 = (t.flags & 2) != 0;
+        constexpr int FB = 8;
+        for (int r0 = g; r0 < na; r0 += FB * G) {
+            P rows[FB];
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+            for (int k = 0; k < FB; ++k) rows[k] = *reinterpret_cast<const P *>(row_s + min(r0 + k * G, na - 1) * RS + li * VEC);
+#pragma unroll
+            for (int k = 0; k < FB; ++k) {
+                const int r = r0 + k * G;
+                if (r < na && !(r == 0 && sh0) && !(r == na - 1 && sh1)) nt_store16(Tout + (int64_t)r * W + li * VEC, rows[k]);
+            }
+        }
+        {
+            // first row (continues from the previous tile) by lane group 0, last row (continues
+            // into the next tile) by the lane group that would have stored it
+            const bool first = sh0 && g == 0;
+            const bool last = sh1 && !(sh0 && na == 1) && g == (na - 1) % G;
+            if (first || last) {
+                const int r = first ? 0 : na - 1;
+                // a group can hold both roles only when they are different rows: do them in turn
+                for (int pass = 0; pass < 2; ++pass) {
+                    const int rr = pass == 0 ? r : na - 1;
+                    if (pass == 1 && !(first && last)) break;
+                    const P row = *reinterpret_cast<const P *>(row_s + rr * RS + li * VEC);
+                    T *dst = Tout + (int64_t)rr * W + li * VEC;
+                    if (DET) {
+                        // the piece of the tile's first fiber is numbered pad[2], that of its last fiber follows
+                        const int slot = t.pad[2] + ((rr == 0 && sh0) ? 0 : (sh0 ? 1 : 0));
+                        *reinterpret_cast<P *>(static_cast<T *>(a.partials) + (int64_t)slot * W + li * VEC) = row;
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) atomic_add(dst + i, row.v[i]);
+                    }
+                }
             }
         }
         if (!more) break;
