@@ -3,13 +3,16 @@
 
 A "step" is one sc_execute of the whole hot path (output fill, CSF traversal, on-chip
 temporary, consumer stage, cross-tile fix-up) of the FUSED schedule on one synthetic
-workload, with every input already resident in HBM.  The default workload is the MTTKRP
-configuration (50,000 x 20,000 x 10,000, 20 M Zipf(1.2) nonzeros, rank 32, fp32).
+workload, with every input already resident in HBM.  The metric is per contraction, so the
+default run measures all five benchmark workloads one after the other: the top-level
+`value`, `roofline` and `cpu_baseline` are those of the largest one (the order-4 TTM chain,
+50 M nonzeros), and `per_config` carries the same figures for each of the five.
 
-Prints ONE JSON line: effective GFLOP/s of the schedule (its own flop count, multiply and
-add counted separately, over the measured step time), a `roofline` object for the
-dominant kernel (algorithmic HBM bytes over its HIP-event-timed duration against 8 TB/s)
-and a `cpu_baseline` object (the fp64 oracle timed on the host cores in the same run).
+Prints ONE JSON line.  Per workload: effective GFLOP/s of the schedule (its own flop count,
+multiply and add counted separately, over the measured step time), a `roofline` object for
+the dominant kernel (algorithmic HBM bytes over its HIP-event-timed duration against
+8 TB/s), the FISSIONED schedule with its traversal kernel's achieved bandwidth, the LINEAR
+(unfactored) nest, the two speedups, and the fp64 oracle timed on the host cores.
 """
 from __future__ import annotations
 
@@ -24,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+HEADLINE = 5   # the largest single-GPU workload
 
 WORKLOAD_TEXT = {
     1: "configs[0]: TTM chain order 3, fp64, 200^3, 8,000 uniform nonzeros, L=M=8",
@@ -33,17 +37,24 @@ WORKLOAD_TEXT = {
     5: "configs[4]: TTM chain order 4, fp32, 10,000^4, 50M Zipf(1.1) nonzeros, L=M=N=8",
 }
 
+PAPER_CONTEXT = ("context only, other hardware and other baseline: the paper reports its fused schedules running "
+                 "orders of magnitude faster than the default TACO schedules on 4x Intel Xeon E5-4650 "
+                 "(32 cores, 2.7 GHz, 80 MB LLC, GCC 11.4 -O3 -ffast-math, median of 31 runs); it prints "
+                 "no GFLOP/s or GB/s figure for these five workloads")
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload id 1..5 (default 2, the headline)")
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (experiments only)")
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=0,
+                    help="measure only this workload (1..5); default: all five, headline on the largest")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workloads (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
-    ap.add_argument("--no-linear", action="store_true", help="skip the LINEAR (unfactored) nest, the baseline the paper's speedups are quoted against")
+    ap.add_argument("--no-linear", action="store_true",
+                    help="skip the LINEAR (unfactored) nest, the baseline the paper's speedups are quoted against")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also queue and time the library's plain copy kernel (1 GiB), for counter runs")
     args = ap.parse_args()
@@ -64,13 +75,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
 
-    cfg = synth.config(args.config, args.scale)
-    t0 = time.time()
-    data = synth.generate(cfg, cache_dir=os.environ.get("TMPDIR", "/tmp") + "/sc_synth_cache")
-    t_gen = time.time() - t0
-    out_shape = synth.output_shape(cfg)
-
     def timed(con, steps, warmup):
+        """Mean and per-step statistics of `steps` executions after `warmup` untimed ones."""
         for _ in range(warmup):
             con.run()
         torch.cuda.synchronize()
@@ -81,9 +87,9 @@ def main() -> int:
             marks[i + 1].record()   # an event between steps costs nothing the stream waits for
         torch.cuda.synchronize()
         per_step = np.array([marks[i].elapsed_time(marks[i + 1]) for i in range(steps)])
-        timed.stats = {"median": float(np.median(per_step)), "std": float(per_step.std()),
-                       "min": float(per_step.min()), "max": float(per_step.max())}
-        return marks[0].elapsed_time(marks[steps]) / steps
+        stats = {"median": float(np.median(per_step)), "std": float(per_step.std()),
+                 "min": float(per_step.min()), "max": float(per_step.max())}
+        return marks[0].elapsed_time(marks[steps]) / steps, stats
 
     def kernel_times(con, steps):
         """Average per-kernel milliseconds over `steps` profiled executions (HIP events
@@ -102,130 +108,166 @@ def main() -> int:
         sc.plan_set_profiling(con.plan, False)
         return {n: acc[n] / steps for n in order}
 
-    t0 = time.time()
-    fused = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
-                        sc.schedule("fused"), out_shape)
-    t_plan = time.time() - t0
-    flops, bytes_fused = sc.plan_model(fused.plan)
-    ms = timed(fused, args.steps, args.warmup)
-    ms_stats = dict(timed.stats)
-    kt = kernel_times(fused, min(args.steps, 20))
-    dom_name = max(kt, key=kt.get)
-    dom_ms = kt[dom_name]
-    # algorithmic bytes of the dominant kernel: the schedule's compulsory bytes minus the
-    # output fill, which is a separate launch
-    elem = 8 if cfg["dtype"] == "f64" else 4
-    out_bytes = float(np.prod(out_shape)) * elem
-    dom_bytes = bytes_fused  # the fused kernel reads every input once and writes the output once
-    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
-    # HBM bytes per launch from stored FETCH_SIZE / WRITE_SIZE counter runs (calibrated against
-    # a copy of known size); None when absent or taken from other kernel sources
-    measured = traffic_store.lookup(f"{args.config}:{dom_name}") if args.scale == 1.0 else None
+    def bench_config(cid):
+        cfg = synth.config(cid, args.scale)
+        t0 = time.time()
+        data = synth.generate(cfg, cache_dir=os.environ.get("TMPDIR", "/tmp") + "/sc_synth_cache")
+        t_gen = time.time() - t0
+        out_shape = synth.output_shape(cfg)
+        elem = 8 if cfg["dtype"] == "f64" else 4
+        print(f"bench: config {cid} generated in {t_gen:.1f} s", file=sys.stderr, flush=True)
 
-    if args.calibrate_copy:
-        src = torch.empty(traffic_store.COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
-        dst = torch.empty_like(src)
-        stream = torch.cuda.current_stream().cuda_stream
-        for _ in range(3):
-            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
-        torch.cuda.synchronize()
-        beg, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        beg.record()
-        for _ in range(10):
-            sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
-        end.record()
-        torch.cuda.synchronize()
-        copy_ms = beg.elapsed_time(end) / 10
-        # the library's plain copy kernel as a practical ceiling: bytes read + bytes written per second
-        stream_copy = {"bytes_each_way": traffic_store.COPY_BYTES, "ms": copy_ms,
-                       "gbs_read_plus_write": 2 * traffic_store.COPY_BYTES / (copy_ms * 1e-3) / 1e9}
-        del src, dst
-    else:
+        t0 = time.time()
+        fused = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                            sc.schedule("fused"), out_shape)
+        t_plan = time.time() - t0
+        flops, bytes_fused = sc.plan_model(fused.plan)
+        ms, ms_stats = timed(fused, args.steps, args.warmup)
+        kt = kernel_times(fused, min(args.steps, 10))
+        dom_name = max(kt, key=kt.get)
+        dom_ms = kt[dom_name]
+        # algorithmic bytes of the dominant kernel: the fused kernel reads every input once and
+        # writes the output once (the schedule's compulsory bytes)
+        dom_bytes = bytes_fused
+        achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+        # HBM bytes per launch from stored FETCH_SIZE / WRITE_SIZE counter runs (calibrated against a
+        # copy of known size); None when absent or taken from other kernel sources
+        measured = traffic_store.lookup(f"{cid}:{dom_name}") if args.scale == 1.0 else None
+        rec = {
+            "config_id": cid,
+            "workload": WORKLOAD_TEXT[cid] + (f" (scaled by {args.scale})" if args.scale != 1.0 else ""),
+            "dtype": cfg["dtype"],
+            "nnz": int(cfg["nnz"]),
+            "tiles": sc.plan_tile_count(fused.plan),
+            "steps": args.steps,
+            "ms_per_step": ms,
+            "ms_per_step_stats": ms_stats,
+            "schedule_flops": flops,
+            "gflops": flops / (ms * 1e-3) / 1e9,
+            "algorithmic_gbs_whole_step": bytes_fused / (ms * 1e-3) / 1e9,
+            "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": achieved / HBM_PEAK_GBS, "traffic": measured["hbm_bytes"] if measured else None,
+                         "algorithmic_bytes": dom_bytes, "kernel_ms": dom_ms},
+            "mfma_busy": measured.get("mfma_busy") if measured else None,
+            "kernels_ms": kt,
+            "setup_s": {"generate": t_gen, "convert_plan_upload": t_plan},
+        }
+
+        if not args.no_fissioned:
+            fis = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                              sc.schedule("fissioned"), out_shape, share=fused)
+            _, bytes_fis = sc.plan_model(fis.plan)
+            ms_f, _ = timed(fis, max(5, args.steps // 2), 2)
+            kt_f = kernel_times(fis, 5)
+            rec["fissioned"] = {"ms_per_step": ms_f, "kernels_ms": kt_f, "algorithmic_bytes": bytes_fis,
+                                "workspace_bytes": fis.ws_bytes}
+            trav = [n for n in kt_f if "traverse" in n or "sddmm" in n or "leaf" in n]
+            if trav:
+                n = trav[0]
+                # traversal kernel of the fissioned schedule: streams the leaves once, writes T once
+                off, rows, cols = sc.plan_intermediate(fis.plan, 0)
+                tb = cfg["nnz"] * (4 + elem) + rows * 4 + rows * cols * elem
+                rec["fissioned"]["traversal"] = {"kernel": n, "algorithmic_bytes": tb, "ms": kt_f[n],
+                                                 "gbs": tb / (kt_f[n] * 1e-3) / 1e9,
+                                                 "frac": tb / (kt_f[n] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+            rec["fused_vs_fissioned_speedup"] = ms_f / ms
+            del fis
+            torch.cuda.empty_cache()
+
+        if not args.no_linear:
+            # the unfactored nest on the same GPU: what the fused schedule is a rewrite of (few steps: slow by design)
+            lin = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                              sc.schedule("linear"), out_shape, share=fused)
+            flops_lin, _ = sc.plan_model(lin.plan)
+            ms_l, _ = timed(lin, max(3, min(args.steps, 5)), 1)
+            rec["linear"] = {"ms_per_step": ms_l, "nest_flops": flops_lin, "gflops": flops_lin / (ms_l * 1e-3) / 1e9}
+            rec["fused_vs_linear_speedup"] = ms_l / ms
+            del lin
+            torch.cuda.empty_cache()
+
         stream_copy = None
+        if args.calibrate_copy:
+            src = torch.empty(traffic_store.COPY_BYTES, dtype=torch.uint8, device="cuda:0").fill_(1)
+            dst = torch.empty_like(src)
+            stream = torch.cuda.current_stream().cuda_stream
+            for _ in range(3):
+                sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
+            torch.cuda.synchronize()
+            beg, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            beg.record()
+            for _ in range(10):
+                sc.stream_copy(dst, src, traffic_store.COPY_BYTES, stream)
+            end.record()
+            torch.cuda.synchronize()
+            copy_ms = beg.elapsed_time(end) / 10
+            # the library's plain copy kernel as a practical ceiling: bytes read + bytes written per second
+            stream_copy = {"bytes_each_way": traffic_store.COPY_BYTES, "ms": copy_ms,
+                           "gbs_read_plus_write": 2 * traffic_store.COPY_BYTES / (copy_ms * 1e-3) / 1e9}
+            del src, dst
+            rec["stream_copy"] = stream_copy
+
+        del fused
+        torch.cuda.empty_cache()
+
+        if not args.no_cpu_baseline:
+            from oracle import oracle as o
+            o.build()
+            cores = o.max_threads()
+            # bounded sample: a prefix of whole top-level slices holding at most `budget` multiply-adds of the
+            # linear nest per run (the whole workload when it is smaller), one warm-up run and three timed ones
+            per_nnz = {"ttmc3": lambda r: r[0] * r[1], "mttkrp3": lambda r: r[0], "sddmm_spmm": lambda r: r[0] + r[1],
+                       "ttmc4": lambda r: r[0] * r[1] * r[2]}[cfg["kind"]](cfg["ranks"])
+            budget = 3e10
+            take = int(min(cfg["nnz"], max(1, budget // per_nnz)))
+            coords = data["coords"][:, :take]
+            vals = data["vals"][:take]
+            secs = o.time_contract(cfg["kind"], coords, vals, cfg["dims"], data["factors"], nthreads=cores, warmup=1, runs=3)
+            t_cpu = float(np.median(secs))
+            frac = take / cfg["nnz"]
+            rec["cpu_baseline"] = {
+                "value": flops * frac / t_cpu / 1e9, "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
+                "sample": (f"first {take} of {cfg['nnz']} nonzeros (leading slices), fp64 linear loop nest, C call only, "
+                           f"1 warm-up + median of 3 runs ({t_cpu:.3f} s); value = schedule flops x sampled fraction / time"),
+                "seconds": t_cpu, "runs_s": secs,
+            }
+            rec["gpu_vs_cpu_oracle"] = rec["gflops"] / rec["cpu_baseline"]["value"]
+        return rec
+
+    cids = [args.config] if args.config else [1, 2, 3, 4, 5]
+    per_config = []
+    for cid in cids:
+        per_config.append(bench_config(cid))
+        print(f"bench: config {cid} done: {per_config[-1]['ms_per_step']:.4f} ms/step, "
+              f"{per_config[-1]['gflops']:.0f} GFLOP/s, roofline {per_config[-1]['roofline']['frac']:.3f}",
+              file=sys.stderr, flush=True)
+    head = next((r for r in per_config if r["config_id"] == HEADLINE), per_config[-1])
 
     result = {
-        "metric": "effective GFLOP/s of the fused schedule (schedule flops / step time), 1 MI355X",
-        "value": flops / (ms * 1e-3) / 1e9,
+        "metric": "effective GFLOP/s of the fused schedule (schedule flops / step time) per contraction, 1 MI355X",
+        "value": head["gflops"],
         "unit": "GFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms,
-        "ms_per_step_stats": ms_stats,
+        "ms_per_step": head["ms_per_step"],
+        "ms_per_step_stats": head["ms_per_step_stats"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": cfg["dtype"],
+        "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.config] + (f" (scaled by {args.scale})" if args.scale != 1.0 else ""),
-                   "schedule": "fused", "nnz": int(cfg["nnz"]), "tiles": sc.plan_tile_count(fused.plan)},
-        "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured["hbm_bytes"] if measured else None,
-                     "algorithmic_bytes": dom_bytes, "kernel_ms": dom_ms},
-        "kernels_ms": kt,
-        "schedule_flops": flops,
-        "algorithmic_gbs_whole_step": bytes_fused / (ms * 1e-3) / 1e9,
-        "setup_s": {"generate": t_gen, "convert_plan_upload": t_plan},
+        "config": {"workload": head["workload"], "schedule": "fused", "nnz": head["nnz"], "tiles": head["tiles"]},
+        "roofline": head["roofline"],
+        "schedule_flops": head["schedule_flops"],
+        "paper_context": PAPER_CONTEXT,
     }
-    if stream_copy:
-        result["stream_copy"] = stream_copy
-    del fused
-    torch.cuda.empty_cache()
-
-    if not args.no_fissioned:
-        fis = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
-                          sc.schedule("fissioned"), out_shape)
-        _, bytes_fis = sc.plan_model(fis.plan)
-        ms_f = timed(fis, max(5, args.steps // 2), 2)
-        kt_f = kernel_times(fis, 5)
-        result["fissioned"] = {"ms_per_step": ms_f, "kernels_ms": kt_f, "algorithmic_bytes": bytes_fis,
-                               "workspace_bytes": fis.ws_bytes}
-        trav = [n for n in kt_f if "traverse" in n or "sddmm" in n or "leaf" in n]
-        if trav:
-            n = trav[0]
-            # traversal kernel of the fissioned schedule: streams the leaves once, writes T once
-            off, rows, cols = sc.plan_intermediate(fis.plan, 0)
-            tb = cfg["nnz"] * (4 + elem) + rows * 4 + rows * cols * elem
-            result["fissioned"]["traversal"] = {"kernel": n, "algorithmic_bytes": tb, "ms": kt_f[n],
-                                                "gbs": tb / (kt_f[n] * 1e-3) / 1e9,
-                                                "frac": tb / (kt_f[n] * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        result["fused_vs_fissioned_speedup"] = ms_f / ms
-        del fis
-        torch.cuda.empty_cache()
-
-    if not args.no_linear:
-        # the unfactored nest on the same GPU: what the fused schedule is a rewrite of (few steps: it is slow by design)
-        lin = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
-                          sc.schedule("linear"), out_shape)
-        flops_lin, _ = sc.plan_model(lin.plan)
-        ms_l = timed(lin, max(3, min(args.steps, 10)), 1)
-        result["linear"] = {"ms_per_step": ms_l, "nest_flops": flops_lin, "gflops": flops_lin / (ms_l * 1e-3) / 1e9}
-        result["fused_vs_linear_speedup"] = ms_l / ms
-        del lin
-        torch.cuda.empty_cache()
-
-    if not args.no_cpu_baseline:
-        from oracle import oracle as o
-        o.build()
-        cores = o.max_threads()
-        # bounded sample: a prefix of whole top-level slices holding about `budget` multiply-adds
-        per_nnz = {"ttmc3": lambda r: r[0] * r[1], "mttkrp3": lambda r: r[0], "sddmm_spmm": lambda r: r[0] + r[1],
-                   "ttmc4": lambda r: r[0] * r[1] * r[2]}[cfg["kind"]](cfg["ranks"])
-        budget = 4e9
-        take = int(min(cfg["nnz"], max(1, budget // per_nnz)))
-        coords = data["coords"][:, :take]
-        vals = data["vals"][:take]
-        t0 = time.time()
-        o.contract(cfg["kind"], coords, vals, cfg["dims"], data["factors"], nthreads=cores)
-        t_cpu = time.time() - t0
-        frac = take / cfg["nnz"]
-        result["cpu_baseline"] = {
-            "value": flops * frac / t_cpu / 1e9, "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"first {take} of {cfg['nnz']} nonzeros (leading slices), fp64 linear loop nest, one run, "
-                      f"{t_cpu:.2f} s; value = schedule flops x sampled fraction / time",
-            "seconds": t_cpu,
-        }
-
+    if "cpu_baseline" in head:
+        result["cpu_baseline"] = head["cpu_baseline"]
+    for k in ("fissioned", "fused_vs_fissioned_speedup", "linear", "fused_vs_linear_speedup", "kernels_ms", "mfma_busy",
+              "stream_copy"):
+        if k in head:
+            result[k] = head[k]
+    result["per_config"] = per_config
     print(json.dumps(result))
     return 0
 

@@ -167,7 +167,9 @@ sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out);
 sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
                          const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched);
 
-/* Bytes of device workspace sc_execute needs (FISSIONED temporaries; 0 is possible). */
+/* Bytes of device workspace sc_execute needs: the temporaries of the `where` nests of Section 4.2
+ * when the schedule materialises them (FISSIONED: T(i,j,m), T1/T2, the sampled values of kernel 1
+ * of Table 2), plus the stored row pieces of a deterministic schedule; 0 is possible. */
 sc_status sc_plan_workspace_bytes(const sc_plan *plan, size_t *bytes);
 
 /* Human-readable description: the forall/where text of the nest (Section 4.2 notation),
@@ -186,9 +188,16 @@ sc_status sc_plan_model(const sc_plan *plan, double *flops, double *bytes);
 sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, size_t *offset_bytes,
                                int64_t *rows, int64_t *cols);
 
-/* Runs the planned contraction on `hip_stream` (a hipStream_t; NULL = the default
- * stream).  `sparse` and every factor must be DEVICE views with the structure sizes and
- * shapes the plan was made for; `out` is device memory for the whole dense result;
+/* Runs the planned contraction -- the loop nest of its schedule: the perfectly nested default
+ * of Section 3 (LINEAR), or the producer / consumer nests of Section 3.1 and Table 2 fused under
+ * their common loops or split -- on `hip_stream` (a hipStream_t; NULL = the default stream).
+ * `sparse` and every factor must be DEVICE views with the shapes the plan was made for, and
+ * `sparse` must have the very pos and crd arrays the plan was built from (tile tables, the list of
+ * rows to zero and the numbering of row pieces all come from them; only node counts are
+ * re-checked here, so a different tensor of equal node counts gives wrong results); vals and the
+ * factor values are free to change between executions.  Every factor spans less than 2 GiB
+ * (rows x ld x element size; SC_ERR_SHAPE_MISMATCH otherwise, before anything is launched).
+ * `out` is device memory for the whole dense result;
  * `workspace` is device memory of at least sc_plan_workspace_bytes() bytes, 256-byte
  * aligned (may be NULL when that is 0).  Asynchronous: returns after queueing. */
 sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors,
@@ -198,7 +207,10 @@ sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_de
 /* Optional per-kernel timing.  With profiling on, sc_execute brackets each kernel it
  * launches with plan-owned HIP events on the caller's stream; after the caller has
  * synchronised the stream, sc_plan_kernel_time reports the elapsed milliseconds of launch
- * `index` of the most recent sc_execute and its name (name may be NULL). */
+ * `index` of the most recent sc_execute and its name (name may be NULL).  With profiling off an
+ * execution writes nothing that belongs to the plan, so one plan may execute on several streams
+ * at once (with separate workspaces and outputs); with profiling on, executions of a plan must
+ * not overlap. */
 sc_status sc_plan_set_profiling(sc_plan *plan, int32_t on);
 sc_status sc_plan_kernel_count(const sc_plan *plan, int32_t *count);
 sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, char *name, size_t name_len, float *ms);
@@ -212,12 +224,14 @@ sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, char *name, si
 sc_status sc_plan_tile_count(const sc_plan *plan, int64_t *count);
 sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9]);
 
-/* Process-global tuning knobs; they affect plans created afterwards.  Names:
+/* Process-global tuning knobs for experiments; sc_plan_create copies them into the plan it
+ * makes, and executions read only that copy (changing a knob never affects an existing plan; set
+ * them from one thread, before creating plans).  Names:
  * "tile_leaves", "tile_nodes_a", "tile_nodes_b" (upper bounds on the leaves / level-a /
  * level-b nodes of one work tile; 0 restores the built-in choice), "tile_interleave"
  * (stride of the order in which tiles are handed to workgroups; 1 = tensor order),
  * "persistent_per_cu" (workgroups per compute unit launched by the kernels that loop over
- * tiles; 0 = as many as fit; read at execute time).  Unknown names give
+ * tiles; 0 = as many as fit).  Unknown names give
  * SC_ERR_EXPR_PARSE; sc_plan_create rejects caps whose on-chip buffers do not fit. */
 sc_status sc_tuning_set(const char *name, int64_t value);
 
@@ -229,7 +243,8 @@ sc_status sc_tuning_set(const char *name, int64_t value);
  * SC_ERR_DEVICE when the launch fails. */
 sc_status sc_stream_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
 
-/* Frees the plan and its device tables.  NULL is accepted. */
+/* Frees the plan and its device tables (the tile tables cut from the CSF levels of Section 2.1 at
+ * plan creation).  NULL is accepted.  Work queued by sc_execute must have finished. */
 sc_status sc_plan_destroy(sc_plan *plan);
 
 #ifdef __cplusplus

@@ -167,6 +167,25 @@ def contract(kind, coords, vals, dims, factors, nthreads=None):
     return _CONTRACT[kind](coords, vals, dims, *factors, nthreads=nthreads)
 
 
+def time_contract(kind, coords, vals, dims, factors, nthreads=None, warmup=1, runs=3):
+    """Wall-clock seconds of `runs` evaluations of the C loop nest alone, after `warmup` untimed ones.
+    The inputs are converted to the C types (fp64, int32, contiguous) once, before the clock starts:
+    the conversions inside contract_* are then no-ops, and the clock covers the ctypes call and the
+    allocation of the fp64 result only."""
+    import time
+    c = [_i32(x) for x in coords]
+    v = _f64(vals)
+    fs = [_f64(f) for f in factors]
+    secs = []
+    for r in range(warmup + runs):
+        t0 = time.perf_counter()
+        _CONTRACT[kind](c, v, dims, *fs, nthreads=nthreads)
+        dt = time.perf_counter() - t0
+        if r >= warmup:
+            secs.append(dt)
+    return secs
+
+
 def abs_bound(kind, coords, vals, dims, factors, nthreads=None):
     """Per output element: sum over all partial products of their absolute values."""
     return _CONTRACT[kind](coords, np.abs(_f64(vals)), dims, *[np.abs(_f64(f)) for f in factors],

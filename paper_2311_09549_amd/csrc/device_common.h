@@ -136,33 +136,36 @@ inline bool rank_ok(int64_t w, sc_dtype dt)
     return lg >= 1 && lg <= 64 && (lg & (lg - 1)) == 0;
 }
 
-// Workgroups using `lds` bytes of LDS each that one compute unit holds at a time: 160 KB,
-// handed out in units of 1280 bytes (measured: a fifth workgroup of 31,880 bytes fits, one of
-// 32,232 does not).  The kernels here are bound by latency, and their time falls almost in
-// proportion to this number, so tile sizes are chosen to land just below a step.
-inline int lds_workgroups_per_cu(size_t lds)
+// Workgroups using `lds` bytes of LDS each that one compute unit holds at a time: the unit's LDS
+// (160 KB on MI355X) is handed out in units of 1280 bytes (measured: a fifth workgroup of 31,880
+// bytes fits, one of 32,232 does not).  The kernels here are bound by latency, and their time
+// falls almost in proportion to this number, so tile sizes are chosen to land just below a step.
+inline int lds_workgroups_per_cu(size_t lds, int64_t lds_per_cu = 160 * 1024)
 {
     const size_t unit = 1280;
     const size_t need = std::max<size_t>(unit, (lds + unit - 1) / unit * unit);
-    return (int)std::max<size_t>(1, std::min<size_t>(8, (160 * 1024) / need));
+    return (int)std::max<size_t>(1, std::min<size_t>(8, (size_t)lds_per_cu / need));
 }
 
 struct Launcher {
     const sc_plan *plan;
     hipStream_t stream;
     sc_status status = SC_OK;
+    bool timed() const { return plan->prof && plan->prof->on && plan->prof->n_launch < kMaxLaunches; }
     void begin(const char *name)
     {
-        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
-        plan->launch_name[plan->n_launch] = name;
-        if (hipEventRecord(plan->ev_begin[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
+        if (!timed()) return;
+        ProfileState &pr = *plan->prof;
+        pr.launch_name[pr.n_launch] = name;
+        if (hipEventRecord(pr.ev_begin[pr.n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
     }
     void end()
     {
         if (hipGetLastError() != hipSuccess) status = SC_ERR_DEVICE;
-        if (!plan->profiling || plan->n_launch >= kMaxLaunches) return;
-        if (hipEventRecord(plan->ev_end[plan->n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
-        plan->n_launch++;
+        if (!timed()) return;
+        ProfileState &pr = *plan->prof;
+        if (hipEventRecord(pr.ev_end[pr.n_launch], stream) != hipSuccess) status = SC_ERR_DEVICE;
+        pr.n_launch++;
     }
 };
 
@@ -171,7 +174,7 @@ inline void launch_fill(Launcher &ln, T *p, int64_t n, const char *name)
 {
     if (n <= 0) return;
     const int64_t nvec = (n + VecWidth<T>::value - 1) / VecWidth<T>::value;
-    const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, 256 * 16);
+    const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, (int64_t)ln.plan->n_cu * 16);
     ln.begin(name);
     fill_zero_kernel<T><<<blocks, NT, 0, ln.stream>>>(p, n);
     ln.end();
@@ -205,7 +208,7 @@ inline void launch_output_zero(Launcher &ln, const sc_plan *p, T *out)
     const int64_t nvec = (int64_t)p->zero_rows.size() * vpr;
     ln.begin("zero_output_rows");
     if (nvec > 0) {
-        const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, 256 * 16);
+        const int blocks = (int)std::min<int64_t>((nvec + NT - 1) / NT, (int64_t)p->n_cu * 16);
         zero_rows_kernel<T><<<blocks, NT, 0, ln.stream>>>(p->d_zero_rows, nvec, vpr, out, p->out_row_elems);
     }
     ln.end();

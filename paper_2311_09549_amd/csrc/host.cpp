@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <stdexcept>
 #include <set>
 #include <string>
 #include <vector>
@@ -219,6 +220,21 @@ sc_status check_header(int32_t order, const int64_t *dims, int64_t nnz, sc_dtype
     return SC_OK;
 }
 
+// Node counts of a CSF view: non-negative, non-decreasing from the root to the leaves, the leaf
+// count equal to nnz, no more slices than the first dimension, all zero exactly when nothing is stored.
+sc_status check_node_counts(const sc_csf_view *v)
+{
+    const int d = v->order;
+    if (v->nfib[d - 1] != v->nnz) return SC_ERR_BAD_DIMS;
+    for (int m = 0; m < d; ++m) {
+        if (v->nfib[m] < 0 || v->nfib[m] > v->nnz) return SC_ERR_BAD_DIMS;
+        if (m && v->nfib[m] < v->nfib[m - 1]) return SC_ERR_BAD_DIMS;
+        if ((v->nfib[m] == 0) != (v->nnz == 0)) return SC_ERR_BAD_DIMS;
+    }
+    if (v->nfib[0] > v->dims[0]) return SC_ERR_BAD_DIMS;
+    return SC_OK;
+}
+
 // Host arrays of a CSF view (copied from the device when needed).
 struct HostCsf {
     std::vector<int32_t> pos_store[4], crd_store[4];
@@ -260,13 +276,8 @@ sc_status validate_csf(const sc_csf_view *v, const HostCsf &h)
     sc_status st = check_header(v->order, v->dims, v->nnz, v->dtype);
     if (st != SC_OK) return st;
     const int d = v->order;
-    if (v->nfib[d - 1] != v->nnz) return SC_ERR_BAD_DIMS;
-    for (int m = 0; m < d; ++m) {
-        if (v->nfib[m] < 0) return SC_ERR_BAD_DIMS;
-        if (m && v->nfib[m] < v->nfib[m - 1]) return SC_ERR_BAD_DIMS;
-        if ((v->nfib[m] == 0) != (v->nnz == 0)) return SC_ERR_BAD_DIMS;
-    }
-    if (v->nfib[0] > v->dims[0]) return SC_ERR_BAD_DIMS;
+    st = check_node_counts(v);
+    if (st != SC_OK) return st;
     if (v->nnz > 0 && !v->vals) return SC_ERR_NULL;
     for (int m = 1; m < d; ++m) {
         const int32_t *pos = h.pos[m];
@@ -579,7 +590,22 @@ extern "C" const char *sc_status_string(sc_status s)
     return kStatusText[(int)s];
 }
 
-extern "C" sc_status sc_coo_to_csf_sizes(const sc_coo_view *coo, int64_t nfib_out[4])
+// Runs `body` and turns any C++ exception into a status: nothing may cross the C boundary.
+template <typename Body>
+static sc_status guarded(Body body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc &) {
+        return SC_ERR_ALLOC;
+    } catch (const std::length_error &) {
+        return SC_ERR_BAD_DIMS;
+    } catch (...) {
+        return SC_ERR_BAD_DIMS;
+    }
+}
+
+static sc_status coo_to_csf_sizes_impl(const sc_coo_view *coo, int64_t nfib_out[4])
 {
     if (!coo || !nfib_out) return SC_ERR_NULL;
     sc_status st = validate_coo(coo);
@@ -597,11 +623,16 @@ extern "C" sc_status sc_coo_to_csf_sizes(const sc_coo_view *coo, int64_t nfib_ou
     return SC_OK;
 }
 
-extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
+extern "C" sc_status sc_coo_to_csf_sizes(const sc_coo_view *coo, int64_t nfib_out[4])
+{
+    return guarded([&] { return coo_to_csf_sizes_impl(coo, nfib_out); });
+}
+
+static sc_status coo_to_csf_impl(const sc_coo_view *coo, sc_csf_view *out)
 {
     if (!coo || !out) return SC_ERR_NULL;
     int64_t nfib[4];
-    sc_status st = sc_coo_to_csf_sizes(coo, nfib);
+    sc_status st = coo_to_csf_sizes_impl(coo, nfib);
     if (st != SC_OK) return st;
     const int d = coo->order;
     for (int m = 0; m < d; ++m) {
@@ -643,8 +674,13 @@ extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
     return SC_OK;
 }
 
-extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
-                                    const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
+extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
+{
+    return guarded([&] { return coo_to_csf_impl(coo, out); });
+}
+
+static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_view *sparse,
+                                  const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
 {
     if (!out) return SC_ERR_NULL;
     *out = nullptr;
@@ -660,6 +696,8 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     if (nfactors != (int32_t)rhs.size() - 1) return SC_ERR_SHAPE_MISMATCH;
 
     st = check_header(sparse->order, sparse->dims, sparse->nnz, sparse->dtype);
+    if (st != SC_OK) return st;
+    st = check_node_counts(sparse);   // before any array is sized from them
     if (st != SC_OK) return st;
     HostCsf h;
     st = fetch_csf(sparse, h, /*want_crd=*/true);
@@ -685,6 +723,8 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
         const sc_dense_view &f = factors[fam.slot_of_factor[s]];
         if (f.dtype != p->dtype) return dtype_ok(f.dtype) ? SC_ERR_BAD_DTYPE : SC_ERR_BAD_DTYPE;
         if (f.rows <= 0 || f.cols <= 0 || f.cols > 4096) return SC_ERR_SHAPE_MISMATCH;
+        // rows are addressed with byte offsets of 31 bits (the walks use bit 31 as the end-of-node mark)
+        if ((uint64_t)f.rows * (uint64_t)f.cols * esize(p->dtype) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
         p->frows[s] = f.rows;
         p->fcols[s] = f.cols;
     }
@@ -753,7 +793,19 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     p->caps = linear ? TileCaps{1024, 1024, 1024}   // node caps that never bind: the kernel keeps no per-node state
                      : default_caps(p->kind, p->dtype, p->sched, p->fcols);
     if (p->caps.tn <= 0) return SC_ERR_SCHED_UNSUPPORTED;  // no kernel instantiated for these ranks
-    const Tuning &tu = tuning();
+    p->tune = tuning();   // read once; executions use the plan's copy
+    {
+        int ndev0 = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceCount(&ndev0) == hipSuccess && ndev0 > 0 && hipGetDevice(&dev) == hipSuccess &&
+            hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            if (prop.multiProcessorCount > 0) p->n_cu = prop.multiProcessorCount;
+            if (prop.maxSharedMemoryPerMultiProcessor >= 64 * 1024) p->lds_per_cu = (int64_t)prop.maxSharedMemoryPerMultiProcessor;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
+    const Tuning &tu = p->tune;
     if (tu.tn) p->caps.tn = tu.tn;
     if (tu.ta) p->caps.ta = tu.ta;
     if (tu.tb) p->caps.tb = tu.tb;
@@ -907,7 +959,7 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
             // spread over the kernel's duration instead of queueing on one address.
             const size_t nt = p->tiles.size();
             const size_t stride =
-                plan_wants_tensor_order(p) ? 1 : (size_t)std::max<int32_t>(1, tuning().interleave ? tuning().interleave : 64);
+                plan_wants_tensor_order(p) ? 1 : (size_t)std::max<int32_t>(1, p->tune.interleave ? p->tune.interleave : 64);
             std::vector<TileRec> order;
             try {
                 order.reserve(nt);
@@ -948,6 +1000,12 @@ extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_cs
     guard.p = nullptr;
     *out = p;
     return SC_OK;
+}
+
+extern "C" sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
+                                    const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
+{
+    return guarded([&] { return plan_create_impl(out, expr, sparse, factors, nfactors, sched); });
 }
 
 extern "C" sc_status sc_plan_workspace_bytes(const sc_plan *plan, size_t *bytes)
@@ -1001,8 +1059,9 @@ extern "C" sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t re
     return SC_OK;
 }
 
-extern "C" sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors,
-                                void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+// Argument checks and launches shared by every execute entry point.
+sc_status sck::execute_checked(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors,
+                               void *out, void *workspace, size_t workspace_bytes, hipStream_t hip_stream)
 {
     if (!plan || !sparse || !factors || !out) return SC_ERR_NULL;
     if (!plan->has_device) return SC_ERR_DEVICE;
@@ -1025,44 +1084,71 @@ extern "C" sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, 
         if (f.rows != plan->frows[s] || f.cols != plan->fcols[s] || f.ld < f.cols) return SC_ERR_SHAPE_MISMATCH;
         // rows are read with 16-byte vector loads
         if ((uintptr_t)f.data % 16 || (f.ld * (int64_t)esize(f.dtype)) % 16) return SC_ERR_SHAPE_MISMATCH;
+        // ... and addressed with 31-bit byte offsets: checked here, before anything is launched
+        if ((uint64_t)f.rows * (uint64_t)f.ld * esize(f.dtype) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
         canon[s] = f;
     }
     if (workspace_bytes < plan->ws_bytes) return SC_ERR_WORKSPACE_SMALL;
     if (plan->ws_bytes && (!workspace || (uintptr_t)workspace % 256)) return plan->ws_bytes && !workspace ? SC_ERR_NULL : SC_ERR_SHAPE_MISMATCH;
-    return launch_plan(plan, sparse, canon, out, workspace, (hipStream_t)hip_stream);
+    return launch_plan(plan, sparse, canon, out, workspace, hip_stream);
+}
+
+extern "C" sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors,
+                                void *out, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return guarded([&] { return execute_checked(plan, sparse, factors, nfactors, out, workspace, workspace_bytes, (hipStream_t)hip_stream); });
 }
 
 extern "C" sc_status sc_plan_set_profiling(sc_plan *plan, int32_t on)
 {
     if (!plan) return SC_ERR_NULL;
-    if (on && !plan->events_made) {
+    if (on && !plan->prof) {
         if (!plan->has_device) return SC_ERR_DEVICE;
-        for (int i = 0; i < kMaxLaunches; ++i) {
-            if (hipEventCreate(&plan->ev_begin[i]) != hipSuccess) return SC_ERR_DEVICE;
-            if (hipEventCreate(&plan->ev_end[i]) != hipSuccess) return SC_ERR_DEVICE;
+        ProfileState *pr = new (std::nothrow) ProfileState();
+        if (!pr) return SC_ERR_ALLOC;
+        int made = 0;
+        bool ok = true;
+        for (; made < kMaxLaunches && ok; ++made) {
+            ok = hipEventCreate(&pr->ev_begin[made]) == hipSuccess;
+            if (ok && hipEventCreate(&pr->ev_end[made]) != hipSuccess) {
+                (void)hipEventDestroy(pr->ev_begin[made]);
+                ok = false;
+            }
+            if (!ok) break;
         }
-        plan->events_made = true;
+        if (!ok) {
+            for (int i = 0; i < made; ++i) {
+                (void)hipEventDestroy(pr->ev_begin[i]);
+                (void)hipEventDestroy(pr->ev_end[i]);
+            }
+            delete pr;
+            return SC_ERR_DEVICE;
+        }
+        plan->prof = pr;
     }
-    plan->profiling = on != 0;
-    plan->n_launch = 0;
+    if (plan->prof) {
+        plan->prof->on = on != 0;
+        plan->prof->n_launch = 0;
+    }
     return SC_OK;
 }
 
 extern "C" sc_status sc_plan_kernel_count(const sc_plan *plan, int32_t *count)
 {
     if (!plan || !count) return SC_ERR_NULL;
-    *count = plan->n_launch;
+    *count = plan->prof ? plan->prof->n_launch : 0;
     return SC_OK;
 }
 
 extern "C" sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, char *name, size_t name_len, float *ms)
 {
     if (!plan || !ms) return SC_ERR_NULL;
-    if (!plan->profiling || !plan->events_made) return SC_ERR_SCHED_UNSUPPORTED;
-    if (index < 0 || index >= plan->n_launch) return SC_ERR_BAD_DIMS;
-    if (hipEventElapsedTime(ms, plan->ev_begin[index], plan->ev_end[index]) != hipSuccess) return SC_ERR_DEVICE;
+    if (!plan->prof || !plan->prof->on) return SC_ERR_SCHED_UNSUPPORTED;
+    const ProfileState &pr = *plan->prof;
+    if (index < 0 || index >= pr.n_launch) return SC_ERR_BAD_DIMS;
+    if (hipEventElapsedTime(ms, pr.ev_begin[index], pr.ev_end[index]) != hipSuccess) return SC_ERR_DEVICE;
     if (name && name_len) {
-        snprintf(name, name_len, "%s", plan->launch_name[index]);
+        snprintf(name, name_len, "%s", pr.launch_name[index]);
     }
     return SC_OK;
 }
@@ -1077,11 +1163,13 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
         if (lv->d_segs) (void)hipFree(lv->d_segs);
     }
     if (plan->d_zero_rows) (void)hipFree(plan->d_zero_rows);
-    if (plan->events_made)
+    if (plan->prof) {
         for (int i = 0; i < kMaxLaunches; ++i) {
-            (void)hipEventDestroy(plan->ev_begin[i]);
-            (void)hipEventDestroy(plan->ev_end[i]);
+            (void)hipEventDestroy(plan->prof->ev_begin[i]);
+            (void)hipEventDestroy(plan->prof->ev_end[i]);
         }
+        delete plan->prof;
+    }
     delete plan;
     return SC_OK;
 }

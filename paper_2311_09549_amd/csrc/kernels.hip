@@ -634,6 +634,18 @@ __global__ void __launch_bounds__(NT) fixup_rows_kernel(const FixRec *__restrict
 template <typename T, int W>
 sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
+    const bool had = p->kind == K_MTTKRP3;
+    const bool mfma = !had && sizeof(T) == 4 && W == 16 && p->fcols[0] == 16;
+    // Range checks come before the first launch, so that a refused execution leaves the output untouched.
+    // Factor rows are addressed with 32-bit byte offsets; the fused MTTKRP walk keeps the C row's offset in a
+    // signed record (negative = "no fiber ends here"), and the leaf walk of the general kernel marks fiber
+    // ends in bit 31 of the D row's offset: 31 bits there.
+    for (int s = 0; s < 2; ++s)
+        if ((uint64_t)fac[s].rows * (uint64_t)fac[s].ld * sizeof(T) >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
+    if (p->sched == SC_SCHED_FUSED && had && (uint64_t)fac[0].rows * (uint64_t)fac[0].ld * sizeof(T) >= (1ull << 31))
+        return SC_ERR_SHAPE_MISMATCH;
+    if (!(p->sched == SC_SCHED_FUSED && had) && (uint64_t)fac[1].rows * (uint64_t)fac[1].ld * sizeof(T) >= (1ull << 31))
+        return SC_ERR_SHAPE_MISMATCH;
     Launcher ln{p, stream};
     launch_output_zero<T>(ln, p, static_cast<T *>(out));
     const int ntiles = (int)p->tiles.size();
@@ -650,11 +662,6 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
-    const bool had = p->kind == K_MTTKRP3;
-    // factor rows are addressed with 32-bit byte offsets
-    for (int s = 0; s < 2; ++s)
-        if ((uint64_t)fac[s].rows * (uint64_t)fac[s].ld * sizeof(T) >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
-    const bool mfma = !had && sizeof(T) == 4 && W == 16 && a.L == 16;
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
             ln.begin("mttkrp3_fused");
@@ -667,8 +674,6 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             if (ln.status != SC_OK) return ln.status;
             return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
-            // the leaf walk marks fiber ends in bit 31 of the factor-row byte offsets
-            if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * sizeof(T) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
             ln.begin("ttmc3_fused_valu");
             order3_kernel<T, W, 0><<<ntiles, NT, lds, stream>>>(a);
         }
@@ -837,7 +842,7 @@ size_t lds_bytes_needed(const sc_plan *p)
 
 sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
-    p->n_launch = 0;
+    if (p->prof && p->prof->on) p->prof->n_launch = 0;
     if (p->sched == SC_SCHED_LINEAR) return launch_linear(p, sp, fac, out, stream);
     switch (p->kind) {
     case K_TTMC3:

@@ -246,9 +246,9 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
     // slower on the 32-wide rows of the MTTKRP).
     a.ntiles = ntiles;
     const size_t lds = leaf_lds_bytes<T>(W, a.tn, a.ta);
-    const int fit = lds_workgroups_per_cu(lds);
-    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 16) : fit;
-    const int blocks = (tuning().per_cu == 0 && fit > 3) ? ntiles : std::min(ntiles, 256 * per_cu);
+    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 16) : fit;
+    const int blocks = (p->tune.per_cu == 0 && fit > 3) ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     if (partials)
         leaf_traverse_kernel<T, W, true><<<blocks, LNT, lds, ln.stream>>>(a, p->d_tiles);
     else

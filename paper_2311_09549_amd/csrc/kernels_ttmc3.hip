@@ -336,7 +336,7 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
     // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
-    const int want = partials ? ntiles : std::min(ntiles, 256 * per_cu);
+    const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);
     a.ntiles = ntiles;
     a.run = (ntiles + want - 1) / want;

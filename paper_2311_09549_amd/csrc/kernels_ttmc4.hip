@@ -444,7 +444,7 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     // compute unit for the two kernels of the FISSIONED schedule
     const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : (mode == 0 ? 6 * fit : 32);
     // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
-    const int want = partials ? ntiles : std::min(ntiles, 256 * per_cu);
+    const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);
     a.slot_b = p->d_slot_b;
     if (partials && mode == 1 && !p->d_slot_b) return SC_ERR_SCHED_UNSUPPORTED;

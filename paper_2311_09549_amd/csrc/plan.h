@@ -69,6 +69,22 @@ struct FixLevel {
     size_t seg_offset = 0;        // ... and the segment sums
 };
 
+// Process-global tuning overrides (0 = use the built-in choice); a plan copies them when it is created.
+struct Tuning {
+    int32_t tn = 0, ta = 0, tb = 0;
+    int32_t interleave = 0;  // stride of the tile upload order (0 = built-in)
+    int32_t per_cu = 0;      // workgroups per compute unit of the persistent kernels (0 = as many as fit)
+};
+
+// HIP events around every launch of the most recent execution (sc_plan_set_profiling).
+struct ProfileState {
+    bool on = false;
+    int32_t n_launch = 0;
+    const char *launch_name[kMaxLaunches];
+    hipEvent_t ev_begin[kMaxLaunches];
+    hipEvent_t ev_end[kMaxLaunches];
+};
+
 struct Intermediate {
     std::string name;   // e.g. "T(i,j,m)"
     size_t offset = 0;  // byte offset inside the workspace (FISSIONED only)
@@ -120,23 +136,20 @@ struct sc_plan {
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 
-    // profiling
-    bool profiling = false;
-    mutable int32_t n_launch = 0;
-    mutable const char *launch_name[sck::kMaxLaunches];
-    hipEvent_t ev_begin[sck::kMaxLaunches];
-    hipEvent_t ev_end[sck::kMaxLaunches];
-    bool events_made = false;
+    // Snapshot of the tuning knobs and of the device the plan was made on (taken once, at plan
+    // creation): an execution reads only these, never process-global state.
+    sck::Tuning tune;
+    int32_t n_cu = 256;                 // compute units of the device (hipDeviceProp; the value without a device is MI355X's)
+    int64_t lds_per_cu = 160 * 1024;    // LDS bytes per compute unit
+
+    // Per-kernel timing (optional).  The record lives behind a pointer: an execution with profiling
+    // off writes nothing that belongs to the plan, so such executions of one plan may overlap on
+    // several streams; with profiling on they must not.
+    sck::ProfileState *prof = nullptr;
 };
 
 namespace sck {
 
-// Process-global tuning overrides (0 = use the built-in choice).
-struct Tuning {
-    int32_t tn = 0, ta = 0, tb = 0;
-    int32_t interleave = 0;  // stride of the tile upload order (0 = built-in)
-    int32_t per_cu = 0;      // workgroups per compute unit of the persistent kernels (0 = as many as fit)
-};
 Tuning &tuning();
 
 // Built-in tile caps for a contraction (host side; the kernels size their LDS from them).
@@ -152,6 +165,10 @@ bool plan_supports_deterministic(const sc_plan *plan);
 
 // Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
 size_t lds_bytes_needed(const sc_plan *plan);
+
+// Argument checks of an execution followed by launch_plan (shared by the execute entry points).
+sc_status execute_checked(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors, void *out,
+                          void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 sc_status launch_plan(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac /*canonical order*/,
                       void *out, void *workspace, hipStream_t stream);

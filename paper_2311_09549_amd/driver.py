@@ -11,14 +11,20 @@ from . import binding as sc
 class Contraction:
     """One planned contraction resident on the GPU."""
 
-    def __init__(self, expr, coords, vals, dims, factors, sched, out_shape, device="cuda:0"):
+    def __init__(self, expr, coords, vals, dims, factors, sched, out_shape, device="cuda:0", share=None):
+        """`share`: another Contraction of the same problem whose converted CSF arrays and device
+        copies of the operands are reused (a second schedule of one problem)."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
-        self.host_csf = sc.coo_to_csf(list(coords), vals, dims)
-        self.plan = sc.plan_create(expr, self.host_csf, [np.ascontiguousarray(f) for f in factors], sched)
-        self.csf = self.host_csf.to_device(self.device)
-        self.factors = [torch.from_numpy(np.ascontiguousarray(f)).to(self.device) for f in factors]
+        if share is not None:
+            self.host_csf, self.csf, self.factors = share.host_csf, share.csf, share.factors
+            self.plan = sc.plan_create(expr, self.host_csf, [np.ascontiguousarray(f) for f in factors], sched)
+        else:
+            self.host_csf = sc.coo_to_csf(list(coords), vals, dims)
+            self.plan = sc.plan_create(expr, self.host_csf, [np.ascontiguousarray(f) for f in factors], sched)
+            self.csf = self.host_csf.to_device(self.device)
+            self.factors = [torch.from_numpy(np.ascontiguousarray(f)).to(self.device) for f in factors]
         tdt = torch.float64 if np.asarray(vals).dtype == np.float64 else torch.float32
         # NaN-filled so that any element the library fails to write is caught
         self.out = torch.full(tuple(int(s) for s in out_shape), float("nan"), dtype=tdt, device=self.device)

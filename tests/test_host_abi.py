@@ -191,6 +191,34 @@ def test_structure_validation_errors():
     assert broken(too_many_slices) in ("SC_ERR_BAD_DIMS", "SC_ERR_CRD_RANGE")
     assert sc.lib().sc_plan_create(None, b"x", None, None, 0, None) == sc.STATUS_NAMES.index("SC_ERR_NULL")
 
+    # Node counts are checked before any array is sized from them, for device views too (whose arrays would
+    # have to be copied first): a negative or oversized count is an error status, never an exception that
+    # crosses the C boundary.
+    def device_view(nfib):
+        c = sc.Csf(csf.order, csf.dims, csf.nnz, csf.dtype_code, nfib, csf.pos, csf.crd, csf.vals, True)
+        return _status(sc.plan_create, cfg["expr"], c, f, ok)
+
+    assert device_view((-5, csf.nfib[1], csf.nfib[2])) == "SC_ERR_BAD_DIMS"
+    assert device_view((csf.nfib[0], -1, csf.nfib[2])) == "SC_ERR_BAD_DIMS"
+    assert device_view((csf.nfib[0], csf.nfib[2] + 1, csf.nfib[2])) == "SC_ERR_BAD_DIMS"
+    assert device_view((csf.nfib[0], csf.nfib[1], csf.nfib[2] + 7)) == "SC_ERR_BAD_DIMS"
+
+
+def test_factors_of_2_gib_or_more_are_refused_at_plan_time():
+    """Factor rows are addressed with 31-bit byte offsets (bit 31 is the end-of-node mark of the walks):
+    a factor that spans 2 GiB or more is refused when the plan is made, for every schedule."""
+    cfg, data, csf = _small(2, 0.002)
+    J, K = cfg["dims"][1], cfg["dims"][2]
+    for which in ("fused", "fissioned"):
+        # bare shapes (no data): C with 2^31 bytes of rows x cols
+        big_rows = (1 << 31) // (32 * 4)
+        c2 = sc.Csf(csf.order, (csf.dims[0], big_rows, K), csf.nnz, csf.dtype_code, csf.nfib, csf.pos, csf.crd, csf.vals, False)
+        fac = [sc.dense_view(None, "f32", rows=big_rows, cols=32), sc.dense_view(None, "f32", rows=K, cols=32)]
+        assert _status(sc.plan_create, cfg["expr"], c2, fac, sc.schedule(which)) == "SC_ERR_SHAPE_MISMATCH"
+        fac = [sc.dense_view(None, "f32", rows=big_rows - 1, cols=32), sc.dense_view(None, "f32", rows=K, cols=32)]
+        c3 = sc.Csf(csf.order, (csf.dims[0], big_rows - 1, K), csf.nnz, csf.dtype_code, csf.nfib, csf.pos, csf.crd, csf.vals, False)
+        assert _status(sc.plan_create, cfg["expr"], c3, fac, sc.schedule(which)) == "SC_OK"
+
 
 @pytest.mark.parametrize("cid,scale,which", [(2, 0.004, "fused"), (2, 0.004, "fissioned"), (3, 0.003, "fused"),
                                              (4, 0.003, "fused"), (5, 0.004, "fused"), (1, 1.0, "fissioned")])
