@@ -204,6 +204,22 @@ sc_status sc_execute(const sc_plan *plan, const sc_csf_view *sparse, const sc_de
                      int32_t nfactors, void *out, void *workspace, size_t workspace_bytes,
                      void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): sc_execute with the workspace taken from a fixed array
+ * of SC_STATIC_WORKSPACE_BYTES bytes inside the library's device image instead of a caller buffer.
+ * Same arguments, checks, kernels and results as sc_execute otherwise.  Calls no hipMalloc /
+ * hipFree or any other allocating routine; the array's device address is looked up once per GPU
+ * (at the first sc_plan_create or sc_execute_static on that GPU) and the array stays resident on
+ * every GPU the library has run on until the process ends.  A plan whose
+ * sc_plan_workspace_bytes() exceeds SC_STATIC_WORKSPACE_BYTES is refused with
+ * SC_ERR_WORKSPACE_SMALL before anything is launched.  All calls on one GPU share the array, which
+ * keeps the contents of the last call (the kernels clear what they need to start from zero):
+ * executions that overlap on one GPU (two streams, two plans) race on it -- serialise them, or use
+ * sc_execute with separate workspaces. */
+#define SC_STATIC_WORKSPACE_BYTES ((size_t)32 << 20)
+sc_status sc_execute_static(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors,
+                            int32_t nfactors, void *out, void *hip_stream);
+
 /* Optional per-kernel timing.  With profiling on, sc_execute brackets each kernel it
  * launches with plan-owned HIP events on the caller's stream; after the caller has
  * synchronised the stream, sc_plan_kernel_time reports the elapsed milliseconds of launch

@@ -33,7 +33,7 @@ EXPORTS = [
     "sc_version", "sc_status_string", "sc_coo_to_csf_sizes", "sc_coo_to_csf", "sc_plan_create",
     "sc_plan_workspace_bytes", "sc_plan_describe", "sc_plan_model", "sc_plan_intermediate", "sc_execute",
     "sc_plan_set_profiling", "sc_plan_kernel_count", "sc_plan_kernel_time", "sc_plan_tile_count", "sc_plan_tile",
-    "sc_tuning_set", "sc_stream_copy", "sc_plan_destroy",
+    "sc_tuning_set", "sc_stream_copy", "sc_plan_destroy", "sc_execute_static",
 ]
 
 _c_i32p = ctypes.POINTER(ctypes.c_int32)
@@ -316,6 +316,18 @@ def execute(plan: Plan, csf: Csf, factors, out, workspace=None, workspace_bytes=
                           ctypes.c_void_p(_addr(out)), ctypes.c_void_p(_addr(workspace)),
                           ctypes.c_size_t(int(workspace_bytes)), ctypes.c_void_p(int(stream)))
     _check(st, "sc_execute")
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20   # SC_STATIC_WORKSPACE_BYTES of the header
+
+
+def execute_static(plan: Plan, csf: Csf, factors, out, stream=0):
+    """sc_execute with the library's own fixed scratch array as the workspace (allocates nothing)."""
+    fv = (DenseView * len(factors))(*[f if isinstance(f, DenseView) else dense_view(f) for f in factors])
+    view = csf.view()
+    st = lib().sc_execute_static(plan.handle, ctypes.byref(view), fv, ctypes.c_int32(len(factors)),
+                                 ctypes.c_void_p(_addr(out)), ctypes.c_void_p(int(stream)))
+    _check(st, "sc_execute_static")
 
 
 def plan_set_profiling(plan: Plan, on: bool):

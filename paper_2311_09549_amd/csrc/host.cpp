@@ -994,6 +994,10 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
                 return SC_ERR_DEVICE;
         }
         p->has_device = true;
+        // set-up step of sc_execute_static: look the fixed scratch array up on this device now, so that the
+        // entry point itself has nothing left to resolve (a failure here only matters to that entry point)
+        sc_status ignored = SC_OK;
+        (void)static_scratch(&ignored);
     } else {
         (void)hipGetLastError();
     }

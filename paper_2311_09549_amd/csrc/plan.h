@@ -170,6 +170,9 @@ size_t lds_bytes_needed(const sc_plan *plan);
 sc_status execute_checked(const sc_plan *plan, const sc_csf_view *sparse, const sc_dense_view *factors, int32_t nfactors, void *out,
                           void *workspace, size_t workspace_bytes, hipStream_t stream);
 
+// Device address of the library's fixed scratch array on the current device (static_scratch.hip).
+void *static_scratch(sc_status *st);
+
 sc_status launch_plan(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac /*canonical order*/,
                       void *out, void *workspace, hipStream_t stream);
 
