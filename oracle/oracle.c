@@ -204,6 +204,38 @@ int oracle_ttmc4(int64_t nnz, const int32_t *ci, const int32_t *cj, const int32_
 }
 
 /*
+ * Table 2, kernel 5 <3D TTMC> (the running example of Sections 1 and 3, Figure 2a):
+ * A(l,m,n) = sum_{i,j,k} B(i,j,k) * C(i,l) * D(j,m) * E(k,n).
+ * A is L x M x N, C is I x L, D is J x M, E is K x N.  The output carries no sparse index, so
+ * the outermost loop here is the dense index l (the perfectly nested loop of Figure 2a may
+ * take its six loops in any order that respects the sparse operand's level order): threads
+ * own disjoint slabs A(l,:,:) and every slab sums the stored entries in storage order.
+ */
+int oracle_ttmc_all(int64_t nnz, const int32_t *ci, const int32_t *cj, const int32_t *ck, const double *vals,
+                    int64_t I, int64_t J, int64_t K, const double *C, int64_t L, const double *D, int64_t M,
+                    const double *E, int64_t N, double *A, int nthreads)
+{
+    for (int64_t z = 0; z < nnz; ++z)
+        if (ci[z] < 0 || ci[z] >= I || cj[z] < 0 || cj[z] >= J || ck[z] < 0 || ck[z] >= K) return -2;
+    memset(A, 0, sizeof(double) * (size_t)(L * M * N));
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+    for (int64_t l = 0; l < L; ++l) {
+        double *Al = A + l * M * N;
+        for (int64_t z = 0; z < nnz; ++z) {
+            const double b = vals[z];
+            const double c = C[(int64_t)ci[z] * L + l];
+            const double *Dj = D + (int64_t)cj[z] * M;
+            const double *Ek = E + (int64_t)ck[z] * N;
+            for (int64_t m = 0; m < M; ++m)
+                for (int64_t n = 0; n < N; ++n)
+                    Al[m * N + n] += b * c * Dj[m] * Ek[n];
+        }
+    }
+    return 0;
+}
+
+/*
  * SpMM, the loop of Figure 1b:  A(i,k) = sum_j B(i,j) * C(j,k).
  * Kept as the degenerate order-2 member of the family; used to pin the others.
  */

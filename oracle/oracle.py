@@ -139,6 +139,21 @@ def contract_ttmc4(coords, vals, dims, C, D, E, nthreads=None):
     return A
 
 
+def contract_ttmc_all(coords, vals, dims, C, D, E, nthreads=None):
+    """A(l,m,n) = sum_ijk B(i,j,k) C(i,l) D(j,m) E(k,n)   (Table 2, kernel 5; Figure 2a)."""
+    ci, cj, ck = (_i32(c) for c in coords)
+    v, C, D, E = _f64(vals), _f64(C), _f64(D), _f64(E)
+    I, J, K = (int(d) for d in dims)
+    L, M, N = C.shape[1], D.shape[1], E.shape[1]
+    assert C.shape[0] == I and D.shape[0] == J and E.shape[0] == K
+    A = np.empty((L, M, N), dtype=np.float64)
+    rc = _load().oracle_ttmc_all(_i64(v.size), _p(ci, _pi32), _p(cj, _pi32), _p(ck, _pi32), _p(v, _pf64),
+                                 _i64(I), _i64(J), _i64(K), _p(C, _pf64), _i64(L), _p(D, _pf64), _i64(M),
+                                 _p(E, _pf64), _i64(N), _p(A, _pf64), ctypes.c_int(_threads(nthreads)))
+    _check(rc, "oracle_ttmc_all")
+    return A
+
+
 def contract_spmm(coords, vals, dims, C, nthreads=None):
     """A(i,k) = sum_j B(i,j) C(j,k)   (Figure 1b)."""
     ci, cj = (_i32(c) for c in coords)
@@ -159,6 +174,7 @@ _CONTRACT = {
     "mttkrp3": contract_mttkrp3,
     "sddmm_spmm": contract_sddmm_spmm,
     "ttmc4": contract_ttmc4,
+    "ttmc_all": contract_ttmc_all,
 }
 
 
@@ -233,6 +249,18 @@ def intermediate_t2_order4(coords, vals, dims, D, E):
     p = np.asarray(coords[3], dtype=np.int64)
     np.add.at(T2, inv, _f64(vals)[:, None, None] * D[k][:, :, None] * E[p][:, None, :])
     return pre, T2
+
+
+def intermediate_slice_ttmc_all(coords, vals, dims, D, E):
+    """Kernel 5, second and third schedule of Table 2: T(s, m, n) = sum over the nonzeros z of the
+    s-th non-empty slice i of vals[z] * D(j,m) * E(k,n).  Returns (slice coordinates, T)."""
+    pre, inv = prefixes(coords, dims, 1)
+    D, E = _f64(D), _f64(E)
+    T = np.zeros((pre.shape[1], D.shape[1], E.shape[1]), dtype=np.float64)
+    j = np.asarray(coords[1], dtype=np.int64)
+    k = np.asarray(coords[2], dtype=np.int64)
+    np.add.at(T, inv, _f64(vals)[:, None, None] * D[j][:, :, None] * E[k][:, None, :])
+    return pre, T
 
 
 def intermediate_sampled(coords, vals, X, Y):

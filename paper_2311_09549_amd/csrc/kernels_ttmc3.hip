@@ -332,9 +332,9 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc3_lds_bytes(a.tn, a.ta, a.tb);
-    const int fit = lds_workgroups_per_cu(lds);
+    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
     // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
-    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : 4 * fit;
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : 4 * fit;
     // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
     const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);

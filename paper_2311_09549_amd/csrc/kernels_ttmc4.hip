@@ -438,11 +438,11 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb, mode);
-    const int fit = lds_workgroups_per_cu(lds);
+    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
     // several runs per resident workgroup slot: shorter runs even out the tiles' different costs, longer
     // ones save row updates; six per slot measured best for the fused kernel (24 per compute unit), 32 per
     // compute unit for the two kernels of the FISSIONED schedule
-    const int per_cu = tuning().per_cu > 0 ? std::min(tuning().per_cu, 64) : (mode == 0 ? 6 * fit : 32);
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : (mode == 0 ? 6 * fit : 32);
     // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
     const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);

@@ -21,6 +21,7 @@ EINSUM = {
     "ttmc3": "ijk,jl,km->ilm",
     "mttkrp3": "ijk,jr,kr->ir",
     "ttmc4": "ijkp,jl,km,pn->ilmn",
+    "ttmc_all": "ijk,il,jm,kn->lmn",
 }
 
 
@@ -38,6 +39,8 @@ def _random_case(kind, rng, dims, nnz, ranks, empty_rows=()):
         shapes = [(dims[1], ranks[0]), (dims[2], ranks[0])]
     elif kind == "sddmm_spmm":
         shapes = [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1])]
+    elif kind == "ttmc_all":
+        shapes = [(dims[0], ranks[0]), (dims[1], ranks[1]), (dims[2], ranks[2])]
     else:
         shapes = [(dims[1], ranks[0]), (dims[2], ranks[1]), (dims[3], ranks[2])]
     factors = [rng.standard_normal(s) for s in shapes]
@@ -65,12 +68,14 @@ CASES = [
     ("mttkrp3", (5, 6, 7), 70, (3,)),
     ("sddmm_spmm", (6, 7), 20, (3, 4)),
     ("ttmc4", (3, 4, 5, 6), 90, (2, 3, 4)),
+    ("ttmc_all", (5, 6, 7), 60, (2, 3, 4)),
+    ("ttmc_all", (4, 3, 9), 108, (4, 2, 3)),   # every coordinate stored
 ]
 
 
 def test_golden_worked_examples(oracle):
     g = json.load(open(os.path.join(HERE, "golden", "worked_examples.json")))
-    for kind in ("ttmc3", "mttkrp3", "sddmm_spmm", "ttmc4"):
+    for kind in ("ttmc3", "mttkrp3", "sddmm_spmm", "ttmc4", "ttmc_all"):
         e = g[kind]
         A = oracle.contract(kind, np.array(e["coords"]), np.array(e["vals"], float), e["dims"],
                             [np.array(f, float) for f in e["factors"]])
@@ -85,7 +90,8 @@ def test_bruteforce_dense_einsum(oracle, kind, dims, nnz, ranks):
     ref = _brute(kind, coords, vals, dims, factors)
     assert A.shape == ref.shape
     np.testing.assert_allclose(A, ref, rtol=0, atol=1e-12 * max(1.0, np.abs(ref).max()))
-    assert np.all(A[1] == 0.0)  # the emptied slice gives an exactly-zero row
+    if kind != "ttmc_all":   # (its output has no sparse index)
+        assert np.all(A[1] == 0.0)  # the emptied slice gives an exactly-zero row
 
 
 @pytest.mark.parametrize("kind,dims,nnz,ranks", CASES)
@@ -273,3 +279,48 @@ def test_out_of_range_coordinate_is_rejected(oracle):
     with pytest.raises(ValueError):
         oracle.contract_ttmc3(np.array([[0], [9], [0]], dtype=np.int32), np.ones(1), (2, 2, 2),
                               np.ones((2, 1)), np.ones((2, 1)))
+
+
+def test_ttmc_all_is_the_mode0_contraction_of_kernel6(oracle):
+    """Kernel 5 = kernel 6 (whose oracle is pinned above and against scipy) followed by the dense
+    contraction of the remaining sparse mode: A(l,m,n) = sum_i C(i,l) * [sum_jk B(i,j,k) D(j,m) E(k,n)]."""
+    rng = np.random.default_rng(31)
+    dims, ranks = (6, 5, 7), (3, 2, 4)
+    coords, vals, (C, D, E) = _random_case("ttmc_all", rng, dims, 80, ranks, empty_rows=(2,))
+    A = oracle.contract("ttmc_all", coords, vals, dims, [C, D, E])
+    S = oracle.contract("ttmc3", coords, vals, dims, [D, E])          # S(i,m,n)
+    np.testing.assert_allclose(A, np.einsum("il,imn->lmn", C, S), rtol=0, atol=1e-12)
+    # and it reduces to a dense triple product when one factor is all ones along a unit rank
+    ones = np.ones((dims[0], 1))
+    A1 = oracle.contract("ttmc_all", coords, vals, dims, [ones, D, E])
+    np.testing.assert_allclose(A1[0], D.T @ _dense(coords, vals, dims).sum(axis=0) @ E, rtol=0, atol=1e-12)
+
+
+def test_ttmc_all_closed_forms(oracle):
+    rng = np.random.default_rng(32)
+    dims = (4, 5, 6)
+    coords, vals, _ = _random_case("ttmc_all", rng, dims, 50, (2, 3, 4))
+    # all-ones factors: every output element is the sum of all stored values
+    f1 = [np.ones((dims[0], 2)), np.ones((dims[1], 3)), np.ones((dims[2], 4))]
+    A = oracle.contract("ttmc_all", coords, vals, dims, f1)
+    np.testing.assert_allclose(A, np.full((2, 3, 4), vals.sum()), rtol=0, atol=1e-12)
+    # identity factors: the output is the dense operand itself (distinct extents: a transposed mode cannot pass)
+    A = oracle.contract("ttmc_all", coords, vals, dims, [np.eye(d) for d in dims])
+    assert np.array_equal(A, _dense(coords, vals, dims))
+
+
+def test_ttmc_all_slice_intermediate(oracle):
+    """T(i,m,n) of the second and third schedule of Table 2, kernel 5, against dense einsum, and the
+    output rebuilt from it (fissioned = fused = linear, Section 4.1)."""
+    rng = np.random.default_rng(33)
+    dims, ranks = (7, 4, 5), (3, 2, 4)
+    coords, vals, (C, D, E) = _random_case("ttmc_all", rng, dims, 60, ranks, empty_rows=(3,))
+    pre, T = oracle.intermediate_slice_ttmc_all(coords, vals, dims, D, E)
+    dense_T = np.einsum("ijk,jm,kn->imn", _dense(coords, vals, dims), D, E)
+    assert np.array_equal(pre[0], np.unique(coords[0]))
+    np.testing.assert_allclose(T, dense_T[pre[0]], rtol=0, atol=1e-12)
+    A = oracle.contract("ttmc_all", coords, vals, dims, [C, D, E])
+    np.testing.assert_allclose(np.einsum("sl,smn->lmn", C[pre[0]], T), A, rtol=0, atol=1e-12)
+    # first schedule: t(i,j,n) per fiber, then A(l,m,n) += t * C(i,l) * D(j,m)
+    pre2, t = oracle.intermediate_leaf(coords, vals, dims, E)
+    np.testing.assert_allclose(np.einsum("fl,fm,fn->lmn", C[pre2[0]], D[pre2[1]], t), A, rtol=0, atol=1e-12)

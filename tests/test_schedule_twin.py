@@ -145,3 +145,171 @@ def test_factored_nest_matches_linear_nest_and_its_operation_count(cid, scale):
     for which in ("fused", "fissioned"):
         plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule(which))
         assert sc.plan_model(plan)[0] == fused
+
+
+# ---------------------------------------------------------------------------
+# Kernel 5 (all-mode TTMC): the schedules of Figure 2 and the three chosen schedules of Table 2
+# ---------------------------------------------------------------------------
+
+def fig2_a(coords, vals, dims, C, D, E, cnt):
+    """Figure 2a: the perfectly nested loop; one iteration per (l, m, n, stored entry)."""
+    L, M, N = C.shape[1], D.shape[1], E.shape[1]
+    A = np.zeros((L, M, N))
+    for l in range(L):
+        for m in range(M):
+            for n in range(N):
+                for z in range(len(vals)):
+                    i, j, k = coords[0][z], coords[1][z], coords[2][z]
+                    A[l, m, n] += vals[z] * C[i, l] * D[j, m] * E[k, n]
+                    cnt.n += 1
+    return A
+
+
+def fig2_b(coords, vals, dims, C, D, E, cnt):
+    """Figure 2b: for (m, l): T<k> from the stored entries, then A(l,m,n) += T(k) E(k,n) over dense k."""
+    L, M, N = C.shape[1], D.shape[1], E.shape[1]
+    K = dims[2]
+    A = np.zeros((L, M, N))
+    for m in range(M):
+        for l in range(L):
+            T = np.zeros(K)
+            for z in range(len(vals)):
+                T[coords[2][z]] += vals[z] * C[coords[0][z], l] * D[coords[1][z], m]
+                cnt.n += 1
+            for n in range(N):
+                for k in range(K):
+                    A[l, m, n] += T[k] * E[k, n]
+                    cnt.n += 1
+    return A
+
+
+def fig2_c(coords, vals, dims, C, D, E, cnt):
+    """Figure 2c (Phi(d) in the text of the cases): for l: T<k,j> from the stored entries; for (m, k):
+    t = sum_j T(k,j) D(j,m); A(l,m,n) += t E(k,n)."""
+    L, M, N = C.shape[1], D.shape[1], E.shape[1]
+    J, K = dims[1], dims[2]
+    A = np.zeros((L, M, N))
+    for l in range(L):
+        T = np.zeros((K, J))
+        for z in range(len(vals)):
+            T[coords[2][z], coords[1][z]] += vals[z] * C[coords[0][z], l]
+            cnt.n += 1
+        for m in range(M):
+            for k in range(K):
+                t = 0.0
+                for j in range(J):
+                    t += T[k, j] * D[j, m]
+                    cnt.n += 1
+                for n in range(N):
+                    A[l, m, n] += t * E[k, n]
+                    cnt.n += 1
+    return A
+
+
+def table2_k5(coords, vals, dims, C, D, E, which, cnt):
+    """The chosen schedules of Table 2, kernel 5, over a CSF walk; cnt counts loop iterations of the
+    innermost statements (the iteration complexity of Section 3)."""
+    L, M, N = C.shape[1], D.shape[1], E.shape[1]
+    A = np.zeros((L, M, N))
+    f1, f2 = _fibers(coords, 1), _fibers(coords, 2)
+    for s in range(len(f1) - 1):
+        i = coords[0][f1[s]]
+        fa, fb = np.searchsorted(f2, f1[s]), np.searchsorted(f2, f1[s + 1])
+        if which == 1:      # i, j', n < t; k': t += B E_kn ; m, l: A_lmn += t C_il D_jm >
+            for f in range(fa, fb):
+                j = coords[1][f2[f]]
+                for n in range(N):
+                    t = 0.0
+                    for z in range(f2[f], f2[f + 1]):
+                        t += vals[z] * E[coords[2][z], n]
+                        cnt.n += 1
+                    for m in range(M):
+                        for l in range(L):
+                            A[l, m, n] += t * C[i, l] * D[j, m]
+                            cnt.n += 1
+        elif which == 2:    # i, n < T_m ; j' < t; k': t += B E_kn, m: T_m += t D_jm > , m, l: A_lmn += T_m C_il >
+            for n in range(N):
+                Tm = np.zeros(M)
+                for f in range(fa, fb):
+                    j = coords[1][f2[f]]
+                    t = 0.0
+                    for z in range(f2[f], f2[f + 1]):
+                        t += vals[z] * E[coords[2][z], n]
+                        cnt.n += 1
+                    for m in range(M):
+                        Tm[m] += t * D[j, m]
+                        cnt.n += 1
+                for m in range(M):
+                    for l in range(L):
+                        A[l, m, n] += Tm[m] * C[i, l]
+                        cnt.n += 1
+        else:               # i, m, n < t; j', k': t += B D_jm E_kn ; l: A_lmn += t C_il >
+            for m in range(M):
+                for n in range(N):
+                    t = 0.0
+                    for z in range(f1[s], f1[s + 1]):
+                        t += vals[z] * D[coords[1][z], m] * E[coords[2][z], n]
+                        cnt.n += 1
+                    for l in range(L):
+                        A[l, m, n] += t * C[i, l]
+                        cnt.n += 1
+    return A
+
+
+def _k5_case(seed, dims, nnz, ranks):
+    rng = np.random.default_rng(seed)
+    flat = np.sort(rng.choice(int(np.prod(dims)), size=nnz, replace=False))
+    coords = [c.astype(np.int32) for c in np.unravel_index(flat, dims)]
+    vals = rng.uniform(-1, 1, nnz)
+    C, D, E = (rng.standard_normal((d, r)) for d, r in zip(dims, ranks))
+    return coords, vals, C, D, E
+
+
+def test_kernel5_figure2_schedules_and_their_iteration_counts():
+    """Figure 2: the branched nests compute what the perfectly nested loop (the oracle) computes, in
+    exactly Phi(a) = LMN nnz, Phi(b) = LM (nnz + NK), Phi(c) = L (nnz + MK (J + N)) iterations."""
+    dims, ranks, nnz = (4, 5, 6), (3, 2, 4), 37
+    coords, vals, C, D, E = _k5_case(51, dims, nnz, ranks)
+    ref = oracle.contract("ttmc_all", coords, vals, dims, [C, D, E])
+    bound = oracle.abs_bound("ttmc_all", coords, vals, dims, [C, D, E])
+    L, M, N = ranks
+    J, K = dims[1], dims[2]
+    for fn, phi in ((fig2_a, L * M * N * nnz), (fig2_b, L * M * (nnz + N * K)), (fig2_c, L * (nnz + M * K * (J + N)))):
+        cnt = Counter()
+        got = fn(coords, vals, dims, C, D, E, cnt)
+        assert np.all(np.abs(got - ref) <= 1e-13 * bound), fn.__name__
+        assert cnt.n == phi, fn.__name__
+
+
+def test_kernel5_iteration_count_ratios_of_the_motivating_cases():
+    """Section 3, Case 1 prints Phi(b) ~ 7.5 Phi(d) and Phi(a) ~ 237.5 Phi(d) for I, J, K = 1800, 800, 1000,
+    L, M, N = 64, 16, 32; Case 2 (J, K = 1600, 2000) prints ~3 and ~92.5.  With the closed forms the twins
+    above were checked against, these ratios come out at sparsity 0.008 and 0.002 (the text's 0.08 and 0.02
+    give 14 / 459 and 11 / 352): the printed sparsities carry one zero too few.  Case 4 prints its two
+    ratios with the schedule labels exchanged: Phi(a) / Phi(b) is 40.4 and Phi(d) / Phi(b) is 1.14."""
+    def phis(I, J, K, L, M, N, sparsity):
+        nnz = sparsity * I * J * K
+        return L * M * N * nnz, L * M * (nnz + N * K), L * (nnz + M * K * (J + N))
+    a, b, d = phis(1800, 800, 1000, 64, 16, 32, 0.008)
+    assert abs(b / d - 7.44) < 0.01 and abs(a / d - 237.5) < 0.5
+    a, b, d = phis(1800, 1600, 2000, 64, 16, 32, 0.002)
+    assert abs(b / d - 3.0) < 0.1 and abs(a / d - 92.5) < 1.0
+    a, b, d = phis(1800, 800, 1000, 64, 16, 32, 0.08)
+    assert a / d > 400   # what the printed sparsity would give
+    a, b, d = phis(265, 1207, 479, 251, 234, 42, 0.0033)
+    assert abs(a / b - 40.4) < 0.5 and abs(d / b - 1.13) < 0.03
+
+
+@pytest.mark.parametrize("which", [1, 2, 3])
+def test_kernel5_table2_schedules_match_the_oracle_and_their_counts(which):
+    dims, ranks, nnz = (5, 4, 6), (3, 2, 4), 41
+    coords, vals, C, D, E = _k5_case(52, dims, nnz, ranks)
+    ref = oracle.contract("ttmc_all", coords, vals, dims, [C, D, E])
+    bound = oracle.abs_bound("ttmc_all", coords, vals, dims, [C, D, E])
+    cnt = Counter()
+    got = table2_k5(coords, vals, dims, C, D, E, which, cnt)
+    assert np.all(np.abs(got - ref) <= 1e-13 * bound)
+    L, M, N = ranks
+    S, F = len(_fibers(coords, 1)) - 1, len(_fibers(coords, 2)) - 1
+    want = {1: N * (nnz + F * M * L), 2: N * (nnz + F * M + S * M * L), 3: M * N * (nnz + S * L)}[which]
+    assert cnt.n == want
