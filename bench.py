@@ -49,7 +49,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0,
-                    help="measure only this workload (1..5); default: all five, headline on the largest")
+                    help="measure only this workload (1..5; 6 = the headline workload plus the all-mode TTMC); default: all five and the all-mode TTMC, headline on the largest")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workloads (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
@@ -233,7 +233,53 @@ def main() -> int:
             rec["gpu_vs_cpu_oracle"] = rec["gflops"] / rec["cpu_baseline"]["value"]
         return rec
 
-    cids = [args.config] if args.config else [1, 2, 3, 4, 5]
+    def bench_ttmc_all():
+        """All-mode TTMC (Table 2, kernel 5) under the three schedules Table 2 lists, on a workload of the first dense
+        sizes of the paper's auxiliary-memory table: not one of the five benchmark workloads, reported beside them."""
+        cid = 6
+        cfg = synth.config(cid, args.scale)
+        data = synth.generate(cfg, cache_dir=os.environ.get("TMPDIR", "/tmp") + "/sc_synth_cache")
+        out_shape = synth.output_shape(cfg)
+        rec = {"workload": "all-mode TTMC A(l,m,n) (Table 2, kernel 5), fp32, 40,000x20,000x8,000, 4M Zipf(1.1) nonzeros, L=M=N=16",
+               "nnz": int(cfg["nnz"]), "schedules": {}}
+        variants = [("schedule2_fused", "fused", []), ("schedule2_fissioned", "fissioned", ["T1(i,j,n)", "T2(i,m,n)"]),
+                    ("schedule1", "fissioned", ["T(i,j,n)"]), ("schedule3", "fused", ["T(i,m,n)"])]
+        first = None
+        for name, kind, temps in variants:
+            con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                              sc.schedule(kind, temps, [0] * len(temps)), out_shape, share=first)
+            first = first or con
+            flops, nbytes = sc.plan_model(con.plan)
+            ms, stats = timed(con, max(5, args.steps // 2), 2)
+            kt = kernel_times(con, 5)
+            dom = max(kt, key=kt.get)
+            rec["schedules"][name] = {
+                "ms_per_step": ms, "ms_per_step_stats": stats, "schedule_flops": flops, "gflops": flops / (ms * 1e-3) / 1e9,
+                "kernels_ms": kt, "workspace_bytes": con.ws_bytes,
+                "roofline": {"bound": "hbm", "kernel": dom, "algorithmic_bytes": nbytes, "kernel_ms": kt[dom],
+                             "achieved": nbytes / (kt[dom] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": nbytes / (kt[dom] * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+            }
+            if con is not first:
+                del con
+        del first
+        torch.cuda.empty_cache()
+        base = rec["schedules"]["schedule2_fused"]["ms_per_step"]
+        rec["speedup_of_schedule2_fused_over"] = {k: v["ms_per_step"] / base for k, v in rec["schedules"].items()}
+        if not args.no_cpu_baseline:
+            from oracle import oracle as o
+            o.build()
+            cores = o.max_threads()
+            secs = o.time_contract(cfg["kind"], data["coords"], data["vals"], cfg["dims"], data["factors"], nthreads=cores, warmup=1, runs=3)
+            t_cpu = float(np.median(secs))
+            L, M, N = cfg["ranks"]
+            rec["cpu_baseline"] = {"seconds": t_cpu, "cores": cores, "kind": "oracle", "unit": "GFLOP/s",
+                                   "value": 4.0 * L * M * N * cfg["nnz"] / t_cpu / 1e9,
+                                   "sample": "whole workload, the perfectly nested loop of Figure 2a in fp64 (4 L M N nnz flops), "
+                                             "C call only, 1 warm-up + median of 3 runs"}
+        return rec
+
+    cids = [5] if args.config == 6 else [args.config] if args.config else [1, 2, 3, 4, 5]
     per_config = []
     for cid in cids:
         per_config.append(bench_config(cid))
@@ -268,6 +314,8 @@ def main() -> int:
         if k in head:
             result[k] = head[k]
     result["per_config"] = per_config
+    if not args.config or args.config == 6:
+        result["next_workloads"] = {"ttmc_all": bench_ttmc_all()}
     print(json.dumps(result))
     return 0
 

@@ -135,10 +135,36 @@ sc_status classify(const Term &lhs, const std::vector<Term> &rhs, Family &fam)
         std::set<std::string> u(sp.idx.begin(), sp.idx.end());
         if (u.size() != d) return SC_ERR_EXPR_UNSUPPORTED;
     }
-    if (lhs.idx.empty() || lhs.idx[0] != sp.idx[0]) return SC_ERR_EXPR_UNSUPPORTED;
     const size_t nf = rhs.size() - 1;
     for (size_t f = 1; f <= nf; ++f)
         if (rhs[f].idx.size() != 2 || rhs[f].idx[0] == rhs[f].idx[1]) return SC_ERR_EXPR_UNSUPPORTED;
+    if (d == 3 && nf == 3 && lhs.idx.size() == 3 && !contains(sp.idx, lhs.idx[0])) {
+        // B(i,j,k) * C(i,l) * D(j,m) * E(k,n) -> A(l,m,n): a factor on every mode, no sparse index in the output
+        // (kernel 5 of Table 2).  Temporaries of its second schedule: the producer B*E keeps {i,j,n}, B*E*D keeps {i,m,n}.
+        int on[3];
+        for (size_t m = 0; m < 3; ++m) {
+            on[m] = -1;
+            for (size_t f = 1; f <= nf; ++f)
+                if (rhs[f].idx[0] == sp.idx[m]) {
+                    if (on[m] >= 0) return SC_ERR_EXPR_UNSUPPORTED;
+                    on[m] = (int)f;
+                }
+            if (on[m] < 0) return SC_ERR_EXPR_UNSUPPORTED;
+        }
+        std::set<std::string> ux;
+        for (size_t m = 0; m < 3; ++m) {
+            const std::string &xi = rhs[on[m]].idx[1];
+            if (contains(sp.idx, xi) || lhs.idx[m] != xi) return SC_ERR_EXPR_UNSUPPORTED;
+            ux.insert(xi);
+            fam.slot_of_factor[m] = on[m] - 1;
+        }
+        if (ux.size() != 3) return SC_ERR_EXPR_UNSUPPORTED;
+        fam.kind = K_TTMC_ALL;
+        fam.temp_idx = {{sp.idx[0], sp.idx[1], lhs.idx[2]}, {sp.idx[0], lhs.idx[1], lhs.idx[2]}};
+        fam.temp_name = {"T1", "T2"};
+        return SC_OK;
+    }
+    if (lhs.idx.empty() || lhs.idx[0] != sp.idx[0]) return SC_ERR_EXPR_UNSUPPORTED;
 
     auto find_on = [&](const std::string &first, int skip_pos) -> int {
         for (size_t f = 1; f <= nf; ++f)
@@ -679,6 +705,147 @@ extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
     return guarded([&] { return coo_to_csf_impl(coo, out); });
 }
 
+static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_view *sparse, const sc_dense_view *factors,
+                                  int32_t nfactors, const sc_schedule *sched);
+
+// Kernel 5 of Table 2 (all-mode TTMC).  The caller picks one of the three schedules Table 2 lists by naming
+// its temporaries: {T(i,j,n)} = schedule 1, {T1(i,j,n), T2(i,m,n)} or nothing = schedule 2, {T(i,m,n)} = schedule 3.
+// The sparse part is planned as an inner order-3 chain over the same tensor with the factors on modes 1 and 2.
+static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, const std::vector<Term> &rhs, const Family &fam,
+                               const sc_csf_view *sparse, const sc_dense_view *factors, const sc_schedule *sched)
+{
+    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;   // no unfactored nest for this kernel
+    if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
+    p->sched = sched->kind;
+    p->deterministic = sched->deterministic == 1;
+    // which schedule: match the named temporaries against the derived index sets
+    int variant = 2;
+    if (sched->n_intermediates < 0 || sched->n_intermediates > 2) return SC_ERR_SCHED_UNSUPPORTED;
+    if (sched->n_intermediates) {
+        bool has[2] = {false, false};
+        for (int t = 0; t < sched->n_intermediates; ++t) {
+            if (!sched->intermediate[t]) return SC_ERR_SCHED_UNSUPPORTED;
+            Term tt;
+            const char *q = sched->intermediate[t];
+            if (!parse_term(q, tt)) return SC_ERR_SCHED_UNSUPPORTED;
+            while (*q && isspace((unsigned char)*q)) ++q;
+            if (*q) return SC_ERR_SCHED_UNSUPPORTED;
+            std::set<std::string> got(tt.idx.begin(), tt.idx.end());
+            if (got.size() != tt.idx.size()) return SC_ERR_SCHED_UNSUPPORTED;
+            int match = -1;
+            for (int u = 0; u < 2; ++u) {
+                std::set<std::string> want(fam.temp_idx[u].begin(), fam.temp_idx[u].end());
+                if (!has[u] && want == got) match = u;
+            }
+            if (match < 0) return SC_ERR_SCHED_UNSUPPORTED;
+            has[match] = true;
+            if (sched->fuse_depth[t] != 0) return SC_ERR_SCHED_UNSUPPORTED;   // the on-chip granularity is the library's choice here
+        }
+        variant = has[0] && has[1] ? 2 : has[0] ? 1 : 3;
+    }
+    p->k5_variant = variant;
+    // schedule 1 keeps t(i,j,n) in the workspace and schedule 3 keeps its scalar per (i,m,n) in registers of the
+    // unfactored inner nest: one class each
+    if (variant == 1 && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    if (variant == 3 && (sched->kind != SC_SCHED_FUSED || p->deterministic)) return SC_ERR_SCHED_UNSUPPORTED;
+
+    // inner plan: S(i,m,n) = B(i,j,k) * D(j,m) * E(k,n)
+    const std::vector<std::string> &si = rhs[0].idx;
+    const std::string inner_expr = "S(" + si[0] + "," + lhs.idx[1] + "," + lhs.idx[2] + ")=" + join(rhs[0].name, si) + "*D_(" + si[1] + "," +
+                                   lhs.idx[1] + ")*E_(" + si[2] + "," + lhs.idx[2] + ")";
+    const sc_dense_view inner_fac[2] = {factors[fam.slot_of_factor[1]], factors[fam.slot_of_factor[2]]};
+    sc_schedule is = {};
+    is.kind = variant == 3 ? SC_SCHED_LINEAR : variant == 1 ? SC_SCHED_FISSIONED : sched->kind;
+    is.deterministic = variant == 3 ? 0 : sched->deterministic;
+    sc_status st = plan_create_impl(&p->inner, inner_expr.c_str(), sparse, inner_fac, 2, &is);
+    if (st != SC_OK) return st;
+    const sc_plan *in = p->inner;
+    p->has_device = in->has_device;
+    p->tune = in->tune;
+    p->n_cu = in->n_cu;
+    p->lds_per_cu = in->lds_per_cu;
+    p->caps = in->caps;
+
+    const double e = (double)esize(p->dtype), nnz = (double)p->nnz;
+    const double S = (double)p->nfib[0], F = (double)p->nfib[1];
+    const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
+    // reduction over slices (fibers for schedule 1): contiguous chunks, one slot each
+    const int64_t units = variant == 1 ? p->nfib[1] : p->dims[0];
+    const int64_t per = variant == 1 ? 1024 : 64;
+    p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>((units + per - 1) / per, (int64_t)p->n_cu * 4));
+    p->k5_chunk = std::max<int64_t>(1, (units + p->k5_nchunks - 1) / p->k5_nchunks);
+    p->k5_nchunks = std::max<int64_t>(1, (units + p->k5_chunk - 1) / p->k5_chunk);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) & ~(size_t)255;
+        return at;
+    };
+    p->k5_s_offset = variant == 1 ? 0 : take((size_t)p->dims[0] * (size_t)(p->fcols[1] * p->fcols[2]) * esize(p->dtype));
+    p->k5_inner_ws_offset = take(in->ws_bytes);
+    p->k5_partials_offset = take((size_t)p->k5_nchunks * (size_t)p->out_elems * esize(p->dtype));
+    p->ws_bytes = off;
+
+    // temporaries as the caller can read them back after a FISSIONED execution: t rows (one per fiber) and
+    // the per-slice tiles (one row per coordinate of the first mode, empty slices included)
+    p->n_inter = variant == 2 ? 2 : 1;
+    const int t2 = variant == 2 ? 1 : 0;
+    if (variant != 3) {
+        p->inter[0].name = join(fam.temp_name[0], fam.temp_idx[0]);
+        p->inter[0].rows = p->nfib[1];
+        p->inter[0].cols = p->fcols[2];
+        p->inter[0].offset = p->k5_inner_ws_offset + (in->sched == SC_SCHED_FISSIONED ? in->inter[0].offset : 0);
+    }
+    if (variant != 1) {
+        p->inter[t2].name = join(fam.temp_name[1], fam.temp_idx[1]);
+        p->inter[t2].rows = p->dims[0];
+        p->inter[t2].cols = p->fcols[1] * p->fcols[2];
+        p->inter[t2].offset = p->k5_s_offset;
+    }
+
+    // iteration counts of the nests as Table 2 writes them (multiply = 1, add = 1)
+    double flops = 0;
+    if (variant == 1) flops = 2 * N * nnz + 3 * L * M * N * F;
+    else if (variant == 2) flops = 2 * N * nnz + 2 * M * N * F + 2 * L * M * N * S;
+    else flops = 3 * M * N * nnz + 2 * L * M * N * S;
+    double fac_bytes = 0;
+    for (int s = 0; s < 3; ++s) fac_bytes += (double)p->frows[s] * (double)p->fcols[s] * e;
+    double bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+    if (variant == 1 || (variant == 2 && p->sched == SC_SCHED_FISSIONED)) bytes += 2 * F * N * e;   // t(i,j,n) written and read
+    p->model_flops = flops;
+    p->model_bytes = bytes;
+
+    std::string &tx = p->text;
+    appendf(tx, "expression: %s\n", expr);
+    const char *Cn = rhs[fam.slot_of_factor[0] + 1].name.c_str(), *Dn = rhs[fam.slot_of_factor[1] + 1].name.c_str(),
+               *En = rhs[fam.slot_of_factor[2] + 1].name.c_str();
+    const char *i_ = si[0].c_str(), *j_ = si[1].c_str(), *k_ = si[2].c_str();
+    const char *l_ = lhs.idx[0].c_str(), *m_ = lhs.idx[1].c_str(), *n_ = lhs.idx[2].c_str();
+    appendf(tx, "schedule: Table 2, kernel 5, schedule %d (%s)\n", variant,
+            p->sched == SC_SCHED_FUSED ? "FUSED: the temporaries of the sparse part stay on chip" : "FISSIONED: t in the workspace");
+    if (variant == 1)
+        appendf(tx, "nest: forall(%s,%s',%s, where(forall(%s,%s, A += t * %s * %s), forall(%s', t += %s * %s)))\n", i_, j_, n_, m_, l_, Cn, Dn, k_,
+                rhs[0].name.c_str(), En);
+    else if (variant == 2)
+        appendf(tx, "nest: forall(%s,%s, where(forall(%s,%s, A += T(%s) * %s), forall(%s', where(forall(%s, T(%s) += t * %s), forall(%s', t += %s * %s)))))\n",
+                i_, n_, m_, l_, m_, Cn, j_, m_, m_, Dn, k_, rhs[0].name.c_str(), En);
+    else
+        appendf(tx, "nest: forall(%s,%s,%s, where(forall(%s, A += t * %s), forall(%s',%s', t += %s * %s * %s)))\n", i_, m_, n_, l_, Cn, j_, k_,
+                rhs[0].name.c_str(), Dn, En);
+    if (variant == 1)
+        appendf(tx, "the output has no sparse index: the rows t(%s,%s,:) pass through the workspace once and are reduced over all fibers by %lld workgroups, "
+                    "whose partial tiles are added in chunk order (always reproducible)\n", i_, j_, (long long)p->k5_nchunks);
+    else
+        appendf(tx, "the output has no sparse index: per-slice tiles S(%s,%s,%s) pass through the workspace once and are reduced over %s by %lld workgroups, "
+                    "whose partial tiles are added in chunk order (always reproducible)\n", i_, m_, n_, i_, (long long)p->k5_nchunks);
+    for (int t = 0; t < p->n_inter; ++t)
+        appendf(tx, "temporary %d: %s, %lld x %lld\n", t, p->inter[t].name.c_str(), (long long)p->inter[t].rows, (long long)p->inter[t].cols);
+    appendf(tx, "structure: nnz=%lld nodes[0]=%lld nodes[1]=%lld\n", (long long)p->nnz, (long long)p->nfib[0], (long long)p->nfib[1]);
+    appendf(tx, "model: %.6g flops, %.6g compulsory HBM bytes, workspace %zu bytes\n", flops, bytes, p->ws_bytes);
+    appendf(tx, "inner plan:\n%s", in->text.c_str());
+    return SC_OK;
+}
+
 static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_view *sparse,
                                   const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
 {
@@ -747,8 +914,19 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         if (p->frows[0] != p->dims[1] || p->frows[1] != p->dims[2] || p->frows[2] != p->dims[3]) return SC_ERR_SHAPE_MISMATCH;
         p->out_row_elems = p->fcols[0] * p->fcols[1] * p->fcols[2];
         break;
+    case K_TTMC_ALL:
+        if (p->frows[0] != p->dims[0] || p->frows[1] != p->dims[1] || p->frows[2] != p->dims[2]) return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[0] * p->fcols[1] * p->fcols[2];
+        break;
     }
-    p->out_elems = p->dims[0] * p->out_row_elems;
+    p->out_elems = p->kind == K_TTMC_ALL ? p->out_row_elems : p->dims[0] * p->out_row_elems;
+    if (p->kind == K_TTMC_ALL) {
+        st = plan_ttmc_all(p, expr, lhs, rhs, fam, sparse, factors, sched);
+        if (st != SC_OK) return st;
+        guard.p = nullptr;
+        *out = p;
+        return SC_OK;
+    }
 
     // ---- schedule ----
     if (sched->kind != SC_SCHED_LINEAR && sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
@@ -870,6 +1048,7 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         place(1, p->nfib[1], p->fcols[1] * p->fcols[2]);
         break;
     }
+    case K_TTMC_ALL: break;   // planned by plan_ttmc_all
     }
     if (linear) {   // every stored entry times every combination of the dense output indices (and of k for the SDDMM)
         const double per = p->kind == K_SDDMM_SPMM ? 4.0 * (double)p->fcols[0] : (double)(p->nfactors + 1);
@@ -928,6 +1107,7 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
                 p->inter[1].name.c_str(), p->inter[0].name.c_str(), p->inter[1].name.c_str(),
                 p->sched == SC_SCHED_FUSED ? "both per tile in LDS" : "both in the workspace");
         break;
+    case K_TTMC_ALL: break;
     }
     for (int t = 0; t < p->n_inter; ++t)
         appendf(tx, "temporary %d: %s, %lld x %lld, position-compressed along the sparse prefix%s\n", t, p->inter[t].name.c_str(),
@@ -1040,7 +1220,12 @@ extern "C" sc_status sc_plan_model(const sc_plan *plan, double *flops, double *b
 extern "C" sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, size_t *offset_bytes, int64_t *rows, int64_t *cols)
 {
     if (!plan) return SC_ERR_NULL;
-    if (plan->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    if (plan->kind == sck::K_TTMC_ALL) {
+        // the per-slice tiles always pass through the workspace; t(i,j,n) only when the sparse part is FISSIONED
+        if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
+        const bool is_t = plan->k5_variant != 3 && index == 0;
+        if (is_t && plan->inner->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    } else if (plan->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
     if (offset_bytes) *offset_bytes = plan->inter[index].offset;
     if (rows) *rows = plan->inter[index].rows;
@@ -1051,6 +1236,7 @@ extern "C" sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, si
 extern "C" sc_status sc_plan_tile_count(const sc_plan *plan, int64_t *count)
 {
     if (!plan || !count) return SC_ERR_NULL;
+    if (plan->inner) plan = plan->inner;
     *count = (int64_t)plan->tiles.size();
     return SC_OK;
 }
@@ -1058,6 +1244,7 @@ extern "C" sc_status sc_plan_tile_count(const sc_plan *plan, int64_t *count)
 extern "C" sc_status sc_plan_tile(const sc_plan *plan, int64_t index, int32_t rec[9])
 {
     if (!plan || !rec) return SC_ERR_NULL;
+    if (plan->inner) plan = plan->inner;
     if (index < 0 || index >= (int64_t)plan->tiles.size()) return SC_ERR_BAD_DIMS;
     memcpy(rec, &plan->tiles[(size_t)index], 9 * sizeof(int32_t));
     return SC_OK;
@@ -1134,6 +1321,7 @@ extern "C" sc_status sc_plan_set_profiling(sc_plan *plan, int32_t on)
         plan->prof->on = on != 0;
         plan->prof->n_launch = 0;
     }
+    if (plan->inner) plan->inner->prof = plan->prof;   // the inner plan's launches are timed into the same record
     return SC_OK;
 }
 
@@ -1160,6 +1348,10 @@ extern "C" sc_status sc_plan_kernel_time(const sc_plan *plan, int32_t index, cha
 extern "C" sc_status sc_plan_destroy(sc_plan *plan)
 {
     if (!plan) return SC_OK;
+    if (plan->inner) {
+        plan->inner->prof = nullptr;   // shared with this plan, freed below
+        (void)sc_plan_destroy(plan->inner);
+    }
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
     if (plan->d_slot_b) (void)hipFree(plan->d_slot_b);
     for (sck::FixLevel *lv : {&plan->det_top, &plan->det_a, &plan->det_b}) {

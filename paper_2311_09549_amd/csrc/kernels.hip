@@ -759,6 +759,7 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
     }
     case K_SDDMM_SPMM: return order2_caps(dtype, fcols);
     case K_TTMC4: return order4_caps(dtype, fcols);
+    case K_TTMC_ALL: break;   // tiles belong to its inner plan
     }
     return c;
 }
@@ -843,7 +844,7 @@ size_t lds_bytes_needed(const sc_plan *p)
 sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
     if (p->prof && p->prof->on) p->prof->n_launch = 0;
-    if (p->sched == SC_SCHED_LINEAR) return launch_linear(p, sp, fac, out, stream);
+    if (p->sched == SC_SCHED_LINEAR && p->kind != K_TTMC_ALL) return launch_linear(p, sp, fac, out, stream);
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:
@@ -851,6 +852,7 @@ sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vi
                                   : dispatch_order3<float>(p, sp, fac, out, ws, stream);
     case K_SDDMM_SPMM: return launch_order2(p, sp, fac, out, ws, stream);
     case K_TTMC4: return launch_order4(p, sp, fac, out, ws, stream);
+    case K_TTMC_ALL: return launch_ttmc_all(p, sp, fac, out, ws, stream);
     default: return SC_ERR_SCHED_UNSUPPORTED;
 
     }

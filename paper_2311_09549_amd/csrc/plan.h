@@ -12,7 +12,7 @@
 
 namespace sck {
 
-enum Kind { K_TTMC3 = 0, K_MTTKRP3 = 1, K_SDDMM_SPMM = 2, K_TTMC4 = 3 };
+enum Kind { K_TTMC3 = 0, K_MTTKRP3 = 1, K_SDDMM_SPMM = 2, K_TTMC4 = 3, K_TTMC_ALL = 4 };
 
 // One work tile: a contiguous range of leaves (stored nonzeros) together with the range
 // of CSF nodes that contain them at every level above.  Level "a" is the parent level of
@@ -136,6 +136,16 @@ struct sc_plan {
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 
+    // All-mode TTMC (kernel 5 of Table 2): the sparse part runs as an inner plan of the order-3 chain
+    // S(i,m,n) = B(i,j,k) D(j,m) E(k,n) over the same tensor; the contraction with C(i,l) is a grid-wide
+    // reduction through per-workgroup slots of the workspace.
+    sc_plan *inner = nullptr;          // owned
+    int32_t k5_variant = 0;            // which schedule of Table 2: 1, 2 or 3
+    size_t k5_s_offset = 0;            // S, dims[0] x (M N) (variants 2, 3)
+    size_t k5_inner_ws_offset = 0;     // workspace of the inner plan
+    size_t k5_partials_offset = 0;     // k5_nchunks x L x (M N)
+    int64_t k5_nchunks = 0, k5_chunk = 0;
+
     // Snapshot of the tuning knobs and of the device the plan was made on (taken once, at plan
     // creation): an execution reads only these, never process-global state.
     sck::Tuning tune;
@@ -184,6 +194,8 @@ size_t linear_lds_bytes(const sc_plan *plan);
 sc_status launch_linear(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, hipStream_t stream);
 sc_status launch_order2(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,
                         hipStream_t stream);
+sc_status launch_ttmc_all(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,
+                          hipStream_t stream);
 TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols);
 size_t order4_lds_bytes_needed(const sc_plan *plan);
 sc_status launch_order4(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,

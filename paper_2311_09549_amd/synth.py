@@ -32,6 +32,7 @@ KINDS = {
     "mttkrp3": ("A(i,r)=B(i,j,k)*C(j,r)*D(k,r)", 3, 2),
     "sddmm_spmm": ("A(i,l)=S(i,j)*X(i,k)*Y(j,k)*Z(j,l)", 2, 3),
     "ttmc4": ("A(i,l,m,n)=B(i,j,k,p)*C(j,l)*D(k,m)*E(p,n)", 4, 3),
+    "ttmc_all": ("A(l,m,n)=B(i,j,k)*C(i,l)*D(j,m)*E(k,n)", 3, 3),
 }
 
 CONFIGS = {
@@ -45,6 +46,11 @@ CONFIGS = {
             coord=(("zipf", 1.3), "uniform"), ranks=(64, 64), factor_dist="normal"),
     5: dict(kind="ttmc4", dtype="f32", dims=(10_000,) * 4, nnz=50_000_000,
             coord=(("zipf", 1.1),) * 4, ranks=(8, 8, 8), factor_dist="normal"),
+    # Not one of the five benchmark workloads: the all-mode TTMC (Table 2, kernel 5) at the first dense
+    # sizes of the paper's auxiliary-memory table (L = M = N = 16), on a power-law tensor of the same
+    # recipe as workload 3 at a size whose unfactored oracle nest still runs in seconds.
+    6: dict(kind="ttmc_all", dtype="f32", dims=(40_000, 20_000, 8_000), nnz=4_000_000,
+            coord=(("zipf", 1.1),) * 3, ranks=(16, 16, 16), factor_dist="normal"),
 }
 
 
@@ -153,6 +159,8 @@ def factor_shapes(cfg: dict):
         return [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1])]
     if kind == "ttmc4":
         return [(dims[1], ranks[0]), (dims[2], ranks[1]), (dims[3], ranks[2])]
+    if kind == "ttmc_all":
+        return [(dims[0], ranks[0]), (dims[1], ranks[1]), (dims[2], ranks[2])]
     raise ValueError(kind)
 
 
@@ -166,6 +174,8 @@ def output_shape(cfg: dict):
         return (dims[0], ranks[1])
     if kind == "ttmc4":
         return (dims[0], ranks[0], ranks[1], ranks[2])
+    if kind == "ttmc_all":
+        return (ranks[0], ranks[1], ranks[2])
     raise ValueError(kind)
 
 

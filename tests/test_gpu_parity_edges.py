@@ -1,7 +1,7 @@
 """GPU parity on the degenerate structures of the method: nothing stored, a single entry, all
 entries in one slice / one fiber (a node cut by many tiles at every level), fibers of one entry
 only, entry counts that land exactly on, just below and just above tile multiples, stored zeros,
-coordinates at both ends of every mode.  Both schedules, all four nests, element-wise against the
+coordinates at both ends of every mode.  Both schedules, all five nests, element-wise against the
 oracle (same bar as the other parity tests)."""
 import numpy as np
 import pytest
@@ -12,7 +12,7 @@ from helpers import assert_parity, run_library
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"mttkrp3": 2, "ttmc3": 3, "sddmm_spmm": 4, "ttmc4": 5}   # kind -> workload whose expression and ranks it borrows
+KINDS = {"mttkrp3": 2, "ttmc3": 3, "sddmm_spmm": 4, "ttmc4": 5, "ttmc_all": 6}   # kind -> workload whose expression and ranks it borrows
 
 
 def _sorted_unique(cols, dims):

@@ -423,3 +423,39 @@ def test_linear_plan_counts_the_unfactored_nest(cid, scale):
     assert "LINEAR" in text and "temporary 0" not in text
     fused = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
     assert sc.plan_model(fused)[0] < want or cfg["dims"][0] < 300
+
+
+def test_all_mode_ttmc_plans():
+    """Kernel 5 of Table 2: classification, the three schedules picked by naming their temporaries, the
+    iteration counts of their nests (the same closed forms the counted twins reproduce), refusals."""
+    cfg = synth.config(6, 0.005)
+    data = synth.generate(cfg)
+    csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
+    nnz, S, F = csf.nnz, csf.nfib[0], csf.nfib[1]
+    L, M, N = cfg["ranks"]
+    want = {1: 2 * N * nnz + 3 * L * M * N * F, 2: 2 * N * nnz + 2 * M * N * F + 2 * L * M * N * S, 3: 3 * M * N * nnz + 2 * L * M * N * S}
+    cases = [("fused", [], 2), ("fissioned", [], 2), ("fused", ["T2(i,m,n)", "T1(i,j,n)"], 2), ("fissioned", ["T(i,j,n)"], 1),
+             ("fused", ["T(i,m,n)"], 3), ("fused", ["Q(n,m,i)"], 3)]
+    for which, names, variant in cases:
+        plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule(which, names, [0] * len(names)))
+        text = sc.plan_describe(plan)
+        assert f"kernel 5, schedule {variant}" in text, text
+        assert sc.plan_model(plan)[0] == want[variant]
+        ws = sc.plan_workspace_bytes(plan)
+        tiles_elems = cfg["dims"][0] * M * N * 4
+        assert ws >= (F * N * 4 if variant == 1 else tiles_elems)
+        assert sc.plan_tile_count(plan) > 0
+    # index names are free; a factor per mode in any order
+    plan = sc.plan_create("Out(a,b,c)=X(p,q,r)*W(r,c)*U(p,a)*V(q,b)", csf, [data["factors"][2], data["factors"][0], data["factors"][1]],
+                          sc.schedule("fused"))
+    assert "kernel 5, schedule 2" in sc.plan_describe(plan)
+    bad = [("linear", []), ("fused", ["T(i,j,n)"]), ("fissioned", ["T(i,m,n)"]), ("fused", ["T(i,j,m)"]), ("fused", ["T(i,j,n)", "T(i,j,n)"])]
+    for which, names in bad:
+        assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, names, [0] * len(names))) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused", ["T(i,m,n)"], [0], deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    # not in the family: an output index that is a sparse index but not the first, or two factors on one mode
+    for expr in ("A(l,j,n)=B(i,j,k)*C(i,l)*D(j,m)*E(k,n)", "A(l,m,n)=B(i,j,k)*C(i,l)*D(i,m)*E(k,n)", "A(m,l,n)=B(i,j,k)*C(i,l)*D(j,m)*E(k,n)"):
+        assert _status(sc.plan_create, expr, csf, data["factors"], sc.schedule("fused")) == "SC_ERR_EXPR_UNSUPPORTED"
+    # shapes: the factor on mode 0 has one row per coordinate of mode 0
+    wrong = [data["factors"][1], data["factors"][1], data["factors"][2]]
+    assert _status(sc.plan_create, cfg["expr"], csf, wrong, sc.schedule("fused")) == "SC_ERR_SHAPE_MISMATCH"
