@@ -66,8 +66,14 @@ typedef enum { SC_F32 = 0, SC_F64 = 1 } sc_dtype;
  * temporary, no workspace, sums combined with atomics (deterministic must be 0);
  * FISSIONED = producer and consumer split, the temporary fully materialised (in the
  * workspace, in HBM); FUSED = producer and consumer fused under their common outer
- * loops, the live temporary kept on chip (registers / LDS). */
-typedef enum { SC_SCHED_LINEAR = 0, SC_SCHED_FUSED = 1, SC_SCHED_FISSIONED = 2 } sc_sched_kind;
+ * loops, the live temporary kept on chip (registers / LDS);
+ * AUTO = the library picks: it evaluates the cost expressions of the candidate schedules it has kernels
+ * for (iteration count and memory traffic, with the concrete node counts and ranks of the operands)
+ * and takes the one of least predicted time among those whose on-chip temporary leaves room for at
+ * least two workgroups per compute unit -- the run-time stage of Section 5, with "auxiliary memory
+ * below half of the last-level cache" read as "below half of a compute unit's LDS".  sc_plan_chosen
+ * and sc_plan_describe report the decision. */
+typedef enum { SC_SCHED_LINEAR = 0, SC_SCHED_FUSED = 1, SC_SCHED_FISSIONED = 2, SC_SCHED_AUTO = 3 } sc_sched_kind;
 
 typedef struct sc_plan sc_plan;
 
@@ -116,10 +122,13 @@ typedef struct {
  *   intermediate[t]  optional text such as "T(i,j,m)" or "T1(i,j,k,n)"; when given, its
  *                    index set must equal the one Section 4.2 derives (indices of the
  *                    producer that also occur in the consumer or the output).
- *   fuse_depth[t]    FISSIONED: must be 0.  FUSED: 0 = library's choice, otherwise
- *                    1..(order-1): how many sparse loops producer and consumer share.
- *                    All FUSED depths compute the same result; sc_plan_describe reports
- *                    the on-chip granularity actually used.
+ *   fuse_depth[t]    how many leading sparse loops producer and consumer share (the fused prefix of
+ *                    Section 4.2).  FISSIONED and AUTO: must be 0.  FUSED: 0 = the depth the library's
+ *                    kernel for this expression is built at, or that depth itself (order-3 and order-4
+ *                    TTM chains 1: the temporaries of a chunk of a slice in LDS; MTTKRP and the
+ *                    SDDMM -> SpMM pair 2: the temporary of one fiber / one stored entry in
+ *                    registers); any other value returns SC_ERR_SCHED_UNSUPPORTED rather than being
+ *                    ignored.  sc_plan_describe reports the on-chip granularity.
  *   deterministic    0: partial sums of rows that span work tiles are combined with
  *                    floating-point atomics (order may vary from run to run).
  *                    1: every tile stores its piece of such a row in the workspace and a last
@@ -176,6 +185,11 @@ sc_status sc_plan_workspace_bytes(const sc_plan *plan, size_t *bytes);
  * the temporaries with their shapes, the flop and compulsory-byte model, tile counts.
  * Always NUL-terminates; truncates to n-1 characters. */
 sc_status sc_plan_describe(const sc_plan *plan, char *buf, size_t n);
+
+/* What the plan runs: the schedule class (never SC_SCHED_AUTO: the class the evaluator settled on
+ * when AUTO was asked for) and, for the all-mode TTMC, which of the three schedules of Table 2,
+ * kernel 5 (1..3; 0 for the other expressions).  Either pointer may be NULL. */
+sc_status sc_plan_chosen(const sc_plan *plan, sc_sched_kind *kind, int32_t *table2_schedule);
 
 /* Model figures of the planned schedule: flops (multiply = 1, add = 1) and compulsory HBM
  * bytes (every input array and the output touched once; temporaries of a FISSIONED

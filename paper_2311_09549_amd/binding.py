@@ -20,7 +20,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsparsecontract.so")
 
 SC_F32, SC_F64 = 0, 1
-SC_SCHED_LINEAR, SC_SCHED_FUSED, SC_SCHED_FISSIONED = 0, 1, 2
+SC_SCHED_LINEAR, SC_SCHED_FUSED, SC_SCHED_FISSIONED, SC_SCHED_AUTO = 0, 1, 2, 3
 
 STATUS_NAMES = [
     "SC_OK", "SC_ERR_NULL", "SC_ERR_BAD_ORDER", "SC_ERR_BAD_DTYPE", "SC_ERR_BAD_DIMS", "SC_ERR_BAD_POS",
@@ -33,7 +33,7 @@ EXPORTS = [
     "sc_version", "sc_status_string", "sc_coo_to_csf_sizes", "sc_coo_to_csf", "sc_plan_create",
     "sc_plan_workspace_bytes", "sc_plan_describe", "sc_plan_model", "sc_plan_intermediate", "sc_execute",
     "sc_plan_set_profiling", "sc_plan_kernel_count", "sc_plan_kernel_time", "sc_plan_tile_count", "sc_plan_tile",
-    "sc_tuning_set", "sc_stream_copy", "sc_plan_destroy", "sc_execute_static",
+    "sc_tuning_set", "sc_stream_copy", "sc_plan_destroy", "sc_execute_static", "sc_plan_chosen",
 ]
 
 _c_i32p = ctypes.POINTER(ctypes.c_int32)
@@ -220,7 +220,7 @@ def dense_view(x, dtype=None, rows=None, cols=None, ld=None) -> DenseView:
 
 def schedule(kind, intermediates=(), fuse_depth=(), deterministic=False) -> Schedule:
     s = Schedule()
-    s.kind = {"linear": SC_SCHED_LINEAR, "fused": SC_SCHED_FUSED, "fissioned": SC_SCHED_FISSIONED}.get(kind, kind)
+    s.kind = {"linear": SC_SCHED_LINEAR, "fused": SC_SCHED_FUSED, "fissioned": SC_SCHED_FISSIONED, "auto": SC_SCHED_AUTO}.get(kind, kind)
     s.n_intermediates = len(intermediates)
     for t, name in enumerate(list(intermediates)[:2]):
         s.intermediate[t] = name.encode() if name is not None else None
@@ -271,6 +271,13 @@ def plan_describe(plan: Plan) -> str:
     buf = ctypes.create_string_buffer(4096)
     _check(lib().sc_plan_describe(plan.handle, buf, ctypes.c_size_t(len(buf))), "sc_plan_describe")
     return buf.value.decode()
+
+
+def plan_chosen(plan: Plan):
+    """(schedule class name, schedule of Table 2 kernel 5 or 0) the plan runs."""
+    kind, variant = ctypes.c_int(), ctypes.c_int32()
+    _check(lib().sc_plan_chosen(plan.handle, ctypes.byref(kind), ctypes.byref(variant)), "sc_plan_chosen")
+    return ["linear", "fused", "fissioned", "auto"][kind.value], int(variant.value)
 
 
 def plan_model(plan: Plan):

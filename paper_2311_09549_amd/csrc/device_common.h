@@ -136,17 +136,6 @@ inline bool rank_ok(int64_t w, sc_dtype dt)
     return lg >= 1 && lg <= 64 && (lg & (lg - 1)) == 0;
 }
 
-// Workgroups using `lds` bytes of LDS each that one compute unit holds at a time: the unit's LDS
-// (160 KB on MI355X) is handed out in units of 1280 bytes (measured: a fifth workgroup of 31,880
-// bytes fits, one of 32,232 does not).  The kernels here are bound by latency, and their time
-// falls almost in proportion to this number, so tile sizes are chosen to land just below a step.
-inline int lds_workgroups_per_cu(size_t lds, int64_t lds_per_cu = 160 * 1024)
-{
-    const size_t unit = 1280;
-    const size_t need = std::max<size_t>(unit, (lds + unit - 1) / unit * unit);
-    return (int)std::max<size_t>(1, std::min<size_t>(8, (size_t)lds_per_cu / need));
-}
-
 struct Launcher {
     const sc_plan *plan;
     hipStream_t stream;

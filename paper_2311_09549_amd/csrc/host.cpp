@@ -705,6 +705,136 @@ extern "C" sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out)
     return guarded([&] { return coo_to_csf_impl(coo, out); });
 }
 
+// Iteration count (multiply = 1, add = 1) and compulsory HBM bytes of one schedule class of an expression,
+// from the concrete node counts and ranks (the cost expressions of Section 3, evaluated as in the run-time
+// stage of Section 5).  `extra` = bytes a FISSIONED schedule adds by writing and reading its temporaries.
+static void schedule_model(const sc_plan *p, sc_sched_kind sched, double *flops_out, double *bytes_out)
+{
+    const double e = (double)esize(p->dtype), nnz = (double)p->nnz, S = (double)p->nfib[0];
+    double fac_bytes = 0;
+    for (int s = 0; s < p->nfactors; ++s) fac_bytes += (double)p->frows[s] * (double)p->fcols[s] * e;
+    double flops = 0, bytes = 0, extra = 0;
+    switch (p->kind) {
+    case K_TTMC3: {
+        const double F = (double)p->nfib[1], L = (double)p->fcols[0], M = (double)p->fcols[1];
+        flops = 2 * M * nnz + 2 * L * M * F;
+        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F * M * e;
+        break;
+    }
+    case K_MTTKRP3: {
+        const double F = (double)p->nfib[1], R = (double)p->fcols[0];
+        flops = 2 * R * (nnz + F);
+        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F * R * e;
+        break;
+    }
+    case K_SDDMM_SPMM: {
+        const double K = (double)p->fcols[0], L = (double)p->fcols[2];
+        flops = nnz * (2 * K + 1 + 2 * L);
+        // every array touched once (perfect reuse of the gathered rows)
+        bytes = nnz * (4 + e) + S * 8 + S * K * e + (double)p->frows[1] * (K + L) * e + (double)p->out_elems * e;
+        extra = 2 * nnz * e;
+        break;
+    }
+    case K_TTMC4: {
+        const double F2 = (double)p->nfib[1], F3 = (double)p->nfib[2];
+        const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
+        flops = 2 * N * nnz + 2 * M * N * F3 + 2 * L * M * N * F2;
+        bytes = nnz * (4 + e) + F3 * 8 + F2 * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
+        extra = 2 * F3 * N * e + 2 * F2 * M * N * e;
+        break;
+    }
+    case K_TTMC_ALL: break;   // see plan_ttmc_all
+    }
+    if (sched == SC_SCHED_LINEAR) {   // every stored entry times every combination of the dense output indices (and of k for the SDDMM)
+        const double per = p->kind == K_SDDMM_SPMM ? 4.0 * (double)p->fcols[0] : (double)(p->nfactors + 1);
+        flops = per * (double)p->out_row_elems * nnz;
+    }
+    if (sched == SC_SCHED_FISSIONED) bytes += extra;
+    *flops_out = flops;
+    *bytes_out = bytes;
+}
+
+// Run-time stage of the scheduler (Section 5, "Time-Complexity-Based Pruning"), for the schedule classes this
+// library has kernels for.  The paper keeps the schedules of least iteration count whose auxiliary memory is
+// below half of the last-level cache; on this machine the temporary of a fused nest lives in LDS, so a class is
+// admissible when kernels exist for the ranks and a workgroup's on-chip buffers leave room for a second
+// workgroup on the compute unit.  Among the admissible classes the least predicted time wins, time being
+// the larger of iteration count / vector peak and compulsory bytes / HBM peak (ties: fewer bytes first).
+struct Candidate {
+    sc_sched_kind kind;
+    int variant;          // kernel 5 only: schedule of Table 2
+    double flops, bytes, seconds;
+    size_t lds;
+    int wg_per_cu;
+    bool available, admissible;
+};
+
+static double predicted_seconds(const sc_plan *p, double flops, double bytes)
+{
+    const double peak_flops = (double)p->n_cu * 64.0 * 2.0 * 2.4e9;   // one fused multiply-add per lane and clock
+    const double peak_bytes = 8.0e12 * (double)p->n_cu / 256.0;
+    return std::max(flops / peak_flops, bytes / peak_bytes);
+}
+
+static const char *sched_name(sc_sched_kind k)
+{
+    return k == SC_SCHED_LINEAR ? "LINEAR" : k == SC_SCHED_FUSED ? "FUSED" : k == SC_SCHED_FISSIONED ? "FISSIONED" : "AUTO";
+}
+
+// Availability and on-chip footprint of one schedule class of an order-2/3/4 contraction.
+static void probe_class(const sc_plan *p, sc_sched_kind kind, bool deterministic, Candidate &c)
+{
+    sc_plan q;
+    q.kind = p->kind; q.dtype = p->dtype; q.order = p->order; q.nnz = p->nnz; q.nfactors = p->nfactors;
+    for (int m = 0; m < 4; ++m) { q.dims[m] = p->dims[m]; q.nfib[m] = p->nfib[m]; }
+    for (int s = 0; s < 3; ++s) { q.frows[s] = p->frows[s]; q.fcols[s] = p->fcols[s]; }
+    q.out_elems = p->out_elems; q.out_row_elems = p->out_row_elems;
+    q.sched = kind;
+    q.deterministic = deterministic;
+    q.caps = kind == SC_SCHED_LINEAR ? TileCaps{1024, 1024, 1024} : default_caps(q.kind, q.dtype, kind, q.fcols);
+    c.kind = kind;
+    c.variant = 0;
+    c.available = q.caps.tn > 0 && !(deterministic && (kind == SC_SCHED_LINEAR || !plan_supports_deterministic(&q)));
+    c.lds = c.available ? lds_bytes_needed(&q) : 0;
+    if (c.lds > 64 * 1024) c.available = false;
+    c.wg_per_cu = c.available ? lds_workgroups_per_cu(c.lds, p->lds_per_cu) : 0;
+    c.admissible = c.available && c.wg_per_cu >= 2;
+}
+
+static void describe_candidates(std::string &tx, const std::vector<Candidate> &cands, size_t best)
+{
+    appendf(tx, "cost evaluator (run-time stage of Section 5): predicted time = max(iterations / vector peak, compulsory bytes / HBM peak); "
+                "admissible = kernels exist and a workgroup's on-chip buffers leave room for a second one per compute unit\n");
+    for (size_t n = 0; n < cands.size(); ++n) {
+        const Candidate &c = cands[n];
+        if (c.variant) appendf(tx, "  candidate Table 2 schedule %d, %s:", c.variant, sched_name(c.kind));
+        else appendf(tx, "  candidate %s:", sched_name(c.kind));
+        if (!c.available) {
+            appendf(tx, " no kernel for these ranks / options\n");
+            continue;
+        }
+        appendf(tx, " %.4g flops, %.4g bytes, %zu bytes of LDS per workgroup (%d per compute unit), predicted %.1f us%s%s\n", c.flops, c.bytes,
+                c.lds, c.wg_per_cu, c.seconds * 1e6, c.admissible ? "" : ", not admissible", n == best ? "  <- chosen" : "");
+    }
+}
+
+static size_t pick_candidate(const std::vector<Candidate> &cands)
+{
+    size_t best = cands.size();
+    for (size_t n = 0; n < cands.size(); ++n) {
+        if (!cands[n].admissible) continue;
+        if (best == cands.size() || cands[n].seconds < cands[best].seconds ||
+            (cands[n].seconds == cands[best].seconds && cands[n].bytes < cands[best].bytes))
+            best = n;
+    }
+    if (best == cands.size())   // nothing admissible: fall back to whatever has a kernel
+        for (size_t n = 0; n < cands.size() && best == cands.size(); ++n)
+            if (cands[n].available) best = n;
+    return best;
+}
+
 static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_view *sparse, const sc_dense_view *factors,
                                   int32_t nfactors, const sc_schedule *sched);
 
@@ -714,12 +844,55 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
 static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, const std::vector<Term> &rhs, const Family &fam,
                                const sc_csf_view *sparse, const sc_dense_view *factors, const sc_schedule *sched)
 {
-    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;   // no unfactored nest for this kernel
     if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
+    sc_schedule picked = {};
+    std::string choice_text;
+    int auto_variant = 0;
+    if (sched->kind == SC_SCHED_AUTO) {
+        // candidates: the three schedules of Table 2 in the classes the library runs them in.  Their iteration counts
+        // differ (N nnz + L M N F, N nnz + M N F + L M N S, M N nnz + L M N S); so do the bytes the sparse part moves.
+        if (sched->n_intermediates != 0) return SC_ERR_SCHED_UNSUPPORTED;
+        const double e = (double)esize(p->dtype), nnz = (double)p->nnz, S = (double)p->nfib[0], F = (double)p->nfib[1];
+        const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
+        double fb = 0;
+        for (int s = 0; s < 3; ++s) fb += (double)p->frows[s] * (double)p->fcols[s] * e;
+        const double base = nnz * (4 + e) + F * 8 + S * 8 + fb + (double)p->out_elems * e;
+        const double tiles = 2 * (double)p->dims[0] * M * N * e, trows = 2 * F * N * e;
+        sc_plan inner;   // the order-3 chain over modes 1 and 2, for availability and LDS footprint
+        inner.kind = K_TTMC3; inner.dtype = p->dtype; inner.order = 3; inner.nnz = p->nnz; inner.nfactors = 2;
+        for (int m = 0; m < 4; ++m) { inner.dims[m] = p->dims[m]; inner.nfib[m] = p->nfib[m]; }
+        inner.frows[0] = p->frows[1]; inner.frows[1] = p->frows[2]; inner.fcols[0] = p->fcols[1]; inner.fcols[1] = p->fcols[2];
+        inner.out_row_elems = p->fcols[1] * p->fcols[2];
+        inner.out_elems = p->dims[0] * inner.out_row_elems;
+        inner.n_cu = p->n_cu; inner.lds_per_cu = p->lds_per_cu;
+        struct { int variant; sc_sched_kind outer, inner; double flops, bytes; } opt[4] = {
+            {2, SC_SCHED_FUSED, SC_SCHED_FUSED, 2 * N * nnz + 2 * M * N * F + 2 * L * M * N * S, base + tiles},
+            {2, SC_SCHED_FISSIONED, SC_SCHED_FISSIONED, 2 * N * nnz + 2 * M * N * F + 2 * L * M * N * S, base + tiles + trows},
+            {1, SC_SCHED_FISSIONED, SC_SCHED_FISSIONED, 2 * N * nnz + 3 * L * M * N * F, base + trows},
+            {3, SC_SCHED_FUSED, SC_SCHED_LINEAR, 3 * M * N * nnz + 2 * L * M * N * S, base + tiles}};
+        std::vector<Candidate> cands(4);
+        for (int n = 0; n < 4; ++n) {
+            probe_class(&inner, opt[n].inner, sched->deterministic == 1 && opt[n].variant != 3, cands[n]);
+            if (opt[n].variant == 3 && sched->deterministic == 1) cands[n].available = cands[n].admissible = false;
+            cands[n].kind = opt[n].outer;
+            cands[n].variant = opt[n].variant;
+            cands[n].flops = opt[n].flops;
+            cands[n].bytes = opt[n].bytes;
+            cands[n].seconds = predicted_seconds(p, opt[n].flops, opt[n].bytes);
+        }
+        const size_t best = pick_candidate(cands);
+        if (best == cands.size()) return SC_ERR_SCHED_UNSUPPORTED;
+        describe_candidates(choice_text, cands, best);
+        picked.kind = cands[best].kind;
+        picked.deterministic = sched->deterministic;
+        auto_variant = cands[best].variant;
+        sched = &picked;
+    }
+    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;   // no unfactored nest for this kernel
     p->sched = sched->kind;
     p->deterministic = sched->deterministic == 1;
     // which schedule: match the named temporaries against the derived index sets
-    int variant = 2;
+    int variant = auto_variant ? auto_variant : 2;
     if (sched->n_intermediates < 0 || sched->n_intermediates > 2) return SC_ERR_SCHED_UNSUPPORTED;
     if (sched->n_intermediates) {
         bool has[2] = {false, false};
@@ -772,7 +945,7 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     // reduction over slices (fibers for schedule 1): contiguous chunks, one slot each
     const int64_t units = variant == 1 ? p->nfib[1] : p->dims[0];
     const int64_t per = variant == 1 ? 1024 : 64;
-    p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>((units + per - 1) / per, (int64_t)p->n_cu * 4));
+    p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>((units + per - 1) / per, (int64_t)p->n_cu * 2));
     p->k5_chunk = std::max<int64_t>(1, (units + p->k5_nchunks - 1) / p->k5_nchunks);
     p->k5_nchunks = std::max<int64_t>(1, (units + p->k5_chunk - 1) / p->k5_chunk);
     size_t off = 0;
@@ -823,6 +996,7 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     const char *l_ = lhs.idx[0].c_str(), *m_ = lhs.idx[1].c_str(), *n_ = lhs.idx[2].c_str();
     appendf(tx, "schedule: Table 2, kernel 5, schedule %d (%s)\n", variant,
             p->sched == SC_SCHED_FUSED ? "FUSED: the temporaries of the sparse part stay on chip" : "FISSIONED: t in the workspace");
+    tx += choice_text;
     if (variant == 1)
         appendf(tx, "nest: forall(%s,%s',%s, where(forall(%s,%s, A += t * %s * %s), forall(%s', t += %s * %s)))\n", i_, j_, n_, m_, l_, Cn, Dn, k_,
                 rhs[0].name.c_str(), En);
@@ -919,6 +1093,18 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         p->out_row_elems = p->fcols[0] * p->fcols[1] * p->fcols[2];
         break;
     }
+    p->tune = tuning();   // read once; executions use the plan's copy
+    {
+        int ndev0 = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDeviceCount(&ndev0) == hipSuccess && ndev0 > 0 && hipGetDevice(&dev) == hipSuccess &&
+            hipGetDeviceProperties(&prop, dev) == hipSuccess) {
+            if (prop.multiProcessorCount > 0) p->n_cu = prop.multiProcessorCount;
+            if (prop.maxSharedMemoryPerMultiProcessor >= 64 * 1024) p->lds_per_cu = (int64_t)prop.maxSharedMemoryPerMultiProcessor;
+        } else {
+            (void)hipGetLastError();
+        }
+    }
     p->out_elems = p->kind == K_TTMC_ALL ? p->out_row_elems : p->dims[0] * p->out_row_elems;
     if (p->kind == K_TTMC_ALL) {
         st = plan_ttmc_all(p, expr, lhs, rhs, fam, sparse, factors, sched);
@@ -929,8 +1115,26 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
     }
 
     // ---- schedule ----
-    if (sched->kind != SC_SCHED_LINEAR && sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
+    sc_schedule picked = {};
+    std::string choice_text;
+    if (sched->kind == SC_SCHED_AUTO) {
+        if (sched->n_intermediates != 0) return SC_ERR_SCHED_UNSUPPORTED;   // AUTO derives the temporaries itself
+        std::vector<Candidate> cands(3);
+        const sc_sched_kind classes[3] = {SC_SCHED_FUSED, SC_SCHED_FISSIONED, SC_SCHED_LINEAR};
+        for (int n = 0; n < 3; ++n) {
+            probe_class(p, classes[n], sched->deterministic == 1, cands[n]);
+            schedule_model(p, classes[n], &cands[n].flops, &cands[n].bytes);
+            cands[n].seconds = predicted_seconds(p, cands[n].flops, cands[n].bytes);
+        }
+        const size_t best = pick_candidate(cands);
+        if (best == cands.size()) return SC_ERR_SCHED_UNSUPPORTED;
+        describe_candidates(choice_text, cands, best);
+        picked.kind = cands[best].kind;
+        picked.deterministic = sched->deterministic;
+        sched = &picked;
+    }
+    if (sched->kind != SC_SCHED_LINEAR && sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     p->deterministic = sched->deterministic == 1;
     p->sched = sched->kind;
     const bool linear = sched->kind == SC_SCHED_LINEAR;
@@ -942,7 +1146,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         p->inter[t].name = join(fam.temp_name[t], fam.temp_idx[t]);
         const int fd = sched->n_intermediates ? sched->fuse_depth[t] : 0;
         if (sched->kind == SC_SCHED_FISSIONED && fd != 0) return SC_ERR_SCHED_UNSUPPORTED;
-        if (sched->kind == SC_SCHED_FUSED && (fd < 0 || fd > p->order - 1)) return SC_ERR_SCHED_UNSUPPORTED;
+        // the depth the FUSED kernel of this expression is built at (0 = that depth); nothing else is offered
+        const int built = (p->kind == K_MTTKRP3 || p->kind == K_SDDMM_SPMM) ? 2 : 1;
+        if (sched->kind == SC_SCHED_FUSED && fd != 0 && fd != built) return SC_ERR_SCHED_UNSUPPORTED;
         p->fuse_depth[t] = fd;
     }
     if (sched->n_intermediates) {
@@ -971,18 +1177,6 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
     p->caps = linear ? TileCaps{1024, 1024, 1024}   // node caps that never bind: the kernel keeps no per-node state
                      : default_caps(p->kind, p->dtype, p->sched, p->fcols);
     if (p->caps.tn <= 0) return SC_ERR_SCHED_UNSUPPORTED;  // no kernel instantiated for these ranks
-    p->tune = tuning();   // read once; executions use the plan's copy
-    {
-        int ndev0 = 0, dev = 0;
-        hipDeviceProp_t prop;
-        if (hipGetDeviceCount(&ndev0) == hipSuccess && ndev0 > 0 && hipGetDevice(&dev) == hipSuccess &&
-            hipGetDeviceProperties(&prop, dev) == hipSuccess) {
-            if (prop.multiProcessorCount > 0) p->n_cu = prop.multiProcessorCount;
-            if (prop.maxSharedMemoryPerMultiProcessor >= 64 * 1024) p->lds_per_cu = (int64_t)prop.maxSharedMemoryPerMultiProcessor;
-        } else {
-            (void)hipGetLastError();
-        }
-    }
     const Tuning &tu = p->tune;
     if (tu.tn) p->caps.tn = tu.tn;
     if (tu.ta) p->caps.ta = tu.ta;
@@ -998,11 +1192,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
     } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
 
     // ---- workspace, model, text ----
-    const double e = (double)esize(p->dtype);
-    const double nnz = (double)p->nnz;
     const int d = p->order;
-    const double S = (double)p->nfib[0];
-    double flops = 0, bytes = 0, extra = 0;
+    double flops = 0, bytes = 0;
+    schedule_model(p, p->sched, &flops, &bytes);
     size_t off = 0;
     auto place = [&](int t, int64_t rows, int64_t cols) {
         p->inter[t].rows = rows;
@@ -1010,52 +1202,17 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         p->inter[t].offset = off;
         off += ((size_t)rows * (size_t)cols * esize(p->dtype) + 255) & ~(size_t)255;
     };
-    double fac_bytes = 0;
-    for (int s = 0; s < nfactors; ++s) fac_bytes += (double)p->frows[s] * (double)p->fcols[s] * e;
     switch (p->kind) {
-    case K_TTMC3: {
-        const double F = (double)p->nfib[1], L = (double)p->fcols[0], M = (double)p->fcols[1];
-        flops = 2 * M * nnz + 2 * L * M * F;
-        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
-        extra = 2 * F * M * e;
-        place(0, p->nfib[1], p->fcols[1]);
-        break;
-    }
-    case K_MTTKRP3: {
-        const double F = (double)p->nfib[1], R = (double)p->fcols[0];
-        flops = 2 * R * (nnz + F);
-        bytes = nnz * (4 + e) + F * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
-        extra = 2 * F * R * e;
-        place(0, p->nfib[1], p->fcols[0]);
-        break;
-    }
-    case K_SDDMM_SPMM: {
-        const double K = (double)p->fcols[0], L = (double)p->fcols[2];
-        flops = nnz * (2 * K + 1 + 2 * L);
-        // every array touched once (perfect reuse of the gathered rows)
-        bytes = nnz * (4 + e) + S * 8 + S * K * e + (double)p->frows[1] * (K + L) * e + (double)p->out_elems * e;
-        extra = 2 * nnz * e;
-        place(0, p->nnz, 1);
-        break;
-    }
-    case K_TTMC4: {
-        const double F2 = (double)p->nfib[1], F3 = (double)p->nfib[2];
-        const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
-        flops = 2 * N * nnz + 2 * M * N * F3 + 2 * L * M * N * F2;
-        bytes = nnz * (4 + e) + F3 * 8 + F2 * 8 + S * 8 + fac_bytes + (double)p->out_elems * e;
-        extra = 2 * F3 * N * e + 2 * F2 * M * N * e;
+    case K_TTMC3: place(0, p->nfib[1], p->fcols[1]); break;
+    case K_MTTKRP3: place(0, p->nfib[1], p->fcols[0]); break;
+    case K_SDDMM_SPMM: place(0, p->nnz, 1); break;
+    case K_TTMC4:
         place(0, p->nfib[2], p->fcols[2]);
         place(1, p->nfib[1], p->fcols[1] * p->fcols[2]);
         break;
-    }
     case K_TTMC_ALL: break;   // planned by plan_ttmc_all
     }
-    if (linear) {   // every stored entry times every combination of the dense output indices (and of k for the SDDMM)
-        const double per = p->kind == K_SDDMM_SPMM ? 4.0 * (double)p->fcols[0] : (double)(p->nfactors + 1);
-        flops = per * (double)p->out_row_elems * nnz;
-    }
     if (p->sched == SC_SCHED_FISSIONED) {
-        bytes += extra;
         p->ws_bytes = off;
     } else {
         p->ws_bytes = 0;
@@ -1077,6 +1234,7 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
     appendf(tx, "expression: %s\n", expr);
     appendf(tx, "schedule: %s\n", linear ? "LINEAR (the unfactored nest, no temporary)"
                                   : p->sched == SC_SCHED_FUSED ? "FUSED (temporaries on chip)" : "FISSIONED (temporaries in the workspace)");
+    tx += choice_text;
     const std::vector<std::string> &si = rhs[0].idx;
     if (linear)
         appendf(tx, "nest: forall(entries of %s, forall(dense indices, %s += product of one element of every operand))\n", rhs[0].name.c_str(),
@@ -1206,6 +1364,14 @@ extern "C" sc_status sc_plan_describe(const sc_plan *plan, char *buf, size_t n)
     const size_t k = std::min(n - 1, plan->text.size());
     memcpy(buf, plan->text.data(), k);
     buf[k] = '\0';
+    return SC_OK;
+}
+
+extern "C" sc_status sc_plan_chosen(const sc_plan *plan, sc_sched_kind *kind, int32_t *table2_schedule)
+{
+    if (!plan) return SC_ERR_NULL;
+    if (kind) *kind = plan->sched;
+    if (table2_schedule) *table2_schedule = plan->kind == sck::K_TTMC_ALL ? plan->k5_variant : 0;
     return SC_OK;
 }
 

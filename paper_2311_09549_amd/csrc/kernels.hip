@@ -714,6 +714,7 @@ sc_status dispatch_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dens
     case 16: return run_order3<T, 16>(p, sp, fac, out, ws, stream);
     case 32: return run_order3<T, 32>(p, sp, fac, out, ws, stream);
     case 64: return run_order3<T, 64>(p, sp, fac, out, ws, stream);
+    case 128: return run_order3<T, 128>(p, sp, fac, out, ws, stream);
     default: return SC_ERR_SCHED_UNSUPPORTED;
     }
 }
@@ -730,7 +731,7 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
     case K_TTMC3:
     case K_MTTKRP3: {
         const int64_t w = kind == K_TTMC3 ? fcols[1] : fcols[0];
-        if (!(w == 8 || w == 16 || w == 32 || w == 64) || !rank_ok(w, dtype)) return c;
+        if (!(w == 8 || w == 16 || w == 32 || w == 64 || w == 128) || !rank_ok(w, dtype)) return c;
         c.tn = 1024;
         if (kind == K_MTTKRP3 && sched == SC_SCHED_FUSED) {
             // fiber sums live in registers: only boundary tables limit the node counts
@@ -800,7 +801,7 @@ bool plan_wants_tensor_order(const sc_plan *p)
 {
     if (p->dtype != SC_F32 || p->sched == SC_SCHED_LINEAR) return false;
     if (p->kind == K_TTMC3) return p->fcols[0] == 16 && p->fcols[1] == 16;
-    return p->kind == K_TTMC4;
+    return p->kind == K_TTMC4 && p->fcols[0] <= 16 && p->fcols[1] == 8 && p->fcols[2] == 8;   // the matrix-core kernels of the order-4 chain
 }
 
 size_t lds_bytes_needed(const sc_plan *p)

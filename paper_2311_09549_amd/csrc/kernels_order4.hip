@@ -241,7 +241,7 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.A = out;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     const size_t lds = order4_lds_bytes<T>(N, M * N, a.L, a.tn, a.ta, a.tb);
-    const bool mfma = sizeof(T) == 4 && a.L <= 16 && (M * N) % 16 == 0;   // the matrix-core kernel (fp32)
+    const bool mfma = sizeof(T) == 4 && a.L <= 16 && M == 8 && N == 8;   // the matrix-core kernel (fp32, M = N = 8)
     if (p->sched == SC_SCHED_FUSED) {
         if (mfma) {
             void *partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
@@ -295,8 +295,13 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
 TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols)
 {
     TileCaps c{0, 0, 0};
-    // instantiated: M = N = 8 (any L up to 16)
-    if (fcols[1] != 8 || fcols[2] != 8 || fcols[0] < 1 || fcols[0] > 16) return c;
+    // instantiated: M = N = 8 (fp32 on matrix cores, fp64 general kernel) and M = N = 16 (fp32, general kernel); any L up to 16
+    if (fcols[0] < 1 || fcols[0] > 16) return c;
+    if (fcols[1] == 16 && fcols[2] == 16 && dtype == SC_F32) {
+        c.tn = 512; c.ta = 256; c.tb = 24;   // T2 rows of 1 KB: 24 of them next to 256 T1 rows
+        return c;
+    }
+    if (fcols[1] != 8 || fcols[2] != 8) return c;
     if (dtype == SC_F64) {
         c.tn = 512; c.ta = 256; c.tb = 40;
     } else {
@@ -312,7 +317,7 @@ size_t order4_lds_bytes_needed(const sc_plan *p)
     const int N = (int)p->fcols[2], W2 = (int)(p->fcols[1] * p->fcols[2]), L = (int)p->fcols[0];
     const size_t own = p->dtype == SC_F64 ? order4_lds_bytes<double>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb)
                                           : order4_lds_bytes<float>(N, W2, L, p->caps.tn, p->caps.ta, p->caps.tb);
-    if (p->dtype == SC_F32 && p->fcols[0] <= 16) {
+    if (p->dtype == SC_F32 && p->fcols[0] <= 16 && p->fcols[1] == 8 && p->fcols[2] == 8) {
         if (!ttmc4_mfma_caps_ok(p)) return SIZE_MAX;
         if (p->sched != SC_SCHED_FISSIONED) return ttmc4_mfma_lds_bytes(p);
         return std::max(ttmc4_mfma_lds_bytes(p), leaf_traverse_lds_bytes(p, N));
@@ -323,6 +328,8 @@ size_t order4_lds_bytes_needed(const sc_plan *p)
 
 sc_status launch_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
+    if (p->fcols[1] == 16 && p->fcols[2] == 16 && p->dtype == SC_F32) return run_order4<float, 16, 16>(p, sp, fac, out, ws, stream);
+    if (p->fcols[1] != 8 || p->fcols[2] != 8) return SC_ERR_SCHED_UNSUPPORTED;
     return p->dtype == SC_F64 ? run_order4<double, 8, 8>(p, sp, fac, out, ws, stream)
                               : run_order4<float, 8, 8>(p, sp, fac, out, ws, stream);
 }

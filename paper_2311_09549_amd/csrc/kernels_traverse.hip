@@ -277,6 +277,7 @@ sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *po
         SC_LEAF(16)
         SC_LEAF(32)
         SC_LEAF(64)
+        SC_LEAF(128)
     default: return SC_ERR_SCHED_UNSUPPORTED;
     }
 #undef SC_LEAF

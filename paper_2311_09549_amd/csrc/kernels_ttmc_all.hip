@@ -132,16 +132,27 @@ __global__ void __launch_bounds__(NT) fiber_reduce_kernel(K5Args a)
     }
 }
 
-// A(e) = sum over chunks b, in order, of partial(b, e): every output element is written
+// A(e) = sum over chunks b of partial(b, e), in an order fixed by the launch: a workgroup owns 64 output
+// elements, its four wavefronts take the chunks round robin and their sums are added in wavefront order.
+// Every output element is written.
 template <typename T>
 __global__ void __launch_bounds__(NT) sum_partials_kernel(const T *__restrict__ partials, int nchunks, int64_t elems, T *__restrict__ out)
 {
-    const int64_t e = (int64_t)blockIdx.x * NT + threadIdx.x;
-    if (e >= elems) return;
+    __shared__ T part_s[NT];
+    const int lane = threadIdx.x % 64, part = threadIdx.x / 64;
+    const int64_t e = (int64_t)blockIdx.x * 64 + lane;
     T s = T(0);
-#pragma unroll 8
-    for (int b = 0; b < nchunks; ++b) s += partials[(int64_t)b * elems + e];
-    out[e] = s;
+    if (e < elems) {
+#pragma unroll 4
+        for (int b = part; b < nchunks; b += NT / 64) s += partials[(int64_t)b * elems + e];
+    }
+    part_s[threadIdx.x] = s;
+    __syncthreads();
+    if (part == 0 && e < elems) {
+        T tot = part_s[lane];
+        for (int w = 1; w < NT / 64; ++w) tot += part_s[w * 64 + lane];
+        out[e] = tot;
+    }
 }
 
 template <typename T>
@@ -191,7 +202,7 @@ sc_status run_ttmc_all(const sc_plan *p, const sc_csf_view *sp, const sc_dense_v
         ln.end();
     }
     ln.begin("ttmc_all_sum_partials");
-    sum_partials_kernel<T><<<(unsigned)((elems + NT - 1) / NT), NT, 0, stream>>>(static_cast<const T *>(a.partials), (int)p->k5_nchunks, elems,
+    sum_partials_kernel<T><<<(unsigned)((elems + 63) / 64), NT, 0, stream>>>(static_cast<const T *>(a.partials), (int)p->k5_nchunks, elems,
                                                                                static_cast<T *>(out));
     ln.end();
     return ln.status;

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -161,6 +162,18 @@ struct sc_plan {
 namespace sck {
 
 Tuning &tuning();
+
+// Workgroups using `lds` bytes of LDS each that one compute unit holds at a time: the unit's LDS
+// (160 KB on MI355X) is handed out in units of 1280 bytes (measured: a fifth workgroup of 31,880
+// bytes fits, one of 32,232 does not).  The kernels here are bound by latency, and their time
+// falls almost in proportion to this number, so tile sizes are chosen to land just below a step.
+inline int lds_workgroups_per_cu(size_t lds, int64_t lds_per_cu = 160 * 1024)
+{
+    const size_t unit = 1280;
+    const size_t need = std::max<size_t>(unit, (lds + unit - 1) / unit * unit);
+    return (int)std::max<size_t>(1, std::min<size_t>(8, (size_t)lds_per_cu / need));
+}
+
 
 // Built-in tile caps for a contraction (host side; the kernels size their LDS from them).
 TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int64_t *fcols);

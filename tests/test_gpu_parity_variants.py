@@ -15,6 +15,9 @@ VARIANTS = [
     (3, 0.002, "f32", (8, 16)), (3, 0.002, "f32", (16, 32)), (3, 0.002, "f32", (4, 8)), (3, 0.002, "f64", (16, 16)),
     (4, 0.002, "f32", (32, 32)), (4, 0.002, "f32", (16, 16)), (4, 0.002, "f64", (64, 64)),
     (5, 0.003, "f32", (16, 8, 8)), (5, 0.003, "f32", (4, 8, 8)), (5, 0.003, "f64", (8, 8, 8)),
+    # the widest ranks: 128-wide rows of the temporaries (order 3), 16 x 16 tiles of the second temporary (order 4)
+    (2, 0.003, "f32", (128,)), (2, 0.003, "f64", (128,)), (3, 0.002, "f32", (128, 128)), (3, 0.002, "f32", (16, 128)),
+    (3, 0.002, "f32", (128, 16)), (3, 0.002, "f64", (64, 128)), (5, 0.003, "f32", (16, 16, 16)), (5, 0.003, "f32", (8, 16, 16)),
 ]
 
 
@@ -28,3 +31,27 @@ def test_parity_variant(oracle, cid, scale, dtype, ranks, which):
     print(f"config {cid} scale {scale} {dtype} ranks {ranks} {which}", flush=True)
     con, got = run_library(cfg, data, which)
     assert_parity(oracle, cfg, data, got)
+
+
+@pytest.mark.parametrize("cid,scale", [(1, 1.0), (2, 0.003), (3, 0.002), (4, 0.002), (5, 0.003), (6, 0.01)])
+def test_parity_schedule_picked_by_the_cost_evaluator(oracle, cid, scale):
+    """SC_SCHED_AUTO plans execute like the class they settle on."""
+    from paper_2311_09549_amd import binding as sc
+    from paper_2311_09549_amd.driver import Contraction
+
+    cfg = synth.config(cid, scale)
+    data = synth.generate(cfg)
+    con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"], sc.schedule("auto"),
+                      synth.output_shape(cfg))
+    print(f"config {cid}: evaluator chose {sc.plan_chosen(con.plan)}", flush=True)
+    con.run()
+    assert_parity(oracle, cfg, data, con.result())
+    if cid == 3:   # ranks only the unfactored nest takes: the evaluator falls back to it
+        import numpy as np
+        cfg = dict(cfg, ranks=(12, 20))
+        data = synth.generate(cfg)
+        con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"], sc.schedule("auto"),
+                          synth.output_shape(cfg))
+        assert sc.plan_chosen(con.plan) == ("linear", 0)
+        con.run()
+        assert_parity(oracle, cfg, data, con.result())

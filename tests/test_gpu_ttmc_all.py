@@ -34,7 +34,8 @@ def _cfg(scale, dtype="f32", ranks=(16, 16, 16), seed_offset=0):
 @pytest.mark.parametrize("which,names", VARIANTS, ids=IDS)
 @pytest.mark.parametrize("scale", [0.002, 0.02])
 @pytest.mark.parametrize("dtype,ranks", [("f32", (16, 16, 16)), ("f64", (16, 16, 16)), ("f32", (8, 16, 8)), ("f32", (32, 4, 32)),
-                                         ("f64", (4, 8, 8)), ("f32", (64, 16, 16))])
+                                         ("f64", (4, 8, 8)), ("f32", (64, 16, 16)), ("f32", (128, 32, 32)), ("f32", (16, 128, 128)),
+                                         ("f32", (64, 64, 64))])
 def test_parity_three_schedules(oracle, dtype, ranks, scale, which, names):
     cfg, data = _cfg(scale, dtype, ranks)
     print(f"ttmc_all {which} {names} {dtype} ranks={ranks} dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)

@@ -126,9 +126,16 @@ def test_derived_temporaries_and_workspace(cid, scale, temps):
                    sc.schedule("fissioned", temps + ["X(i)"], [0] * (len(temps) + 1))) in ("SC_ERR_SCHED_UNSUPPORTED",)
     assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
                    sc.schedule("fissioned", temps, [1] * len(temps))) == "SC_ERR_SCHED_UNSUPPORTED"
-    fused = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused", temps, [1] * len(temps)))
+    # FUSED: the fuse depth is 0 (the library's) or the depth its kernel is built at; other depths are refused, not ignored
+    built = 2 if cfg["kind"] in ("mttkrp3", "sddmm_spmm") else 1
+    fused = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused", temps, [built] * len(temps)))
     assert sc.plan_workspace_bytes(fused) == 0
     assert _status(sc.plan_intermediate, fused, 0) == "SC_ERR_SCHED_UNSUPPORTED"
+    assert sc.plan_chosen(fused) == ("fused", 0)
+    for depth in (1, 2, 3):
+        if depth != built:
+            assert _status(sc.plan_create, cfg["expr"], csf, data["factors"],
+                           sc.schedule("fused", temps, [depth] * len(temps))) == "SC_ERR_SCHED_UNSUPPORTED"
 
 
 def test_expression_family():
@@ -459,3 +466,40 @@ def test_all_mode_ttmc_plans():
     # shapes: the factor on mode 0 has one row per coordinate of mode 0
     wrong = [data["factors"][1], data["factors"][1], data["factors"][2]]
     assert _status(sc.plan_create, cfg["expr"], csf, wrong, sc.schedule("fused")) == "SC_ERR_SHAPE_MISMATCH"
+
+
+def test_cost_evaluator_picks_a_schedule():
+    """SC_SCHED_AUTO (run-time stage of Section 5): the class of least predicted time among those with kernels
+    for the ranks; the decision and the candidates' figures are in the description."""
+    for cid, scale in [(1, 1.0), (2, 0.004), (3, 0.003), (4, 0.003), (5, 0.004)]:
+        cfg, data, csf = _small(cid, scale)
+        plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("auto"))
+        assert sc.plan_chosen(plan) == ("fused", 0), cid           # same iterations as FISSIONED, fewer bytes
+        text = sc.plan_describe(plan)
+        assert "cost evaluator" in text and text.count("candidate") == 3 and "<- chosen" in text
+        ref = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("fused"))
+        assert sc.plan_model(plan) == sc.plan_model(ref) and sc.plan_workspace_bytes(plan) == sc.plan_workspace_bytes(ref)
+    # ranks no factored kernel is built for: only the unfactored nest can run them, and AUTO says so
+    cfg, data, csf = _small(3, 0.003)
+    odd = [np.ascontiguousarray(np.resize(f, (f.shape[0], 24))) for f in data["factors"]]
+    assert _status(sc.plan_create, cfg["expr"], csf, odd, sc.schedule("fused")) == "SC_ERR_SCHED_UNSUPPORTED"
+    plan = sc.plan_create(cfg["expr"], csf, odd, sc.schedule("auto"))
+    assert sc.plan_chosen(plan) == ("linear", 0)
+    assert "no kernel for these ranks" in sc.plan_describe(plan)
+    # ... unless the caller also asks for a reproducible result, which the unfactored nest cannot give
+    assert _status(sc.plan_create, cfg["expr"], csf, odd, sc.schedule("auto", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
+    # AUTO takes no temporaries or depths from the caller
+    assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("auto", ["T(i,j,m)"], [0])) == "SC_ERR_SCHED_UNSUPPORTED"
+
+    # all-mode TTMC: the three schedules of Table 2 compete; the second has the fewest iterations wherever slices
+    # hold several fibers, and the third takes over when the second has no kernel for the ranks
+    cfg = synth.config(6, 0.005)
+    data = synth.generate(cfg)
+    csf = sc.coo_to_csf(list(data["coords"]), data["vals"], cfg["dims"])
+    plan = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("auto"))
+    assert sc.plan_chosen(plan) == ("fused", 2)
+    assert sc.plan_describe(plan).count("candidate Table 2 schedule") == 4
+    odd = [data["factors"][0]] + [np.ascontiguousarray(np.resize(f, (f.shape[0], 24))) for f in data["factors"][1:]]
+    plan = sc.plan_create(cfg["expr"], csf, odd, sc.schedule("auto"))
+    assert sc.plan_chosen(plan) == ("fused", 3)
+    assert _status(sc.plan_create, cfg["expr"], csf, odd, sc.schedule("auto", deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
