@@ -236,6 +236,75 @@ int oracle_ttmc_all(int64_t nnz, const int32_t *ci, const int32_t *cj, const int
 }
 
 /*
+ * Table 2, kernel 8 <MTTKRP,GEMM>:
+ * A(i,m) = sum_{j,k,r} B(i,j,k) * C(j,r) * D(k,r) * E(r,m).
+ * A is I x M, C is J x R, D is K x R, E is R x M.
+ */
+int oracle_mttkrp_gemm(int64_t nnz, const int32_t *ci, const int32_t *cj, const int32_t *ck, const double *vals,
+                       int64_t I, int64_t J, int64_t K, const double *C, const double *D, int64_t R,
+                       const double *E, int64_t M, double *A, int nthreads)
+{
+    int64_t *row_ptr, *perm;
+    int rc = bucket_by_row(nnz, ci, I, &row_ptr, &perm);
+    if (rc) return rc;
+    for (int64_t n = 0; n < nnz; ++n)
+        if (cj[n] < 0 || cj[n] >= J || ck[n] < 0 || ck[n] >= K) { free(row_ptr); free(perm); return -2; }
+    memset(A, 0, sizeof(double) * (size_t)(I * M));
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int64_t i = 0; i < I; ++i) {
+        double *Ai = A + i * M;
+        for (int64_t q = row_ptr[i]; q < row_ptr[i + 1]; ++q) {
+            const int64_t n = perm[q];
+            const double b = vals[n];
+            const double *Cj = C + (int64_t)cj[n] * R;
+            const double *Dk = D + (int64_t)ck[n] * R;
+            for (int64_t r = 0; r < R; ++r)
+                for (int64_t m = 0; m < M; ++m)
+                    Ai[m] += b * Cj[r] * Dk[r] * E[r * M + m];
+        }
+    }
+    free(row_ptr); free(perm);
+    return 0;
+}
+
+/*
+ * Table 2, kernel 2 <SDDMM,SpMM,GEMM>:
+ * A(i,m) = sum_{j,k,l} S(i,j) * X(i,k) * Y(j,k) * Z(j,l) * F(l,m).
+ * S is I x J sparse, X is I x K, Y is J x K, Z is J x L, F is L x M, A is I x M.
+ * The perfectly nested loop: every stored entry times one element of every factor for every
+ * combination of k, l and m.
+ */
+int oracle_sddmm_spmm_gemm(int64_t nnz, const int32_t *ci, const int32_t *cj, const double *vals,
+                           int64_t I, int64_t J, const double *X, const double *Y, int64_t K,
+                           const double *Z, int64_t L, const double *F, int64_t M, double *A, int nthreads)
+{
+    int64_t *row_ptr, *perm;
+    int rc = bucket_by_row(nnz, ci, I, &row_ptr, &perm);
+    if (rc) return rc;
+    for (int64_t n = 0; n < nnz; ++n)
+        if (cj[n] < 0 || cj[n] >= J) { free(row_ptr); free(perm); return -2; }
+    memset(A, 0, sizeof(double) * (size_t)(I * M));
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads)
+    for (int64_t i = 0; i < I; ++i) {
+        double *Ai = A + i * M;
+        const double *Xi = X + i * K;
+        for (int64_t q = row_ptr[i]; q < row_ptr[i + 1]; ++q) {
+            const int64_t n = perm[q];
+            const double *Yj = Y + (int64_t)cj[n] * K;
+            const double *Zj = Z + (int64_t)cj[n] * L;
+            for (int64_t k = 0; k < K; ++k)
+                for (int64_t l = 0; l < L; ++l)
+                    for (int64_t m = 0; m < M; ++m)
+                        Ai[m] += vals[n] * Xi[k] * Yj[k] * Zj[l] * F[l * M + m];
+        }
+    }
+    free(row_ptr); free(perm);
+    return 0;
+}
+
+/*
  * SpMM, the loop of Figure 1b:  A(i,k) = sum_j B(i,j) * C(j,k).
  * Kept as the degenerate order-2 member of the family; used to pin the others.
  */

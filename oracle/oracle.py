@@ -154,6 +154,37 @@ def contract_ttmc_all(coords, vals, dims, C, D, E, nthreads=None):
     return A
 
 
+def contract_mttkrp_gemm(coords, vals, dims, C, D, E, nthreads=None):
+    """A(i,m) = sum_jkr B(i,j,k) C(j,r) D(k,r) E(r,m)   (Table 2, kernel 8)."""
+    ci, cj, ck = (_i32(c) for c in coords)
+    v, C, D, E = _f64(vals), _f64(C), _f64(D), _f64(E)
+    I, J, K = (int(d) for d in dims)
+    R, M = C.shape[1], E.shape[1]
+    assert C.shape[0] == J and D.shape == (K, R) and E.shape[0] == R
+    A = np.empty((I, M), dtype=np.float64)
+    rc = _load().oracle_mttkrp_gemm(_i64(v.size), _p(ci, _pi32), _p(cj, _pi32), _p(ck, _pi32), _p(v, _pf64),
+                                    _i64(I), _i64(J), _i64(K), _p(C, _pf64), _p(D, _pf64), _i64(R),
+                                    _p(E, _pf64), _i64(M), _p(A, _pf64), ctypes.c_int(_threads(nthreads)))
+    _check(rc, "oracle_mttkrp_gemm")
+    return A
+
+
+def contract_sddmm_spmm_gemm(coords, vals, dims, X, Y, Z, F, nthreads=None):
+    """A(i,m) = sum_jkl S(i,j) X(i,k) Y(j,k) Z(j,l) F(l,m)   (Table 2, kernel 2)."""
+    ci, cj = (_i32(c) for c in coords)
+    v, X, Y, Z, F = _f64(vals), _f64(X), _f64(Y), _f64(Z), _f64(F)
+    I, J = (int(d) for d in dims)
+    K, L, M = X.shape[1], Z.shape[1], F.shape[1]
+    assert X.shape[0] == I and Y.shape == (J, K) and Z.shape[0] == J and F.shape[0] == L
+    A = np.empty((I, M), dtype=np.float64)
+    rc = _load().oracle_sddmm_spmm_gemm(_i64(v.size), _p(ci, _pi32), _p(cj, _pi32), _p(v, _pf64),
+                                        _i64(I), _i64(J), _p(X, _pf64), _p(Y, _pf64), _i64(K),
+                                        _p(Z, _pf64), _i64(L), _p(F, _pf64), _i64(M), _p(A, _pf64),
+                                        ctypes.c_int(_threads(nthreads)))
+    _check(rc, "oracle_sddmm_spmm_gemm")
+    return A
+
+
 def contract_spmm(coords, vals, dims, C, nthreads=None):
     """A(i,k) = sum_j B(i,j) C(j,k)   (Figure 1b)."""
     ci, cj = (_i32(c) for c in coords)
@@ -175,6 +206,8 @@ _CONTRACT = {
     "sddmm_spmm": contract_sddmm_spmm,
     "ttmc4": contract_ttmc4,
     "ttmc_all": contract_ttmc_all,
+    "mttkrp_gemm": contract_mttkrp_gemm,
+    "sddmm_spmm_gemm": contract_sddmm_spmm_gemm,
 }
 
 

@@ -22,6 +22,8 @@ EINSUM = {
     "mttkrp3": "ijk,jr,kr->ir",
     "ttmc4": "ijkp,jl,km,pn->ilmn",
     "ttmc_all": "ijk,il,jm,kn->lmn",
+    "mttkrp_gemm": "ijk,jr,kr,rm->im",
+    "sddmm_spmm_gemm": "ij,ik,jk,jl,lm->im",
 }
 
 
@@ -41,6 +43,10 @@ def _random_case(kind, rng, dims, nnz, ranks, empty_rows=()):
         shapes = [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1])]
     elif kind == "ttmc_all":
         shapes = [(dims[0], ranks[0]), (dims[1], ranks[1]), (dims[2], ranks[2])]
+    elif kind == "mttkrp_gemm":
+        shapes = [(dims[1], ranks[0]), (dims[2], ranks[0]), (ranks[0], ranks[1])]
+    elif kind == "sddmm_spmm_gemm":
+        shapes = [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1]), (ranks[1], ranks[2])]
     else:
         shapes = [(dims[1], ranks[0]), (dims[2], ranks[1]), (dims[3], ranks[2])]
     factors = [rng.standard_normal(s) for s in shapes]
@@ -56,6 +62,9 @@ def _dense(coords, vals, dims):
 
 def _brute(kind, coords, vals, dims, factors):
     B = _dense(coords, vals, dims)
+    if kind == "sddmm_spmm_gemm":
+        X, Y, Z, F = factors
+        return ((B * (X @ Y.T)) @ Z) @ F
     if kind == "sddmm_spmm":
         X, Y, Z = factors
         return (B * (X @ Y.T)) @ Z
@@ -70,12 +79,14 @@ CASES = [
     ("ttmc4", (3, 4, 5, 6), 90, (2, 3, 4)),
     ("ttmc_all", (5, 6, 7), 60, (2, 3, 4)),
     ("ttmc_all", (4, 3, 9), 108, (4, 2, 3)),   # every coordinate stored
+    ("mttkrp_gemm", (5, 6, 7), 70, (3, 4)),
+    ("sddmm_spmm_gemm", (6, 7), 20, (3, 4, 2)),
 ]
 
 
 def test_golden_worked_examples(oracle):
     g = json.load(open(os.path.join(HERE, "golden", "worked_examples.json")))
-    for kind in ("ttmc3", "mttkrp3", "sddmm_spmm", "ttmc4", "ttmc_all"):
+    for kind in ("ttmc3", "mttkrp3", "sddmm_spmm", "ttmc4", "ttmc_all", "mttkrp_gemm", "sddmm_spmm_gemm"):
         e = g[kind]
         A = oracle.contract(kind, np.array(e["coords"]), np.array(e["vals"], float), e["dims"],
                             [np.array(f, float) for f in e["factors"]])
@@ -324,3 +335,22 @@ def test_ttmc_all_slice_intermediate(oracle):
     # first schedule: t(i,j,n) per fiber, then A(l,m,n) += t * C(i,l) * D(j,m)
     pre2, t = oracle.intermediate_leaf(coords, vals, dims, E)
     np.testing.assert_allclose(np.einsum("fl,fm,fn->lmn", C[pre2[0]], D[pre2[1]], t), A, rtol=0, atol=1e-12)
+
+
+def test_trailing_gemm_kernels_are_their_producers_times_the_last_factor(oracle):
+    """Kernels 8 and 2 of Table 2 = the MTTKRP / kernel 1 (pinned above) followed by a dense matrix
+    product with the last factor (numpy matmul), on non-square shapes."""
+    rng = np.random.default_rng(41)
+    dims = (6, 5, 7)
+    coords, vals, (C, D, E) = _random_case("mttkrp_gemm", rng, dims, 90, (3, 5), empty_rows=(4,))
+    A = oracle.contract("mttkrp_gemm", coords, vals, dims, [C, D, E])
+    np.testing.assert_allclose(A, oracle.contract("mttkrp3", coords, vals, dims, [C, D]) @ E, rtol=0, atol=1e-12)
+    assert np.all(A[4] == 0)
+    dims = (7, 6)
+    coords, vals, (X, Y, Z, F) = _random_case("sddmm_spmm_gemm", rng, dims, 25, (3, 4, 5), empty_rows=(2,))
+    A = oracle.contract("sddmm_spmm_gemm", coords, vals, dims, [X, Y, Z, F])
+    np.testing.assert_allclose(A, oracle.contract("sddmm_spmm", coords, vals, dims, [X, Y, Z]) @ F, rtol=0, atol=1e-12)
+    assert np.all(A[2] == 0)
+    # an identity last factor leaves the producer's result
+    A = oracle.contract("sddmm_spmm_gemm", coords, vals, dims, [X, Y, Z, np.eye(4)])
+    np.testing.assert_allclose(A, oracle.contract("sddmm_spmm", coords, vals, dims, [X, Y, Z]), rtol=0, atol=1e-13)

@@ -313,3 +313,60 @@ def test_kernel5_table2_schedules_match_the_oracle_and_their_counts(which):
     S, F = len(_fibers(coords, 1)) - 1, len(_fibers(coords, 2)) - 1
     want = {1: N * (nnz + F * M * L), 2: N * (nnz + F * M + S * M * L), 3: M * N * (nnz + S * L)}[which]
     assert cnt.n == want
+
+
+def test_trailing_gemm_schedules_of_table2_match_the_oracle_and_their_counts():
+    """Kernel 8: i,r < t; j',k': t += B C D, m: A += t E >.  Kernel 2, first schedule: i < T_l; j' < t; k: t += S X Y,
+    l: T_l += t Z >, m,l: A += T_l F >.  Iteration counts R (nnz + S M) and nnz (K + L) + S L M."""
+    rng = np.random.default_rng(61)
+    dims, R, M, nnz = (5, 4, 6), 3, 4, 40
+    flat = np.sort(rng.choice(int(np.prod(dims)), size=nnz, replace=False))
+    coords = [c.astype(np.int32) for c in np.unravel_index(flat, dims)]
+    vals = rng.uniform(-1, 1, nnz)
+    C, D, E = rng.standard_normal((dims[1], R)), rng.standard_normal((dims[2], R)), rng.standard_normal((R, M))
+    f1 = _fibers(coords, 1)
+    A = np.zeros((dims[0], M))
+    n = 0
+    for s in range(len(f1) - 1):
+        i = coords[0][f1[s]]
+        for r in range(R):
+            t = 0.0
+            for z in range(f1[s], f1[s + 1]):
+                t += vals[z] * C[coords[1][z], r] * D[coords[2][z], r]
+                n += 1
+            for m in range(M):
+                A[i, m] += t * E[r, m]
+                n += 1
+    ref = oracle.contract("mttkrp_gemm", coords, vals, dims, [C, D, E])
+    bound = oracle.abs_bound("mttkrp_gemm", coords, vals, dims, [C, D, E])
+    assert np.all(np.abs(A - ref) <= 1e-13 * np.maximum(bound, 1e-300))
+    assert n == R * (nnz + (len(f1) - 1) * M)
+
+    dims, K, L, M, nnz = (6, 7), 3, 4, 5, 22
+    flat = np.sort(rng.choice(int(np.prod(dims)), size=nnz, replace=False))
+    coords = [c.astype(np.int32) for c in np.unravel_index(flat, dims)]
+    vals = rng.uniform(-1, 1, nnz)
+    X, Y, Z, F = (rng.standard_normal(sh) for sh in ((dims[0], K), (dims[1], K), (dims[1], L), (L, M)))
+    f1 = _fibers(coords, 1)
+    A = np.zeros((dims[0], M))
+    n = 0
+    for s in range(len(f1) - 1):
+        i = coords[0][f1[s]]
+        Tl = np.zeros(L)
+        for z in range(f1[s], f1[s + 1]):
+            j = coords[1][z]
+            t = 0.0
+            for k in range(K):
+                t += vals[z] * X[i, k] * Y[j, k]
+                n += 1
+            for l in range(L):
+                Tl[l] += t * Z[j, l]
+                n += 1
+        for m in range(M):
+            for l in range(L):
+                A[i, m] += Tl[l] * F[l, m]
+                n += 1
+    ref = oracle.contract("sddmm_spmm_gemm", coords, vals, dims, [X, Y, Z, F])
+    bound = oracle.abs_bound("sddmm_spmm_gemm", coords, vals, dims, [X, Y, Z, F])
+    assert np.all(np.abs(A - ref) <= 1e-13 * np.maximum(bound, 1e-300))
+    assert n == nnz * (K + L) + (len(f1) - 1) * L * M
