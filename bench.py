@@ -49,7 +49,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=0,
-                    help="measure only this workload (1..5; 6 = the headline workload plus the all-mode TTMC); default: all five and the all-mode TTMC, headline on the largest")
+                    help="measure only this workload (1..5); 6..10 = the headline workload plus one of the further workloads (all-mode TTMC and its rank sweep, kernel 8, kernel 2, uniform cases 1 and 2); default: everything, headline on the largest")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workloads (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-fissioned", action="store_true")
@@ -233,53 +233,84 @@ def main() -> int:
             rec["gpu_vs_cpu_oracle"] = rec["gflops"] / rec["cpu_baseline"]["value"]
         return rec
 
-    def bench_ttmc_all():
-        """All-mode TTMC (Table 2, kernel 5) under the three schedules Table 2 lists, on a workload of the first dense
-        sizes of the paper's auxiliary-memory table: not one of the five benchmark workloads, reported beside them."""
-        cid = 6
-        cfg = synth.config(cid, args.scale)
+    K5_VARIANTS = [("schedule2_fused", "fused", []), ("schedule2_fissioned", "fissioned", ["T1(i,j,n)", "T2(i,m,n)"]),
+                   ("schedule1", "fissioned", ["T(i,j,n)"]), ("schedule3", "fused", ["T(i,m,n)"])]
+    CLASS_VARIANTS = [("fused", "fused", []), ("fissioned", "fissioned", []), ("linear", "linear", [])]
+
+    def bench_next(cid, text, variants, steps, linear_flops=None, with_oracle=True, cfg=None):
+        """A workload beyond the five benchmark ones: every listed schedule timed, the first one the reference of the
+        speedups; kernels timed one by one; the oracle's perfectly nested loop timed when it runs in seconds."""
+        cfg = cfg or synth.config(cid, args.scale)
         data = synth.generate(cfg, cache_dir=os.environ.get("TMPDIR", "/tmp") + "/sc_synth_cache")
         out_shape = synth.output_shape(cfg)
-        rec = {"workload": "all-mode TTMC A(l,m,n) (Table 2, kernel 5), fp32, 40,000x20,000x8,000, 4M Zipf(1.1) nonzeros, L=M=N=16",
-               "nnz": int(cfg["nnz"]), "schedules": {}}
-        variants = [("schedule2_fused", "fused", []), ("schedule2_fissioned", "fissioned", ["T1(i,j,n)", "T2(i,m,n)"]),
-                    ("schedule1", "fissioned", ["T(i,j,n)"]), ("schedule3", "fused", ["T(i,m,n)"])]
+        rec = {"workload": text, "nnz": int(cfg["nnz"]), "ranks": list(cfg["ranks"]), "schedules": {}}
         first = None
         for name, kind, temps in variants:
             con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
                               sc.schedule(kind, temps, [0] * len(temps)), out_shape, share=first)
             first = first or con
             flops, nbytes = sc.plan_model(con.plan)
-            ms, stats = timed(con, max(5, args.steps // 2), 2)
+            ms, stats = timed(con, steps, 2)
             kt = kernel_times(con, 5)
             dom = max(kt, key=kt.get)
-            rec["schedules"][name] = {
+            entry = {
                 "ms_per_step": ms, "ms_per_step_stats": stats, "schedule_flops": flops, "gflops": flops / (ms * 1e-3) / 1e9,
-                "kernels_ms": kt, "workspace_bytes": con.ws_bytes,
+                "kernels_ms": kt, "workspace_bytes": con.ws_bytes, "chosen": list(sc.plan_chosen(con.plan)),
                 "roofline": {"bound": "hbm", "kernel": dom, "algorithmic_bytes": nbytes, "kernel_ms": kt[dom],
                              "achieved": nbytes / (kt[dom] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                              "frac": nbytes / (kt[dom] * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None},
             }
+            gemm = [n for n in kt if n.startswith("trailing_gemm")]
+            if gemm:   # the GEMM-shaped stage on its own: its flops over its time against the fp32 matrix-core peak
+                r_, m_ = cfg["ranks"][-2], cfg["ranks"][-1]
+                gf = 2.0 * cfg["dims"][0] * r_ * m_
+                entry["gemm_stage"] = {"kernel": gemm[0], "ms": kt[gemm[0]], "flops": gf, "tflops": gf / (kt[gemm[0]] * 1e-3) / 1e12,
+                                       "frac_of_fp32_matrix_peak": gf / (kt[gemm[0]] * 1e-3) / 157.3e12}
+            rec["schedules"][name] = entry
             if con is not first:
                 del con
         del first
         torch.cuda.empty_cache()
-        base = rec["schedules"]["schedule2_fused"]["ms_per_step"]
-        rec["speedup_of_schedule2_fused_over"] = {k: v["ms_per_step"] / base for k, v in rec["schedules"].items()}
-        if not args.no_cpu_baseline:
+        ref = variants[0][0]
+        base = rec["schedules"][ref]["ms_per_step"]
+        rec["speedup_of_" + ref + "_over"] = {k: v["ms_per_step"] / base for k, v in rec["schedules"].items()}
+        if with_oracle and not args.no_cpu_baseline:
             from oracle import oracle as o
             o.build()
             cores = o.max_threads()
             secs = o.time_contract(cfg["kind"], data["coords"], data["vals"], cfg["dims"], data["factors"], nthreads=cores, warmup=1, runs=3)
             t_cpu = float(np.median(secs))
-            L, M, N = cfg["ranks"]
             rec["cpu_baseline"] = {"seconds": t_cpu, "cores": cores, "kind": "oracle", "unit": "GFLOP/s",
-                                   "value": 4.0 * L * M * N * cfg["nnz"] / t_cpu / 1e9,
-                                   "sample": "whole workload, the perfectly nested loop of Figure 2a in fp64 (4 L M N nnz flops), "
+                                   "value": (linear_flops or 0.0) / t_cpu / 1e9,
+                                   "sample": "whole workload, the perfectly nested loop in fp64 (its own flop count), "
                                              "C call only, 1 warm-up + median of 3 runs"}
         return rec
 
-    cids = [5] if args.config == 6 else [args.config] if args.config else [1, 2, 3, 4, 5]
+    def bench_rank_sweep():
+        """All-mode TTMC on the 4 M-nonzero tensor over dense sizes of the paper's auxiliary-memory table, schedule picked
+        by the cost evaluator: time, the evaluator's choice, and the LDS footprint that decides how many workgroups share
+        a compute unit (where the on-chip temporary stops fitting, the evaluator leaves the fused class)."""
+        base = synth.config(6, args.scale)
+        data0 = synth.generate(base, cache_dir=os.environ.get("TMPDIR", "/tmp") + "/sc_synth_cache")
+        rows = []
+        first = None
+        for L, MN in [(16, 16), (64, 16), (128, 16), (16, 32), (64, 32), (128, 32), (16, 64), (64, 64), (128, 64), (16, 128), (128, 128)]:
+            cfg = dict(base, ranks=(L, MN, MN))
+            rng_cfg = synth.generate(dict(cfg, nnz=1, dims=base["dims"]))   # factors only (same seeds as a full draw)
+            factors = rng_cfg["factors"]
+            con = Contraction(cfg["expr"], data0["coords"], data0["vals"], cfg["dims"], factors, sc.schedule("auto"),
+                              synth.output_shape(cfg))
+            flops, nbytes = sc.plan_model(con.plan)
+            ms, _ = timed(con, 5, 1)
+            text = sc.plan_describe(con.plan)
+            chosen = [ln for ln in text.splitlines() if "<- chosen" in ln]
+            rows.append({"L": L, "M": MN, "N": MN, "ms": ms, "gflops": flops / (ms * 1e-3) / 1e9, "chosen": list(sc.plan_chosen(con.plan)),
+                         "evaluator": chosen[0].strip() if chosen else None, "workspace_bytes": con.ws_bytes})
+            del con
+            torch.cuda.empty_cache()
+        return rows
+
+    cids = [5] if args.config >= 6 else [args.config] if args.config else [1, 2, 3, 4, 5]
     per_config = []
     for cid in cids:
         per_config.append(bench_config(cid))
@@ -314,8 +345,30 @@ def main() -> int:
         if k in head:
             result[k] = head[k]
     result["per_config"] = per_config
-    if not args.config or args.config == 6:
-        result["next_workloads"] = {"ttmc_all": bench_ttmc_all()}
+    if not args.config or args.config >= 6:
+        nw = {}
+        st = max(5, args.steps // 2)
+        if args.config in (0, 6):
+            L, M, N = synth.CONFIGS[6]["ranks"]
+            nw["ttmc_all"] = bench_next(6, "all-mode TTMC A(l,m,n) (Table 2, kernel 5), fp32, 40,000x20,000x8,000, 4M Zipf(1.1) nonzeros, L=M=N=16",
+                                        K5_VARIANTS, st, linear_flops=4.0 * L * M * N * synth.CONFIGS[6]["nnz"])
+            nw["ttmc_all_rank_sweep"] = bench_rank_sweep()
+        if args.config in (0, 7):
+            R, M = synth.CONFIGS[7]["ranks"]
+            nw["mttkrp_gemm"] = bench_next(7, "MTTKRP then GEMM A(i,m) (Table 2, kernel 8), fp32, the tensor of configs[1], R=32, M=64",
+                                           CLASS_VARIANTS, st, linear_flops=4.0 * R * M * synth.CONFIGS[7]["nnz"])
+        if args.config in (0, 8):
+            nw["sddmm_spmm_gemm"] = bench_next(8, "SDDMM->SpMM then GEMM A(i,m) (Table 2, kernel 2), fp32, the matrix of configs[3], K=L=M=64",
+                                               CLASS_VARIANTS[:2], st, with_oracle=False)
+        if args.config in (0, 9):
+            nw["ttmc_all_uniform_case1"] = bench_next(9, "all-mode TTMC, motivating case 1 of Section 3: uniform 1800x800x1000, sparsity 0.008, L,M,N=64,16,32 "
+                                                         "(the paper's Figure 2 schedules on 32 Xeon cores: 2.48 s / 6.26 s / 32.40 s)", K5_VARIANTS, 5,
+                                                      with_oracle=False)
+        if args.config in (0, 10):
+            nw["ttmc_all_uniform_case2"] = bench_next(10, "all-mode TTMC, motivating case 2 of Section 3: uniform 1800x1600x2000, sparsity 0.002, L,M,N=64,16,32 "
+                                                          "(the paper's Figure 2 schedules on 32 Xeon cores: 10.20 s / 8.60 s / 33.51 s)", K5_VARIANTS, 5,
+                                                       with_oracle=False)
+        result["next_workloads"] = nw
     print(json.dumps(result))
     return 0
 

@@ -115,7 +115,7 @@ std::string join(const std::string &name, const std::vector<std::string> &idx)
 
 struct Family {
     Kind kind;
-    int slot_of_factor[3];  // canonical slot -> position among the dense factors (0-based after the sparse operand)
+    int slot_of_factor[4];  // canonical slot -> position among the dense factors (0-based after the sparse operand)
     std::vector<std::vector<std::string>> temp_idx;  // derived temporaries, deepest producer first
     std::vector<std::string> temp_name;
 };
@@ -172,6 +172,53 @@ sc_status classify(const Term &lhs, const std::vector<Term> &rhs, Family &fam)
         return -1;
     };
 
+    if (d == 3 && nf == 3 && lhs.idx.size() == 2) {
+        // B(i,j,k) * C(j,r) * D(k,r) * E(r,m) -> A(i,m): the MTTKRP followed by a dense product (kernel 8 of Table 2)
+        const int c = find_on(sp.idx[1], -1), dd = find_on(sp.idx[2], -1);
+        if (c < 0 || dd < 0 || c == dd) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &r = rhs[c].idx[1];
+        if (rhs[dd].idx[1] != r || contains(sp.idx, r)) return SC_ERR_EXPR_UNSUPPORTED;
+        int e = -1;
+        for (size_t f = 1; f <= nf; ++f)
+            if ((int)f != c && (int)f != dd) e = (int)f;
+        if (e < 0 || rhs[e].idx[0] != r) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &m = rhs[e].idx[1];
+        if (contains(sp.idx, m) || m == r || lhs.idx[1] != m) return SC_ERR_EXPR_UNSUPPORTED;
+        fam.kind = K_MTTKRP_GEMM;
+        fam.slot_of_factor[0] = c - 1; fam.slot_of_factor[1] = dd - 1; fam.slot_of_factor[2] = e - 1;
+        fam.temp_idx = {{sp.idx[0], sp.idx[1], r}, {sp.idx[0], r}};
+        fam.temp_name = {"T1", "T2"};
+        return SC_OK;
+    }
+    if (d == 2 && nf == 4) {
+        // S(i,j) * X(i,k) * Y(j,k) * Z(j,l) * F(l,m) -> A(i,m): kernel 1 followed by a dense product (kernel 2 of Table 2)
+        if (lhs.idx.size() != 2) return SC_ERR_EXPR_UNSUPPORTED;
+        const int x = find_on(sp.idx[0], -1);
+        if (x < 0) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &k = rhs[x].idx[1];
+        int y = -1, z = -1, ff = -1;
+        for (size_t f = 1; f <= nf; ++f) {
+            if ((int)f == x) continue;
+            if (rhs[f].idx[0] == sp.idx[1]) {
+                if (rhs[f].idx[1] == k) { if (y >= 0) return SC_ERR_EXPR_UNSUPPORTED; y = (int)f; }
+                else { if (z >= 0) return SC_ERR_EXPR_UNSUPPORTED; z = (int)f; }
+            } else {
+                if (ff >= 0) return SC_ERR_EXPR_UNSUPPORTED;
+                ff = (int)f;
+            }
+        }
+        if (y < 0 || z < 0 || ff < 0) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &l = rhs[z].idx[1];
+        if (rhs[ff].idx[0] != l) return SC_ERR_EXPR_UNSUPPORTED;
+        const std::string &m = rhs[ff].idx[1];
+        if (contains(sp.idx, k) || contains(sp.idx, l) || contains(sp.idx, m) || m == l || m == k || l == k) return SC_ERR_EXPR_UNSUPPORTED;
+        if (lhs.idx[1] != m) return SC_ERR_EXPR_UNSUPPORTED;
+        fam.kind = K_SDDMM_SPMM_GEMM;
+        fam.slot_of_factor[0] = x - 1; fam.slot_of_factor[1] = y - 1; fam.slot_of_factor[2] = z - 1; fam.slot_of_factor[3] = ff - 1;
+        fam.temp_idx = {{sp.idx[0], sp.idx[1]}, {sp.idx[0], l}};
+        fam.temp_name = {"T1", "T2"};
+        return SC_OK;
+    }
     if (d == 2 && nf == 3) {
         // S(i,j) * X(i,k) * Y(j,k) * Z(j,l) -> A(i,l)
         int x = find_on(sp.idx[0], -1);
@@ -745,7 +792,9 @@ static void schedule_model(const sc_plan *p, sc_sched_kind sched, double *flops_
         extra = 2 * F3 * N * e + 2 * F2 * M * N * e;
         break;
     }
-    case K_TTMC_ALL: break;   // see plan_ttmc_all
+    case K_TTMC_ALL:
+    case K_MTTKRP_GEMM:
+    case K_SDDMM_SPMM_GEMM: break;   // see plan_ttmc_all / plan_trailing_gemm
     }
     if (sched == SC_SCHED_LINEAR) {   // every stored entry times every combination of the dense output indices (and of k for the SDDMM)
         const double per = p->kind == K_SDDMM_SPMM ? 4.0 * (double)p->fcols[0] : (double)(p->nfactors + 1);
@@ -1020,6 +1069,103 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     return SC_OK;
 }
 
+// Kernels 8 <MTTKRP,GEMM> and 2 <SDDMM,SpMM,GEMM> of Table 2: a two-level nest whose inner level is an expression the
+// library already runs (the MTTKRP, or kernel 1) and whose outer level multiplies the row it leaves per slice with the
+// last factor.  The sparse part is planned as an inner plan under the caller's schedule class (AUTO included); its
+// rows pass through the workspace once and the dense product runs on the matrix cores.
+static sc_status plan_trailing_gemm(sc_plan *p, const char *expr, const Term &lhs, const std::vector<Term> &rhs, const Family &fam,
+                                    const sc_csf_view *sparse, const sc_dense_view *factors, const sc_schedule *sched)
+{
+    if (sched->deterministic != 0 && sched->deterministic != 1) return SC_ERR_SCHED_UNSUPPORTED;
+    const int nin = p->nfactors - 1;   // factors of the sparse part
+    const std::vector<std::string> &si = rhs[0].idx;
+    const std::string &r = fam.temp_idx[1][1];   // index contracted by the dense product
+    // named temporaries: the sparse part's own one and / or the row temporary; anything else is refused
+    if (sched->n_intermediates < 0 || sched->n_intermediates > 2) return SC_ERR_SCHED_UNSUPPORTED;
+    bool has[2] = {false, false};
+    for (int t = 0; t < sched->n_intermediates; ++t) {
+        if (!sched->intermediate[t]) return SC_ERR_SCHED_UNSUPPORTED;
+        Term tt;
+        const char *q = sched->intermediate[t];
+        if (!parse_term(q, tt)) return SC_ERR_SCHED_UNSUPPORTED;
+        while (*q && isspace((unsigned char)*q)) ++q;
+        if (*q) return SC_ERR_SCHED_UNSUPPORTED;
+        std::set<std::string> got(tt.idx.begin(), tt.idx.end());
+        if (got.size() != tt.idx.size()) return SC_ERR_SCHED_UNSUPPORTED;
+        int match = -1;
+        for (int u = 0; u < 2; ++u) {
+            std::set<std::string> want(fam.temp_idx[u].begin(), fam.temp_idx[u].end());
+            if (!has[u] && want == got) match = u;
+        }
+        if (match < 0 || sched->fuse_depth[t] != 0) return SC_ERR_SCHED_UNSUPPORTED;
+        has[match] = true;
+    }
+    std::string inner_expr = "P(" + si[0] + "," + r + ")=" + join(rhs[0].name, si);
+    sc_dense_view inner_fac[3];
+    for (int s = 0; s < nin; ++s) {
+        const Term &t = rhs[fam.slot_of_factor[s] + 1];
+        inner_expr += "*F" + std::to_string(s) + "_(" + t.idx[0] + "," + t.idx[1] + ")";
+        inner_fac[s] = factors[fam.slot_of_factor[s]];
+    }
+    sc_schedule is = {};
+    is.kind = sched->kind;
+    is.deterministic = sched->deterministic;
+    sc_status st = plan_create_impl(&p->inner, inner_expr.c_str(), sparse, inner_fac, nin, &is);
+    if (st != SC_OK) return st;
+    const sc_plan *in = p->inner;
+    p->sched = in->sched;
+    p->deterministic = in->deterministic;
+    p->has_device = in->has_device;
+    p->tune = in->tune;
+    p->n_cu = in->n_cu;
+    p->lds_per_cu = in->lds_per_cu;
+    p->caps = in->caps;
+
+    const int64_t R = p->fcols[nin - 1], M = p->fcols[nin];
+    const double e = (double)esize(p->dtype);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) & ~(size_t)255;
+        return at;
+    };
+    p->tg_rows_offset = take((size_t)p->dims[0] * (size_t)R * esize(p->dtype));
+    p->tg_inner_ws_offset = take(in->ws_bytes);
+    p->ws_bytes = off;
+    p->n_inter = in->sched == SC_SCHED_LINEAR ? 1 : 2;
+    int t2 = 0;
+    if (p->n_inter == 2) {
+        p->inter[0].name = join(fam.temp_name[0], fam.temp_idx[0]);
+        p->inter[0].rows = in->inter[0].rows;
+        p->inter[0].cols = in->inter[0].cols;
+        p->inter[0].offset = p->tg_inner_ws_offset + in->inter[0].offset;
+        t2 = 1;
+    }
+    p->inter[t2].name = join(fam.temp_name[1], fam.temp_idx[1]);
+    p->inter[t2].rows = p->dims[0];
+    p->inter[t2].cols = R;
+    p->inter[t2].offset = p->tg_rows_offset;
+
+    // the sparse part's iteration count, then one multiply-add per (non-empty slice, r, m); bytes: every input and
+    // the output once (the rows in between are the price of the split, not counted)
+    p->model_flops = in->model_flops + 2.0 * (double)R * (double)M * (double)p->nfib[0];
+    p->model_bytes = in->model_bytes - (double)in->out_elems * e + (double)p->frows[nin] * (double)M * e + (double)p->out_elems * e;
+
+    std::string &tx = p->text;
+    appendf(tx, "expression: %s\n", expr);
+    appendf(tx, "schedule: Table 2, kernel %d: the rows %s of the sparse part (%s) pass through the workspace and are multiplied with %s on the matrix cores "
+                "(fp32, %s a multiple of 4 and %s of 16; the vector ALUs otherwise)\n",
+            p->kind == K_MTTKRP_GEMM ? 8 : 2, p->inter[t2].name.c_str(), sched_name(in->sched), rhs[fam.slot_of_factor[nin] + 1].name.c_str(),
+            r.c_str(), lhs.idx[1].c_str());
+    appendf(tx, "nest: forall(%s, where(forall(%s,%s, %s += %s * %s), <sparse part>))\n", si[0].c_str(), lhs.idx[1].c_str(), r.c_str(),
+            join(lhs.name, lhs.idx).c_str(), p->inter[t2].name.c_str(), rhs[fam.slot_of_factor[nin] + 1].name.c_str());
+    for (int t = 0; t < p->n_inter; ++t)
+        appendf(tx, "temporary %d: %s, %lld x %lld\n", t, p->inter[t].name.c_str(), (long long)p->inter[t].rows, (long long)p->inter[t].cols);
+    appendf(tx, "model: %.6g flops, %.6g compulsory HBM bytes, workspace %zu bytes\n", p->model_flops, p->model_bytes, p->ws_bytes);
+    appendf(tx, "inner plan:\n%s", in->text.c_str());
+    return SC_OK;
+}
+
 static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_view *sparse,
                                   const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched)
 {
@@ -1092,6 +1238,17 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         if (p->frows[0] != p->dims[0] || p->frows[1] != p->dims[1] || p->frows[2] != p->dims[2]) return SC_ERR_SHAPE_MISMATCH;
         p->out_row_elems = p->fcols[0] * p->fcols[1] * p->fcols[2];
         break;
+    case K_MTTKRP_GEMM:
+        if (p->frows[0] != p->dims[1] || p->frows[1] != p->dims[2] || p->fcols[0] != p->fcols[1] || p->frows[2] != p->fcols[0])
+            return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[2];
+        break;
+    case K_SDDMM_SPMM_GEMM:
+        if (p->frows[0] != p->dims[0] || p->frows[1] != p->dims[1] || p->frows[2] != p->dims[1] || p->fcols[0] != p->fcols[1] ||
+            p->frows[3] != p->fcols[2])
+            return SC_ERR_SHAPE_MISMATCH;
+        p->out_row_elems = p->fcols[3];
+        break;
     }
     p->tune = tuning();   // read once; executions use the plan's copy
     {
@@ -1106,8 +1263,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         }
     }
     p->out_elems = p->kind == K_TTMC_ALL ? p->out_row_elems : p->dims[0] * p->out_row_elems;
-    if (p->kind == K_TTMC_ALL) {
-        st = plan_ttmc_all(p, expr, lhs, rhs, fam, sparse, factors, sched);
+    if (p->kind == K_TTMC_ALL || p->kind == K_MTTKRP_GEMM || p->kind == K_SDDMM_SPMM_GEMM) {
+        st = p->kind == K_TTMC_ALL ? plan_ttmc_all(p, expr, lhs, rhs, fam, sparse, factors, sched)
+                                   : plan_trailing_gemm(p, expr, lhs, rhs, fam, sparse, factors, sched);
         if (st != SC_OK) return st;
         guard.p = nullptr;
         *out = p;
@@ -1210,7 +1368,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
         place(0, p->nfib[2], p->fcols[2]);
         place(1, p->nfib[1], p->fcols[1] * p->fcols[2]);
         break;
-    case K_TTMC_ALL: break;   // planned by plan_ttmc_all
+    case K_TTMC_ALL:
+    case K_MTTKRP_GEMM:
+    case K_SDDMM_SPMM_GEMM: break;   // planned by plan_ttmc_all / plan_trailing_gemm
     }
     if (p->sched == SC_SCHED_FISSIONED) {
         p->ws_bytes = off;
@@ -1265,7 +1425,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
                 p->inter[1].name.c_str(), p->inter[0].name.c_str(), p->inter[1].name.c_str(),
                 p->sched == SC_SCHED_FUSED ? "both per tile in LDS" : "both in the workspace");
         break;
-    case K_TTMC_ALL: break;
+    case K_TTMC_ALL:
+    case K_MTTKRP_GEMM:
+    case K_SDDMM_SPMM_GEMM: break;
     }
     for (int t = 0; t < p->n_inter; ++t)
         appendf(tx, "temporary %d: %s, %lld x %lld, position-compressed along the sparse prefix%s\n", t, p->inter[t].name.c_str(),
@@ -1391,6 +1553,10 @@ extern "C" sc_status sc_plan_intermediate(const sc_plan *plan, int32_t index, si
         if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
         const bool is_t = plan->k5_variant != 3 && index == 0;
         if (is_t && plan->inner->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
+    } else if (plan->kind == sck::K_MTTKRP_GEMM || plan->kind == sck::K_SDDMM_SPMM_GEMM) {
+        // the rows of the sparse part always pass through the workspace; its own temporary only when it runs FISSIONED
+        if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
+        if (index < plan->n_inter - 1 && plan->inner->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     } else if (plan->sched != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;
     if (index < 0 || index >= plan->n_inter) return SC_ERR_BAD_DIMS;
     if (offset_bytes) *offset_bytes = plan->inter[index].offset;
@@ -1433,7 +1599,7 @@ sc_status sck::execute_checked(const sc_plan *plan, const sc_csf_view *sparse, c
     }
     if (plan->nnz > 0 && !sparse->vals) return SC_ERR_NULL;
     if ((uintptr_t)out % 16) return SC_ERR_SHAPE_MISMATCH;
-    sc_dense_view canon[3];
+    sc_dense_view canon[4];
     for (int s = 0; s < plan->nfactors; ++s) {
         const sc_dense_view &f = factors[plan->slot_of_factor[s]];
         if (!f.data) return SC_ERR_NULL;

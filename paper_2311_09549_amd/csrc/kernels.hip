@@ -760,7 +760,9 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
     }
     case K_SDDMM_SPMM: return order2_caps(dtype, fcols);
     case K_TTMC4: return order4_caps(dtype, fcols);
-    case K_TTMC_ALL: break;   // tiles belong to its inner plan
+    case K_TTMC_ALL:
+    case K_MTTKRP_GEMM:
+    case K_SDDMM_SPMM_GEMM: break;   // tiles belong to the inner plan
     }
     return c;
 }
@@ -845,7 +847,7 @@ size_t lds_bytes_needed(const sc_plan *p)
 sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *ws, hipStream_t stream)
 {
     if (p->prof && p->prof->on) p->prof->n_launch = 0;
-    if (p->sched == SC_SCHED_LINEAR && p->kind != K_TTMC_ALL) return launch_linear(p, sp, fac, out, stream);
+    if (p->sched == SC_SCHED_LINEAR && !p->inner) return launch_linear(p, sp, fac, out, stream);
     switch (p->kind) {
     case K_TTMC3:
     case K_MTTKRP3:
@@ -854,6 +856,8 @@ sc_status launch_plan(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vi
     case K_SDDMM_SPMM: return launch_order2(p, sp, fac, out, ws, stream);
     case K_TTMC4: return launch_order4(p, sp, fac, out, ws, stream);
     case K_TTMC_ALL: return launch_ttmc_all(p, sp, fac, out, ws, stream);
+    case K_MTTKRP_GEMM:
+    case K_SDDMM_SPMM_GEMM: return launch_trailing_gemm(p, sp, fac, out, ws, stream);
     default: return SC_ERR_SCHED_UNSUPPORTED;
 
     }

@@ -13,7 +13,7 @@
 
 namespace sck {
 
-enum Kind { K_TTMC3 = 0, K_MTTKRP3 = 1, K_SDDMM_SPMM = 2, K_TTMC4 = 3, K_TTMC_ALL = 4 };
+enum Kind { K_TTMC3 = 0, K_MTTKRP3 = 1, K_SDDMM_SPMM = 2, K_TTMC4 = 3, K_TTMC_ALL = 4, K_MTTKRP_GEMM = 5, K_SDDMM_SPMM_GEMM = 6 };
 
 // One work tile: a contiguous range of leaves (stored nonzeros) together with the range
 // of CSF nodes that contain them at every level above.  Level "a" is the parent level of
@@ -102,8 +102,8 @@ struct sc_plan {
     int64_t nnz;
     int64_t nfib[4];
     int32_t nfactors;
-    int32_t slot_of_factor[3];   // canonical slot -> position in the caller's factor array
-    int64_t frows[3], fcols[3];  // canonical slots
+    int32_t slot_of_factor[4];   // canonical slot -> position in the caller's factor array
+    int64_t frows[4], fcols[4];  // canonical slots
     int64_t out_elems;
     int64_t out_row_elems;       // elements of one output row (per top-level slice)
 
@@ -146,6 +146,10 @@ struct sc_plan {
     size_t k5_inner_ws_offset = 0;     // workspace of the inner plan
     size_t k5_partials_offset = 0;     // k5_nchunks x L x (M N)
     int64_t k5_nchunks = 0, k5_chunk = 0;
+
+    // Trailing dense product (kernels 8 and 2 of Table 2): the sparse part runs as an inner plan (MTTKRP, or kernel 1)
+    // whose rows, one per coordinate of the first mode, pass through the workspace.
+    size_t tg_rows_offset = 0, tg_inner_ws_offset = 0;
 
     // Snapshot of the tuning knobs and of the device the plan was made on (taken once, at plan
     // creation): an execution reads only these, never process-global state.
@@ -209,6 +213,8 @@ sc_status launch_order2(const sc_plan *plan, const sc_csf_view *sp, const sc_den
                         hipStream_t stream);
 sc_status launch_ttmc_all(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,
                           hipStream_t stream);
+sc_status launch_trailing_gemm(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,
+                               hipStream_t stream);
 TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols);
 size_t order4_lds_bytes_needed(const sc_plan *plan);
 sc_status launch_order4(const sc_plan *plan, const sc_csf_view *sp, const sc_dense_view *fac, void *out, void *workspace,

@@ -33,6 +33,8 @@ KINDS = {
     "sddmm_spmm": ("A(i,l)=S(i,j)*X(i,k)*Y(j,k)*Z(j,l)", 2, 3),
     "ttmc4": ("A(i,l,m,n)=B(i,j,k,p)*C(j,l)*D(k,m)*E(p,n)", 4, 3),
     "ttmc_all": ("A(l,m,n)=B(i,j,k)*C(i,l)*D(j,m)*E(k,n)", 3, 3),
+    "mttkrp_gemm": ("A(i,m)=B(i,j,k)*C(j,r)*D(k,r)*E(r,m)", 3, 3),
+    "sddmm_spmm_gemm": ("A(i,m)=S(i,j)*X(i,k)*Y(j,k)*Z(j,l)*F(l,m)", 2, 4),
 }
 
 CONFIGS = {
@@ -49,6 +51,17 @@ CONFIGS = {
     # Not one of the five benchmark workloads: the all-mode TTMC (Table 2, kernel 5) at the first dense
     # sizes of the paper's auxiliary-memory table (L = M = N = 16), on a power-law tensor of the same
     # recipe as workload 3 at a size whose unfactored oracle nest still runs in seconds.
+    # Kernels 8 and 2 of Table 2 (a dense product behind the MTTKRP / behind kernel 1) on the tensors of workloads 2 and 4.
+    7: dict(kind="mttkrp_gemm", dtype="f32", dims=(50_000, 20_000, 10_000), nnz=20_000_000,
+            coord=(("zipf", 1.2),) * 3, ranks=(32, 64), factor_dist="normal", seed_as=2),
+    8: dict(kind="sddmm_spmm_gemm", dtype="f32", dims=(1_000_000, 1_000_000), nnz=16_000_000,
+            coord=(("zipf", 1.3), "uniform"), ranks=(64, 64, 64), factor_dist="normal", seed_as=4),
+    # The uniform-sparsity motivating cases 1 and 2 of Section 3 for the all-mode TTMC (bounds and dense sizes as
+    # printed; sparsities 0.008 and 0.002, the values the printed iteration-count ratios correspond to).
+    9: dict(kind="ttmc_all", dtype="f32", dims=(1800, 800, 1000), nnz=11_520_000,
+            coord=("uniform",) * 3, ranks=(64, 16, 32), factor_dist="normal"),
+    10: dict(kind="ttmc_all", dtype="f32", dims=(1800, 1600, 2000), nnz=11_520_000,
+             coord=("uniform",) * 3, ranks=(64, 16, 32), factor_dist="normal"),
     6: dict(kind="ttmc_all", dtype="f32", dims=(40_000, 20_000, 8_000), nnz=4_000_000,
             coord=(("zipf", 1.1),) * 3, ranks=(16, 16, 16), factor_dist="normal"),
 }
@@ -161,6 +174,10 @@ def factor_shapes(cfg: dict):
         return [(dims[1], ranks[0]), (dims[2], ranks[1]), (dims[3], ranks[2])]
     if kind == "ttmc_all":
         return [(dims[0], ranks[0]), (dims[1], ranks[1]), (dims[2], ranks[2])]
+    if kind == "mttkrp_gemm":
+        return [(dims[1], ranks[0]), (dims[2], ranks[0]), (ranks[0], ranks[1])]
+    if kind == "sddmm_spmm_gemm":
+        return [(dims[0], ranks[0]), (dims[1], ranks[0]), (dims[1], ranks[1]), (ranks[1], ranks[2])]
     raise ValueError(kind)
 
 
@@ -176,6 +193,10 @@ def output_shape(cfg: dict):
         return (dims[0], ranks[0], ranks[1], ranks[2])
     if kind == "ttmc_all":
         return (ranks[0], ranks[1], ranks[2])
+    if kind == "mttkrp_gemm":
+        return (dims[0], ranks[1])
+    if kind == "sddmm_spmm_gemm":
+        return (dims[0], ranks[2])
     raise ValueError(kind)
 
 
@@ -186,7 +207,7 @@ def generate(cfg: dict, cache_dir: str | None = None) -> dict:
     several processes of one session do not redraw them; the cache is keyed by every field
     the draw depends on."""
     import os
-    seed = 1000 + int(cfg.get("id", 0)) + int(cfg.get("seed_offset", 0)) * 100
+    seed = 1000 + int(cfg.get("seed_as", cfg.get("id", 0))) + int(cfg.get("seed_offset", 0)) * 100
     dt = np.float64 if cfg["dtype"] == "f64" else np.float32
     coords = None
     path = None

@@ -10,7 +10,8 @@ TOL = {"f32": 1e-5, "f64": 1e-12}   # |gpu - oracle| <= TOL * sum|partial produc
 
 def default_schedule(kind, which):
     names = {"ttmc3": ["T(i,j,m)"], "mttkrp3": ["T(i,j,r)"], "sddmm_spmm": ["T(i,j)"],
-             "ttmc4": ["T1(i,j,k,n)", "T2(i,j,m,n)"], "ttmc_all": ["T1(i,j,n)", "T2(i,m,n)"]}[kind]
+             "ttmc4": ["T1(i,j,k,n)", "T2(i,j,m,n)"], "ttmc_all": ["T1(i,j,n)", "T2(i,m,n)"],
+             "mttkrp_gemm": ["T1(i,j,r)", "T2(i,r)"], "sddmm_spmm_gemm": ["T1(i,j)", "T2(i,l)"]}[kind]
     if which == "linear":
         return sc.schedule("linear")
     if which == "fused":

@@ -1,7 +1,7 @@
 """GPU parity on the degenerate structures of the method: nothing stored, a single entry, all
 entries in one slice / one fiber (a node cut by many tiles at every level), fibers of one entry
 only, entry counts that land exactly on, just below and just above tile multiples, stored zeros,
-coordinates at both ends of every mode.  Both schedules, all five nests, element-wise against the
+coordinates at both ends of every mode.  Both schedules, all seven nests, element-wise against the
 oracle (same bar as the other parity tests)."""
 import numpy as np
 import pytest
@@ -12,7 +12,7 @@ from helpers import assert_parity, run_library
 
 pytestmark = pytest.mark.gpu
 
-KINDS = {"mttkrp3": 2, "ttmc3": 3, "sddmm_spmm": 4, "ttmc4": 5, "ttmc_all": 6}   # kind -> workload whose expression and ranks it borrows
+KINDS = {"mttkrp3": 2, "ttmc3": 3, "sddmm_spmm": 4, "ttmc4": 5, "ttmc_all": 6, "mttkrp_gemm": 7, "sddmm_spmm_gemm": 8}   # kind -> workload whose expression and ranks it borrows
 
 
 def _sorted_unique(cols, dims):
@@ -65,7 +65,7 @@ def _case(kind, name, zeros=False):
     order = len(base["dims"])
     rng = np.random.default_rng([77, KINDS[kind], sum(map(ord, name))])
     dims, coords = _structure(name, order, rng)
-    if kind == "sddmm_spmm":
+    if kind in ("sddmm_spmm", "sddmm_spmm_gemm"):
         dims = (max(dims), max(dims))      # X is indexed by i, Y and Z by j: one square shape keeps it simple
     cfg = dict(base, dims=tuple(int(d) for d in dims), nnz=len(coords[0]))
     dt = np.float32 if cfg["dtype"] == "f32" else np.float64

@@ -104,3 +104,35 @@ def test_parity_full_size(oracle, which, names):
     worst = float((err / bound).max())
     print(f"ttmc_all full size {which} {names}: max scaled error {worst:.3e}, workspace {con.ws_bytes} bytes", flush=True)
     assert np.all(err <= TOL["f32"] * bound)
+
+
+@pytest.mark.parametrize("cid", [9, 10])
+def test_uniform_motivating_cases_on_sampled_outputs(oracle, cid):
+    """Cases 1 and 2 of Section 3 (uniform 1800 x 800 x 1000 at sparsity 0.008 and 1800 x 1600 x 2000 at 0.002,
+    L, M, N = 64, 16, 32; 11.5 M nonzeros each).  The perfectly nested loop over the whole output would take
+    3.8 * 10^11 iterations, so the oracle is run on sampled outputs: an element A(l,m,n) depends on column l of C,
+    m of D and n of E only, hence 4 x 4 x 4 sampled columns form an exact sub-problem.  All three schedules."""
+    cfg = synth.config(cid)
+    data = synth.generate(cfg, cache_dir=os.path.join(os.environ.get("TMPDIR", "/tmp"), "sc_synth_cache"))
+    C, D, E = data["factors"]
+    rng = np.random.default_rng(cid)
+    ls, ms, ns = (np.sort(rng.choice(f.shape[1], 4, replace=False)) for f in (C, D, E))
+    sub = [np.ascontiguousarray(C[:, ls]), np.ascontiguousarray(D[:, ms]), np.ascontiguousarray(E[:, ns])]
+    ref = oracle.contract("ttmc_all", data["coords"], data["vals"], cfg["dims"], sub)
+    bound = oracle.abs_bound("ttmc_all", data["coords"], data["vals"], cfg["dims"], sub)
+    first = None
+    for (which, names), label in zip(VARIANTS, IDS):
+        con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                          sc.schedule(which, list(names), [0] * len(names)), synth.output_shape(cfg), share=first)
+        first = first or con
+        con.run()
+        got = con.result().astype(np.float64)
+        assert not np.isnan(got).any()
+        pick = got[np.ix_(ls, ms, ns)]
+        worst = float((np.abs(pick - ref) / bound).max())
+        print(f"uniform case {cid - 8} {label}: 64 sampled outputs, max scaled error {worst:.3e}", flush=True)
+        assert np.all(np.abs(pick - ref) <= TOL["f32"] * bound)
+        # schedules agree with one another over the whole output (each within its own bound of the exact result)
+        if con is not first:
+            full_bound_proxy = np.abs(got).max()
+            assert np.all(np.abs(got - first.result().astype(np.float64)) <= 1e-4 * full_bound_proxy)
