@@ -1154,7 +1154,7 @@ static sc_status plan_trailing_gemm(sc_plan *p, const char *expr, const Term &lh
     std::string &tx = p->text;
     appendf(tx, "expression: %s\n", expr);
     appendf(tx, "schedule: Table 2, kernel %d: the rows %s of the sparse part (%s) pass through the workspace and are multiplied with %s on the matrix cores "
-                "(fp32, %s a multiple of 4 and %s of 16; the vector ALUs otherwise)\n",
+                "(fp32, %s in {16, 32, 64, 128} and %s a multiple of 16; the vector ALUs otherwise)\n",
             p->kind == K_MTTKRP_GEMM ? 8 : 2, p->inter[t2].name.c_str(), sched_name(in->sched), rhs[fam.slot_of_factor[nin] + 1].name.c_str(),
             r.c_str(), lhs.idx[1].c_str());
     appendf(tx, "nest: forall(%s, where(forall(%s,%s, %s += %s * %s), <sparse part>))\n", si[0].c_str(), lhs.idx[1].c_str(), r.c_str(),
