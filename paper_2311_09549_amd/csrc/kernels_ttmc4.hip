@@ -253,6 +253,17 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
         // ---- the next tile's reads go out now and land while this tile is worked on ----
         Stage sn;
         if (tile + 1 < lastp1) issue(tn, sn);
+        // FUSED: the C rows of the tile's f2 fibers are fetched ahead of the consumer (16 lanes per row, rows
+        // tid / 16 + 16 r; their offsets are in LDS by now) and are parked in the space of the T1 rows as soon
+        // as those are dead.  The consumer then reads both operands of its MFMAs from LDS instead of gathering
+        // C in its inner loop, where the gather's latency was paid once per block of fibers.
+        const bool c_in_lds = MODE == 0 && a.tb * 16 <= (a.ta + 1) * RS1;
+        float cval[T4_TR2];
+        if (c_in_lds) {
+            const char *Cl = reinterpret_cast<const char *>(a.C) + min(tid % 16, L - 1) * 4;
+#pragma unroll
+            for (int r = 0; r < T4_TR2; ++r) cval[r] = *reinterpret_cast<const float *>(Cl + coff2_s[min(tid / 16 + r * T4_G2, nb - 1)]);
+        }
 
         // ---- marks of both walks ----
         if (MODE == 0) leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
@@ -319,6 +330,14 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                 st.owner = st.head && (rowp != row0 || ge == na);
             }
             __syncthreads();
+            if (c_in_lds) {   // the T1 rows are dead: their space takes the C rows (l >= L padded with zeros)
+                const int l = tid % 16;
+#pragma unroll
+                for (int r = 0; r < T4_TR2; ++r) {
+                    const int f = tid / 16 + r * T4_G2;
+                    if (f < nb) row1_s[f * 16 + l] = l < L ? cval[r] : 0.f;
+                }
+            }
             leaf_combine<float, T4_W2>(row2_s, carry2_s, bb_s, chunk_lr2, st, g, li, q2);
             __syncthreads();
         }
@@ -378,7 +397,9 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                         const int lf = fb + 4 * ub + kk;
                         const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
                         const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
-                        const float cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
+                        float cvr;
+                        if (MODE == 0 && c_in_lds) cvr = row1_s[lfc * 16 + col];
+                        else cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
                         tv[ub] = lf < f1 ? tvr : 0.f;
                         cv[ub] = lval ? cvr : 0.f;
                     }
