@@ -234,7 +234,7 @@ def main() -> int:
         return rec
 
     K5_VARIANTS = [("schedule2_fused", "fused", []), ("schedule2_fissioned", "fissioned", ["T1(i,j,n)", "T2(i,m,n)"]),
-                   ("schedule1", "fissioned", ["T(i,j,n)"]), ("schedule3", "fused", ["T(i,m,n)"])]
+                   ("schedule1", "fissioned", ["T(i,j,n)"]), ("schedule3", "fused", ["T(i,m,n)"]), ("linear", "linear", [])]
     CLASS_VARIANTS = [("fused", "fused", []), ("fissioned", "fissioned", []), ("linear", "linear", [])]
 
     def bench_next(cid, text, variants, steps, linear_flops=None, with_oracle=True, cfg=None):

@@ -937,11 +937,15 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
         auto_variant = cands[best].variant;
         sched = &picked;
     }
-    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED) return SC_ERR_SCHED_UNSUPPORTED;   // no unfactored nest for this kernel
+    if (sched->kind != SC_SCHED_FUSED && sched->kind != SC_SCHED_FISSIONED && sched->kind != SC_SCHED_LINEAR) return SC_ERR_SCHED_UNSUPPORTED;
     p->sched = sched->kind;
     p->deterministic = sched->deterministic == 1;
     // which schedule: match the named temporaries against the derived index sets
     int variant = auto_variant ? auto_variant : 2;
+    if (sched->kind == SC_SCHED_LINEAR) {   // Figure 2a: no temporary (the reduction over the grid is ordered, so the result is reproducible either way)
+        if (sched->n_intermediates != 0) return SC_ERR_SCHED_UNSUPPORTED;
+        variant = 0;
+    }
     if (sched->n_intermediates < 0 || sched->n_intermediates > 2) return SC_ERR_SCHED_UNSUPPORTED;
     if (sched->n_intermediates) {
         bool has[2] = {false, false};
@@ -977,8 +981,8 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
                                    lhs.idx[1] + ")*E_(" + si[2] + "," + lhs.idx[2] + ")";
     const sc_dense_view inner_fac[2] = {factors[fam.slot_of_factor[1]], factors[fam.slot_of_factor[2]]};
     sc_schedule is = {};
-    is.kind = variant == 3 ? SC_SCHED_LINEAR : variant == 1 ? SC_SCHED_FISSIONED : sched->kind;
-    is.deterministic = variant == 3 ? 0 : sched->deterministic;
+    is.kind = (variant == 3 || variant == 0) ? SC_SCHED_LINEAR : variant == 1 ? SC_SCHED_FISSIONED : sched->kind;
+    is.deterministic = (variant == 3 || variant == 0) ? 0 : sched->deterministic;
     sc_status st = plan_create_impl(&p->inner, inner_expr.c_str(), sparse, inner_fac, 2, &is);
     if (st != SC_OK) return st;
     const sc_plan *in = p->inner;
@@ -992,8 +996,8 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     const double S = (double)p->nfib[0], F = (double)p->nfib[1];
     const double L = (double)p->fcols[0], M = (double)p->fcols[1], N = (double)p->fcols[2];
     // reduction over slices (fibers for schedule 1): contiguous chunks, one slot each
-    const int64_t units = variant == 1 ? p->nfib[1] : p->dims[0];
-    const int64_t per = variant == 1 ? 1024 : 64;
+    const int64_t units = variant <= 1 ? p->nfib[1] : p->dims[0];
+    const int64_t per = variant == 1 ? 1024 : variant == 0 ? 256 : 64;
     p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>((units + per - 1) / per, (int64_t)p->n_cu * 2));
     p->k5_chunk = std::max<int64_t>(1, (units + p->k5_nchunks - 1) / p->k5_nchunks);
     p->k5_nchunks = std::max<int64_t>(1, (units + p->k5_chunk - 1) / p->k5_chunk);
@@ -1003,22 +1007,22 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
         off += (bytes + 255) & ~(size_t)255;
         return at;
     };
-    p->k5_s_offset = variant == 1 ? 0 : take((size_t)p->dims[0] * (size_t)(p->fcols[1] * p->fcols[2]) * esize(p->dtype));
-    p->k5_inner_ws_offset = take(in->ws_bytes);
+    p->k5_s_offset = variant <= 1 ? 0 : take((size_t)p->dims[0] * (size_t)(p->fcols[1] * p->fcols[2]) * esize(p->dtype));
+    p->k5_inner_ws_offset = take(variant == 0 ? 0 : in->ws_bytes);
     p->k5_partials_offset = take((size_t)p->k5_nchunks * (size_t)p->out_elems * esize(p->dtype));
     p->ws_bytes = off;
 
     // temporaries as the caller can read them back after a FISSIONED execution: t rows (one per fiber) and
     // the per-slice tiles (one row per coordinate of the first mode, empty slices included)
-    p->n_inter = variant == 2 ? 2 : 1;
+    p->n_inter = variant == 2 ? 2 : variant == 0 ? 0 : 1;
     const int t2 = variant == 2 ? 1 : 0;
-    if (variant != 3) {
+    if (variant == 1 || variant == 2) {
         p->inter[0].name = join(fam.temp_name[0], fam.temp_idx[0]);
         p->inter[0].rows = p->nfib[1];
         p->inter[0].cols = p->fcols[2];
         p->inter[0].offset = p->k5_inner_ws_offset + (in->sched == SC_SCHED_FISSIONED ? in->inter[0].offset : 0);
     }
-    if (variant != 1) {
+    if (variant >= 2) {
         p->inter[t2].name = join(fam.temp_name[1], fam.temp_idx[1]);
         p->inter[t2].rows = p->dims[0];
         p->inter[t2].cols = p->fcols[1] * p->fcols[2];
@@ -1027,7 +1031,8 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
 
     // iteration counts of the nests as Table 2 writes them (multiply = 1, add = 1)
     double flops = 0;
-    if (variant == 1) flops = 2 * N * nnz + 3 * L * M * N * F;
+    if (variant == 0) flops = 4 * L * M * N * nnz;
+    else if (variant == 1) flops = 2 * N * nnz + 3 * L * M * N * F;
     else if (variant == 2) flops = 2 * N * nnz + 2 * M * N * F + 2 * L * M * N * S;
     else flops = 3 * M * N * nnz + 2 * L * M * N * S;
     double fac_bytes = 0;
@@ -1043,10 +1048,15 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
                *En = rhs[fam.slot_of_factor[2] + 1].name.c_str();
     const char *i_ = si[0].c_str(), *j_ = si[1].c_str(), *k_ = si[2].c_str();
     const char *l_ = lhs.idx[0].c_str(), *m_ = lhs.idx[1].c_str(), *n_ = lhs.idx[2].c_str();
-    appendf(tx, "schedule: Table 2, kernel 5, schedule %d (%s)\n", variant,
-            p->sched == SC_SCHED_FUSED ? "FUSED: the temporaries of the sparse part stay on chip" : "FISSIONED: t in the workspace");
+    if (variant == 0)
+        appendf(tx, "schedule: LINEAR (Figure 2a: the perfectly nested loop, no temporary)\n");
+    else
+        appendf(tx, "schedule: Table 2, kernel 5, schedule %d (%s)\n", variant,
+                p->sched == SC_SCHED_FUSED ? "FUSED: the temporaries of the sparse part stay on chip" : "FISSIONED: t in the workspace");
     tx += choice_text;
-    if (variant == 1)
+    if (variant == 0)
+        appendf(tx, "nest: forall(%s,%s,%s,%s,%s',%s', A += %s * %s * %s * %s)\n", l_, m_, n_, i_, j_, k_, rhs[0].name.c_str(), Cn, Dn, En);
+    else if (variant == 1)
         appendf(tx, "nest: forall(%s,%s',%s, where(forall(%s,%s, A += t * %s * %s), forall(%s', t += %s * %s)))\n", i_, j_, n_, m_, l_, Cn, Dn, k_,
                 rhs[0].name.c_str(), En);
     else if (variant == 2)
@@ -1055,7 +1065,10 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     else
         appendf(tx, "nest: forall(%s,%s,%s, where(forall(%s, A += t * %s), forall(%s',%s', t += %s * %s * %s)))\n", i_, m_, n_, l_, Cn, j_, k_,
                 rhs[0].name.c_str(), Dn, En);
-    if (variant == 1)
+    if (variant == 0)
+        appendf(tx, "the output has no sparse index: %lld workgroups sum contiguous chunks of fibers, their partial tiles are added in chunk order\n",
+                (long long)p->k5_nchunks);
+    else if (variant == 1)
         appendf(tx, "the output has no sparse index: the rows t(%s,%s,:) pass through the workspace once and are reduced over all fibers by %lld workgroups, "
                     "whose partial tiles are added in chunk order (always reproducible)\n", i_, j_, (long long)p->k5_nchunks);
     else

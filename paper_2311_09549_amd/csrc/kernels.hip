@@ -53,13 +53,23 @@ struct Order3Args {
     int32_t tn, ta, tb;  // caps used to carve LDS
 };
 
+// `crow_l`: columns of C when the consumer runs on the matrix cores (it then keeps the tile's C rows in LDS), else 0
 template <typename T>
-__host__ __device__ constexpr size_t order3_lds_bytes(int W, int tn, int ta)
+__host__ __device__ constexpr size_t order3_lds_bytes(int W, int tn, int ta, int crow_l = 0)
 {
-    return leaf_walk_lds_bytes<T>(W, tn, ta, NT) + (size_t)(3 * ta + 8) * 4 + 64;
+    return leaf_walk_lds_bytes<T>(W, tn, ta, NT) + (size_t)(3 * ta + 8) * 4 + 64 + (crow_l ? (size_t)ta * (crow_l + 4) * 4 + 16 : 0);
 }
 
-template <typename T, int W, int MODE>
+// fp32 outer products whose ranks are multiples of the 16 x 16 MFMA tile (other than the 16 x 16 case, which has a
+// kernel of its own) run the consumer of order3_kernel on the matrix cores.
+__host__ __device__ constexpr bool order3_mfma_ranks(int L, int W)
+{
+    return W % 16 == 0 && (L == 16 || L == 32 || L == 64 || L == 128) && !(L == 16 && W == 16);
+}
+
+typedef float o3_floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename T, int W, int MODE, bool MF = false>
 __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
 {
     constexpr int VEC = VecWidth<T>::value;
@@ -80,6 +90,8 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     int *crda_s = chunk_lr + G;          // ta: j of each fiber
     int *bb_s = crda_s + a.ta;           // ta + 2: first fiber of each slice (tile-local)
     int *crdb_s = bb_s + a.ta + 2;       // ta: output row of each slice
+    // MF: C rows of the tile's fibers, ta rows of L + 4 floats (16-byte aligned)
+    float *crow_s = reinterpret_cast<float *>(smem + ((order3_lds_bytes<T>(W, a.tn, a.ta) + 15) & ~(size_t)15));
 
     const TileRec t = a.tiles[blockIdx.x];
     const int tid = threadIdx.x;
@@ -117,6 +129,18 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     for (int i = tid; i < nb; i += NT) crdb_s[i] = a.crd1[t.b0 + i];
     __syncthreads();
 
+    if constexpr (MF) {
+        // C rows -> LDS, 16 bytes per lane, consecutive lanes on consecutive pieces of a row
+        const int LS = a.L + 4, vpr = a.L / 4;
+        const int sh = vpr == 4 ? 2 : vpr == 8 ? 3 : vpr == 16 ? 4 : 5;
+        const float *Cg = static_cast<const float *>(a.C);
+#pragma unroll 4
+        for (int idx = tid; idx < (na << sh); idx += NT) {
+            const int f = idx >> sh, q4 = (idx & (vpr - 1)) * 4;
+            *reinterpret_cast<o3_floatx4 *>(crow_s + f * LS + q4) = *reinterpret_cast<const o3_floatx4 *>(Cg + (int64_t)crda_s[f] * a.ldC + q4);
+        }
+    }
+
     // ---- producer: the shared leaf walk, leaves -> rows of T in LDS ----
     if (MODE == 0) {
         leaf_mark(rec_s, ba_s, chunk_lr, tid, NT, na, q);
@@ -133,6 +157,47 @@ __global__ void __launch_bounds__(NT) order3_kernel(Order3Args a)
     const T *C = static_cast<const T *>(a.C);
     T *A = static_cast<T *>(a.A);
     const int L = a.L;
+    if constexpr (MF) {
+        // Matrix cores: A(i, l, m) = sum_f C(j_f, l) * T(f, m) per slice is an (L x Kf) * (Kf x W) product.  A
+        // wavefront owns output tiles of 16 (l) x 16 (m) for every slice of the work tile, so no sums cross
+        // wavefronts; four fibers per v_mfma_f32_16x16x4_f32, operand A = T (m along the rows), operand B = the
+        // C rows (l along the columns), both read from LDS; a lane ends up with four consecutive m of one l.
+        if (MODE != 0) __syncthreads();   // (the fused path has passed a barrier since the C rows were written)
+        const int lane = tid % 64, wave = tid / 64;
+        const int kk = lane / 16, col = lane % 16;
+        const int LS = L + 4;
+        constexpr int NTM = W / 16;
+        const int ntile = (L / 16) * NTM;
+        float *Af = reinterpret_cast<float *>(A);
+        for (int ot = wave; ot < ntile; ot += NT / 64) {
+            const int lt = ot / NTM, mt = ot % NTM;
+            for (int ls = 0; ls < nb; ++ls) {
+                const int f0 = max(bb_s[ls], ls == 0 ? cf0 : 0), f1 = bb_s[ls + 1];
+                const bool first_shared = ls == 0 && (t.flags & 4), last_shared = ls == nb - 1 && (t.flags & 8);
+                if (f0 >= f1 && !(a.partials && (first_shared || last_shared))) continue;
+                o3_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                for (int fb = f0; fb < f1; fb += 4) {
+                    const int lf = fb + kk;
+                    const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
+                    const float tvr = reinterpret_cast<const float *>(row_s)[lfc * RS + mt * 16 + col];
+                    const float cv = crow_s[lfc * LS + lt * 16 + col];
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(lf < f1 ? tvr : 0.f, cv, acc, 0, 0, 0);
+                }
+                // acc[r] = A(l = 16 lt + col, m = 16 mt + 4 kk + r)
+                const int64_t eoff = (int64_t)(lt * 16 + col) * W + mt * 16 + 4 * kk;
+                if (!first_shared && !last_shared) {
+                    *reinterpret_cast<o3_floatx4 *>(Af + (int64_t)crdb_s[ls] * L * W + eoff) = acc;
+                } else if (a.partials) {
+                    *reinterpret_cast<o3_floatx4 *>(static_cast<float *>(a.partials) + (int64_t)(first_shared ? t.pad[0] : t.pad[1]) * L * W + eoff) = acc;
+                } else {
+                    float *dst = Af + (int64_t)crdb_s[ls] * L * W + eoff;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) atomic_add(dst + r, acc[r]);
+                }
+            }
+        }
+        return;
+    }
     for (int e = tid; e < L * W; e += NT) {
         const int l = e / W, m = e % W;
         for (int ls = 0; ls < nb; ++ls) {
@@ -661,7 +726,9 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
     a.A = out;
     a.partials = p->deterministic && ws ? static_cast<char *>(ws) + p->det_top.slot_offset : nullptr;
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
-    const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta);
+    constexpr bool can_mf = sizeof(T) == 4 && W % 16 == 0;
+    const bool mf = can_mf && !had && !mfma && order3_mfma_ranks(a.L, W);
+    const size_t lds = order3_lds_bytes<T>(W, a.tn, a.ta, mf ? a.L : 0);
     if (p->sched == SC_SCHED_FUSED) {
         if (had) {
             ln.begin("mttkrp3_fused");
@@ -674,6 +741,14 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             if (ln.status != SC_OK) return ln.status;
             return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
+            if constexpr (can_mf) {
+                if (mf) {
+                    ln.begin("ttmc3_fused_mfma_tiles");
+                    order3_kernel<T, W, 0, true><<<ntiles, NT, lds, stream>>>(a);
+                    ln.end();
+                    return launch_fixup(p, ln, p->det_top, ws, out);
+                }
+            }
             ln.begin("ttmc3_fused_valu");
             order3_kernel<T, W, 0><<<ntiles, NT, lds, stream>>>(a);
         }
@@ -697,6 +772,14 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             if (ln.status != SC_OK) return ln.status;
             return launch_fixup(p, ln, p->det_top, ws, out);
         } else {
+            if constexpr (can_mf) {
+                if (mf) {
+                    ln.begin("ttmc3_consume_mfma_tiles");
+                    order3_kernel<T, W, 2, true><<<ntiles, NT, lds, stream>>>(a);
+                    ln.end();
+                    return launch_fixup(p, ln, p->det_top, ws, out);
+                }
+            }
             ln.begin("ttmc3_consume_valu");
             order3_kernel<T, W, 2><<<ntiles, NT, lds, stream>>>(a);
         }
@@ -748,6 +831,11 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.tn = 512;
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
+            if (dtype == SC_F32 && order3_mfma_ranks((int)fcols[0], (int)w)) {
+                // matrix-core consumer of the general kernel: T rows and C rows of a tile share about 28 KB
+                c.ta = (int32_t)std::max<int64_t>(16, std::min<int64_t>(256, (28 * 1024) / ((w + 4 + fcols[0] + 4) * 4)));
+                c.tb = c.ta;
+            }
             if (dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
                 // matrix-core kernel: measured best on the 30 M-nonzero workload; 216 rows keep the
                 // workgroup's LDS just below the size at which five fit a compute unit
@@ -833,8 +921,9 @@ size_t lds_bytes_needed(const sc_plan *p)
         }
         {
             // general outer-product kernel, fused or as the consumer behind the leaf traversal
+            const bool mf = p->kind == K_TTMC3 && p->dtype == SC_F32 && order3_mfma_ranks((int)p->fcols[0], (int)producer_width(p));
             const size_t own = p->dtype == SC_F64 ? order3_lds_bytes<double>((int)producer_width(p), p->caps.tn, p->caps.ta)
-                                                  : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta);
+                                                  : order3_lds_bytes<float>((int)producer_width(p), p->caps.tn, p->caps.ta, mf ? (int)p->fcols[0] : 0);
             if (p->sched != SC_SCHED_FISSIONED) return own;
             return std::max(own, leaf_traverse_lds_bytes(p, (int)producer_width(p)));
         }

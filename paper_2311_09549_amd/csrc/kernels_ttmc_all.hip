@@ -132,6 +132,65 @@ __global__ void __launch_bounds__(NT) fiber_reduce_kernel(K5Args a)
     }
 }
 
+// LINEAR: the perfectly nested loop of Figure 2a, nothing factored out: every stored entry is multiplied with one
+// element of each of the three factors for every (l, m, n).  A workgroup walks a contiguous chunk of fibers; a
+// thread owns KB_L output elements e = (l, m, n) of one block of KB_L * NT elements (blockIdx.y) and keeps their
+// sums in registers; the partial tiles of the chunks are added by sum_partials like those of the other schedules.
+template <typename T>
+__global__ void __launch_bounds__(NT) linear_all_kernel(K5Args a, const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd3,
+                                                        const T *__restrict__ vals, const T *__restrict__ E, int64_t ldE)
+{
+    __shared__ int s_first;
+    const int tid = threadIdx.x;
+    const int64_t elems = (int64_t)a.L * a.MN;
+    const int64_t f0 = (int64_t)blockIdx.x * a.chunk, f1 = min(f0 + a.chunk, a.rows);
+    const T *C = static_cast<const T *>(a.C);
+    const T *D = static_cast<const T *>(a.D);
+    if (tid == 0) {   // slice that holds fiber f0: last s with pos2[s] <= f0
+        int lo = 0, hi = a.nslices;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (a.pos2[mid] <= f0) lo = mid; else hi = mid;
+        }
+        s_first = lo;
+    }
+    __syncthreads();
+    int l[KB_L], m[KB_L], n[KB_L];
+    bool ok[KB_L];
+    T acc[KB_L];
+#pragma unroll
+    for (int r = 0; r < KB_L; ++r) {
+        const int64_t e = ((int64_t)blockIdx.y * KB_L + r) * NT + tid;
+        ok[r] = e < elems;
+        const int64_t ec = ok[r] ? e : 0;
+        l[r] = (int)(ec / a.MN);
+        m[r] = (int)((ec % a.MN) / a.N);
+        n[r] = (int)(ec % a.N);
+        acc[r] = T(0);
+    }
+    int s = s_first;
+    int64_t s_end = a.pos2[s + 1];
+    int64_t i = a.crd1[s];
+    for (int64_t f = f0; f < f1; ++f) {
+        if (f >= s_end) {   // uniform: every thread walks the same fibers
+            ++s;
+            s_end = a.pos2[s + 1];
+            i = a.crd1[s];
+        }
+        const int64_t j = a.crd2[f];
+        for (int z = pos3[f]; z < pos3[f + 1]; ++z) {
+            const int64_t k = crd3[z];
+            const T v = vals[z];
+#pragma unroll
+            for (int r = 0; r < KB_L; ++r) acc[r] += v * C[i * a.ldC + l[r]] * D[j * a.ldD + m[r]] * E[k * ldE + n[r]];
+        }
+    }
+    T *P = static_cast<T *>(a.partials) + (int64_t)blockIdx.x * elems;
+#pragma unroll
+    for (int r = 0; r < KB_L; ++r)
+        if (ok[r]) P[((int64_t)blockIdx.y * KB_L + r) * NT + tid] = acc[r];
+}
+
 // A(e) = sum over chunks b of partial(b, e), in an order fixed by the launch: a workgroup owns 64 output
 // elements, its four wavefronts take the chunks round robin and their sums are added in wavefront order.
 // Every output element is written.
@@ -175,7 +234,17 @@ sc_status run_ttmc_all(const sc_plan *p, const sc_csf_view *sp, const sc_dense_v
         launch_fill<T>(ln, static_cast<T *>(out), elems, "fill_output");
         return ln.status;
     }
-    if (p->k5_variant == 1) {
+    if (p->k5_variant == 0) {
+        // the unfactored nest over all stored entries
+        a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1];
+        a.rows = p->nfib[1];
+        a.nslices = (int32_t)p->nfib[0];
+        const dim3 lgrid((unsigned)p->k5_nchunks, (unsigned)((elems + (int64_t)KB_L * NT - 1) / ((int64_t)KB_L * NT)), 1);
+        ln.begin("ttmc_all_linear_nest");
+        linear_all_kernel<T><<<lgrid, NT, 0, stream>>>(a, sp->pos[2], sp->crd[2], static_cast<const T *>(sp->vals),
+                                                       static_cast<const T *>(fac[2].data), fac[2].ld);
+        ln.end();
+    } else if (p->k5_variant == 1) {
         // t(f,:) per fiber by the leaf traversal of the inner plan (its first FISSIONED kernel), then the fiber reduction
         Launcher li{in, stream};
         void *T1 = wsb + p->k5_inner_ws_offset + in->inter[0].offset;

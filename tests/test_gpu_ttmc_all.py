@@ -17,8 +17,8 @@ from helpers import TOL, assert_parity
 pytestmark = pytest.mark.gpu
 
 # (schedule class, named temporaries): schedule 2 (default), 2, 1, 3 of Table 2
-VARIANTS = [("fused", ()), ("fissioned", ("T1(i,j,n)", "T2(i,m,n)")), ("fissioned", ("T(i,j,n)",)), ("fused", ("T(i,m,n)",))]
-IDS = ["schedule2-fused", "schedule2-fissioned", "schedule1", "schedule3"]
+VARIANTS = [("fused", ()), ("fissioned", ("T1(i,j,n)", "T2(i,m,n)")), ("fissioned", ("T(i,j,n)",)), ("fused", ("T(i,m,n)",)), ("linear", ())]
+IDS = ["schedule2-fused", "schedule2-fissioned", "schedule1", "schedule3", "linear"]
 
 
 def _contraction(cfg, data, which, names, det=False):

@@ -456,7 +456,9 @@ def test_all_mode_ttmc_plans():
     plan = sc.plan_create("Out(a,b,c)=X(p,q,r)*W(r,c)*U(p,a)*V(q,b)", csf, [data["factors"][2], data["factors"][0], data["factors"][1]],
                           sc.schedule("fused"))
     assert "kernel 5, schedule 2" in sc.plan_describe(plan)
-    bad = [("linear", []), ("fused", ["T(i,j,n)"]), ("fissioned", ["T(i,m,n)"]), ("fused", ["T(i,j,m)"]), ("fused", ["T(i,j,n)", "T(i,j,n)"])]
+    lin = sc.plan_create(cfg["expr"], csf, data["factors"], sc.schedule("linear"))
+    assert sc.plan_model(lin)[0] == 4 * L * M * N * nnz and "Figure 2a" in sc.plan_describe(lin)
+    bad = [("linear", ["T(i,m,n)"]), ("fused", ["T(i,j,n)"]), ("fissioned", ["T(i,m,n)"]), ("fused", ["T(i,j,m)"]), ("fused", ["T(i,j,n)", "T(i,j,n)"])]
     for which, names in bad:
         assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule(which, names, [0] * len(names))) == "SC_ERR_SCHED_UNSUPPORTED"
     assert _status(sc.plan_create, cfg["expr"], csf, data["factors"], sc.schedule("fused", ["T(i,m,n)"], [0], deterministic=True)) == "SC_ERR_SCHED_UNSUPPORTED"
