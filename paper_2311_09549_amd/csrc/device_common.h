@@ -225,6 +225,7 @@ sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void 
 // Order-4 TTM chain on matrix cores (fp32, M = N = 8, L <= 16; its own kernel file): mode 0 the FUSED schedule,
 // modes 1 and 2 the second and third kernel of the FISSIONED one.
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p);
+WalkShape ttmc4_mfma_walk_shape();
 bool ttmc4_mfma_caps_ok(const sc_plan *p);
 sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
                             void *T2, void *out, void *partials);

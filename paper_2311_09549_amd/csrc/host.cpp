@@ -462,6 +462,60 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
     }
 }
 
+// Walk tables of a plan (see WalkTables): the coordinate arrays of the two lowest levels with the
+// end-of-node bits folded in, and per tile the node at the head of every lane group's chunk.  `order`
+// is the device tile table.
+sc_status build_walk_tables(sc_plan *p, const sc_csf_view *v, const HostCsf &h, const std::vector<TileRec> &order)
+{
+    WalkTables &w = p->walk;
+    const int d = v->order;
+    if (w.shape.levels <= 0 || !h.have_crd || order.empty()) return SC_OK;
+    try {
+        for (int lv = 0; lv < w.shape.levels; ++lv) {
+            const int m = d - 1 - lv;                 // CSF level of the children
+            const int64_t n = v->nfib[m], nparent = v->nfib[m - 1];
+            std::vector<uint32_t> rec((size_t)n);
+            for (int64_t c = 0; c < n; ++c) rec[(size_t)c] = (uint32_t)h.crd[m][c];
+            for (int64_t f = 0; f < nparent; ++f) rec[(size_t)h.pos[m][f + 1] - 1] |= 0x80000000u;
+            if (hipMalloc((void **)&w.d_rec[lv], sizeof(uint32_t) * (size_t)n) != hipSuccess) return SC_ERR_DEVICE;
+            if (hipMemcpy(w.d_rec[lv], rec.data(), sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
+        }
+        const int g0 = w.shape.groups[0], g1 = w.shape.levels > 1 ? w.shape.groups[1] : 0;
+        w.heads_per_tile = (g0 + g1 + 1) / 2 * 2;
+        std::vector<uint16_t> heads(order.size() * (size_t)w.heads_per_tile, 0);
+        for (size_t t = 0; t < order.size(); ++t) {
+            const TileRec &tr = order[t];
+            uint16_t *hd = heads.data() + t * (size_t)w.heads_per_tile;
+            // leaf walk: children n0 .. n1 of the nodes a0 .. of level d - 2
+            {
+                const int32_t *pos = h.pos[d - 1];
+                const int n = tr.n1 - tr.n0, q = walk_chunk(n, g0, w.shape.batch[0]);
+                int32_t node = tr.a0;
+                for (int g = 0; g < g0 && (int64_t)g * q < n; ++g) {
+                    const int32_t x = tr.n0 + g * q;
+                    while (pos[node + 1] <= x) ++node;
+                    const bool head = g > 0 && pos[node] != x;
+                    hd[g] = (uint16_t)((node - tr.a0) | (head ? 0x8000 : 0));
+                }
+            }
+            if (w.shape.levels > 1) {   // the walk one level up: children a0 .. a0 + na of the nodes b0 ..
+                const int32_t *pos = h.pos[d - 2];
+                const int n = tr.na, q = walk_chunk(n, g1, w.shape.batch[1]);
+                int32_t node = tr.b0;
+                for (int g = 0; g < g1 && (int64_t)g * q < n; ++g) {
+                    const int32_t x = tr.a0 + g * q;
+                    while (pos[node + 1] <= x) ++node;
+                    const bool head = g > 0 && pos[node] != x;
+                    hd[g0 + g] = (uint16_t)((node - tr.b0) | (head ? 0x8000 : 0));
+                }
+            }
+        }
+        if (hipMalloc((void **)&w.d_heads, sizeof(uint16_t) * heads.size()) != hipSuccess) return SC_ERR_DEVICE;
+        if (hipMemcpy(w.d_heads, heads.data(), sizeof(uint16_t) * heads.size(), hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
+    } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
+    return SC_OK;
+}
+
 // Top level of a tile record ("a" for order 2, "b" for order 3, "c" for order 4): whether its
 // first / last slice continues from the previous / into the next tile, first slice, slice count.
 struct TopLevel {
@@ -1491,6 +1545,9 @@ static sc_status plan_create_impl(sc_plan **out, const char *expr, const sc_csf_
                 if (hipMalloc((void **)&p->d_slot_b, sizeof(int32_t) * nt) != hipSuccess) return SC_ERR_DEVICE;
                 if (hipMemcpy(p->d_slot_b, sb.data(), sizeof(int32_t) * nt, hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
             }
+            p->walk.shape = plan_walk_shape(p);
+            const sc_status ws = build_walk_tables(p, sparse, h, order);
+            if (ws != SC_OK) return ws;
         }
         if (p->zero_selective && !p->zero_rows.empty()) {
             if (hipMalloc((void **)&p->d_zero_rows, sizeof(int32_t) * p->zero_rows.size()) != hipSuccess) return SC_ERR_DEVICE;
@@ -1699,6 +1756,9 @@ extern "C" sc_status sc_plan_destroy(sc_plan *plan)
     }
     if (plan->d_tiles) (void)hipFree(plan->d_tiles);
     if (plan->d_slot_b) (void)hipFree(plan->d_slot_b);
+    for (uint32_t *r : plan->walk.d_rec)
+        if (r) (void)hipFree(r);
+    if (plan->walk.d_heads) (void)hipFree(plan->walk.d_heads);
     for (sck::FixLevel *lv : {&plan->det_top, &plan->det_a, &plan->det_b}) {
         if (lv->d_fix) (void)hipFree(lv->d_fix);
         if (lv->d_segs) (void)hipFree(lv->d_segs);

@@ -894,6 +894,12 @@ bool plan_wants_tensor_order(const sc_plan *p)
     return p->kind == K_TTMC4 && p->fcols[0] <= 16 && p->fcols[1] == 8 && p->fcols[2] == 8;   // the matrix-core kernels of the order-4 chain
 }
 
+WalkShape plan_walk_shape(const sc_plan *p)
+{
+    if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_walk_shape();
+    return WalkShape{};
+}
+
 size_t lds_bytes_needed(const sc_plan *p)
 {
     if (p->sched == SC_SCHED_LINEAR) return linear_lds_bytes(p);

@@ -306,8 +306,8 @@ TileCaps order4_caps(sc_dtype dtype, const int64_t *fcols)
         c.tn = 512; c.ta = 256; c.tb = 40;
     } else {
         // the largest tile with which four workgroups of the matrix-core kernel fit a compute unit
-        // (40,528 bytes of LDS each); measured best on the 50 M-nonzero workload
-        c.tn = 768; c.ta = 384; c.tb = 76;
+        // (40,784 bytes of LDS each); measured best on the 50 M-nonzero workload
+        c.tn = 768; c.ta = 384; c.tb = 78;
     }
     return c;
 }

@@ -9,7 +9,10 @@
 //     A(i, l, m, n) = sum_{f2 in slice i} C(j, l) * T2(f2, m, n)
 // Both temporaries live in LDS for the nodes of one tile.
 //
-//   stage    every global read of the tile is issued before the first is used
+//   stage    every global read of the tile is issued before the first is used; the coordinates of
+//            the two walked levels come from the plan's walk tables, with the end-of-fiber bits in
+//            them, as do the fibers at the heads of the lane groups' chunks: no fiber bounds are
+//            read and nothing is marked at run time
 //   leaves   the shared branch-free leaf walk with 8-wide rows (2 lanes per nonzero) -> T1 rows
 //   middle   the same walk one level up: children are the f3 fibers (their T1 row comes from
 //            LDS, the D row is gathered), a group of 16 lanes owns a chunk of children and
@@ -22,12 +25,17 @@
 //            into the next tile stays in registers, so a heavy slice costs one global update
 //            per workgroup; only a slice that crosses the run's ends is added atomically to
 //            the zeroed output
+#include <type_traits>
+
 #include "leaf_walk.h"
 
 namespace sck {
 
 struct Ttmc4Args {
-    const int32_t *crd1, *pos2, *crd2, *pos3, *crd3, *pos4, *crd4;
+    const int32_t *crd1, *pos2, *crd2;
+    const uint32_t *rec3, *rec4;   // the plan's walk tables: coordinates of the f3 fibers / of the nonzeros | end-of-parent bit 31
+    const uint16_t *heads;         // per tile: T4_G1 chunk heads of the leaf walk, then T4_G2 of the middle walk
+    int32_t heads_per_tile;
     const float *vals;
     const float *C, *D, *E;
     int64_t ldC, ldD, ldE;
@@ -47,6 +55,7 @@ constexpr int T4_RS2 = leaf_row_stride<float>(T4_W2);
 constexpr int T4_G1 = NT / (T4_N / 4);     // lane groups of the leaf walk (2 lanes each)
 constexpr int T4_LG2 = T4_W2 / 4;          // lanes per T2 row
 constexpr int T4_G2 = NT / T4_LG2;         // lane groups of the middle walk
+constexpr int T4_U1 = 4, T4_U2 = 4;          // children a lane group of the leaf / middle walk takes per step
 constexpr int T4_MAXR = 3;                 // tn <= T4_MAXR * NT
 constexpr int T4_MAXA = 2;                 // ta + 1 <= T4_MAXA * NT, tb + 1 <= NT
 constexpr int T4_TR1 = 3;                  // MODE 1: T1 rows copied per 2-lane group, ta <= T4_TR1 * G1
@@ -59,7 +68,7 @@ static_assert(NT / 64 == T4_W2 / 16, "one wavefront per 16 columns of a T2 row")
 // workgroups that fit a compute unit, so LDS bytes are what to save.
 __host__ __device__ constexpr size_t ttmc4_leaf_scratch_bytes(int tn, int ta)
 {
-    return (size_t)T4_G1 * T4_RS1 * 4 + (size_t)padded(tn + 8) * sizeof(LeafRec<float>) + (size_t)(ta + 2) * 4 + (size_t)T4_G1 * 4;
+    return (size_t)T4_G1 * T4_RS1 * 4 + (size_t)padded(tn + 8) * sizeof(LeafRec<float>) + (size_t)T4_G1 * 4;
 }
 
 __host__ __device__ constexpr size_t ttmc4_shared_bytes(int tn, int ta, int tb)
@@ -72,8 +81,8 @@ __host__ __device__ constexpr size_t ttmc4_shared_bytes(int tn, int ta, int tb)
 // The third kernel of the FISSIONED schedule (mode 2) reads finished T2 rows and has no T1 rows.
 __host__ __device__ constexpr size_t ttmc4_lds_bytes(int tn, int ta, int tb, int mode = 0)
 {
-    return (size_t)(mode == 2 ? 0 : (ta + 1) * T4_RS1 * 4) + ttmc4_shared_bytes(tn, ta, tb) + (size_t)(ta + 4) * 4 + (size_t)(tb + 2) * 4 +
-           (size_t)T4_G2 * 4 + (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
+    return (size_t)(mode == 2 ? 0 : (ta + 1) * T4_RS1 * 4) + ttmc4_shared_bytes(tn, ta, tb) + (size_t)(ta + 4) * 4 + (size_t)T4_G2 * 4 +
+           (size_t)tb * 4 + (size_t)(tb + 2) * 4 + (size_t)tb * 4 + 64;
 }
 
 typedef float t4_floatx4 __attribute__((ext_vector_type(4)));
@@ -85,7 +94,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
 {
     using P = Pack<float, 4>;
     using Rec = LeafRec<float>;
-    constexpr int U1 = 4, U2 = 4;
+    constexpr int U1 = T4_U1, U2 = T4_U2;
     constexpr int RS1 = T4_RS1, RS2 = T4_RS2;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -94,15 +103,13 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
     // leaf stage (dead once the T1 rows are complete) ...
     float *carry1_s = reinterpret_cast<float *>(shared_s);                    // G1 rows of RS1
     Rec *rec_s = reinterpret_cast<Rec *>(carry1_s + (size_t)T4_G1 * RS1);     // padded(tn + 8)
-    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));            // ta + 2: first nonzero of each f3
-    int *chunk_lr1 = ba_s + a.ta + 2;                                         // G1
+    uint32_t *chunk1_s = reinterpret_cast<uint32_t *>(rec_s + padded(a.tn + 8));   // G1: chunk heads of the leaf walk
     // ... and, in the same space, what the middle walk and the consumer use
     float *row2_s = reinterpret_cast<float *>(shared_s);                      // (tb + 1) rows of RS2: T2
     float *carry2_s = row2_s + (size_t)(a.tb + 1) * RS2;                      // G2 rows of RS2
     uint32_t *krec_s = reinterpret_cast<uint32_t *>(shared_s + ttmc4_shared_bytes(a.tn, a.ta, a.tb));   // ta + 4: D row offset of each f3 | end-of-f2 bit 31
-    int *bb_s = reinterpret_cast<int *>(krec_s + a.ta + 4);                   // tb + 2: first f3 of each f2
-    int *chunk_lr2 = bb_s + a.tb + 2;                                         // G2
-    uint32_t *coff2_s = reinterpret_cast<uint32_t *>(chunk_lr2 + T4_G2);      // tb: byte offset of C(j,:) per f2
+    uint32_t *chunk2_s = krec_s + a.ta + 4;                                   // G2: chunk heads of the middle walk
+    uint32_t *coff2_s = chunk2_s + T4_G2;                                     // tb: byte offset of C(j,:) per f2
     int *bc_s = reinterpret_cast<int *>(coff2_s + a.tb);                      // tb + 2: first f2 of each slice
     int *crdc_s = bc_s + a.tb + 2;                                            // tb: output row of each slice
 
@@ -122,27 +129,26 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
     struct Stage {
         uint32_t pp[T4_MAXR];
         float vv[T4_MAXR];
-        int p4[T4_MAXA], k3[T4_MAXA];
-        int p3, j2, p2, i1;
+        uint32_t k3[T4_MAXA];
+        int j2, p2, i1;
+        uint32_t hd;
         P t1row[MODE == 1 ? T4_TR1 : 1], t2row[MODE == 2 ? T4_TR2 : 1];
     };
-    auto issue = [&](const TileRec &t, Stage &s) {
+    auto issue = [&](const TileRec &t, int tile, Stage &s) {
         const int nchild = t.n1 - t.n0;
         const int na = t.na, nb = t.nb, nc = t.nc;
         if (MODE == 0) {
 #pragma unroll
             for (int r = 0; r < T4_MAXR; ++r) {
                 const int c = t.n0 + min(tid + r * NT, nchild - 1);
-                s.pp[r] = (uint32_t)a.crd4[c];
+                s.pp[r] = a.rec4[c];
                 s.vv[r] = a.vals[c];
             }
-#pragma unroll
-            for (int r = 0; r < T4_MAXA; ++r) s.p4[r] = a.pos4[t.a0 + min(tid + r * NT, na)];
         }
         if (MODE != 2) {
 #pragma unroll
-            for (int r = 0; r < T4_MAXA; ++r) s.k3[r] = a.crd3[t.a0 + min(tid + r * NT, na - 1)];
-            s.p3 = a.pos3[t.b0 + min(tid, nb)];
+            for (int r = 0; r < T4_MAXA; ++r) s.k3[r] = a.rec3[t.a0 + min(tid + r * NT, na - 1)];
+            s.hd = a.heads[(int64_t)tile * a.heads_per_tile + min(tid, T4_G1 + T4_G2 - 1)];
         }
         if (MODE != 1) {
             s.j2 = a.crd2[t.b0 + min(tid, nb - 1)];
@@ -166,7 +172,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
     };
     TileRec t = tiles[first];   // a launched workgroup has at least one tile
     Stage st;
-    issue(t, st);
+    issue(t, first, st);
 
     for (int tile = first; tile < lastp1; ++tile) {
         const TileRec tn = tiles[min(tile + 1, lastp1 - 1)];
@@ -181,9 +187,8 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
         {
             const uint32_t(&pp)[T4_MAXR] = st.pp;
             const float(&vv)[T4_MAXR] = st.vv;
-            const int(&p4)[T4_MAXA] = st.p4;
-            const int(&k3)[T4_MAXA] = st.k3;
-            const int p3 = st.p3, j2 = st.j2, p2 = st.p2, i1 = st.i1;
+            const uint32_t(&k3)[T4_MAXA] = st.k3;
+            const int j2 = st.j2, p2 = st.p2, i1 = st.i1;
             const auto &t1row = st.t1row;
             const auto &t2row = st.t2row;
             if (MODE == 0) {
@@ -192,7 +197,8 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                     const int c = tid + r * NT;
                     if (c < nchild) {
                         Rec rec;
-                        rec.koff = pp[r] * rowE;
+                        // the tile's last nonzero closes the fiber it is in as far as this tile goes
+                        rec.koff = (pp[r] & 0x7fffffffu) * rowE | (pp[r] & 0x80000000u) | (c == nchild - 1 ? 0x80000000u : 0u);
                         rec.v = vv[r];
                         rec_s[pidx(c)] = rec;
                     }
@@ -203,11 +209,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                     rec.v = 0.f;
                     rec_s[pidx(nchild + tid)] = rec;
                 }
-#pragma unroll
-                for (int r = 0; r < T4_MAXA; ++r) {
-                    const int i = tid + r * NT;
-                    if (i <= na) ba_s[i] = min(max(p4[r], t.n0), t.n1) - t.n0;
-                }
+                if (tid < T4_G1) chunk1_s[tid] = st.hd;
             }
             // A node cut by a tile boundary has one complete row in the workspace; the tile in
             // which it starts consumes it, the tiles it continues into see a zero row.
@@ -237,10 +239,10 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
 #pragma unroll
                 for (int r = 0; r < T4_MAXA; ++r) {
                     const int i = tid + r * NT;
-                    if (i < na) krec_s[i] = (uint32_t)k3[r] * rowD;
+                    if (i < na) krec_s[i] = (k3[r] & 0x7fffffffu) * rowD | (k3[r] & 0x80000000u) | (i == na - 1 ? 0x80000000u : 0u);
                 }
                 if (tid < U2) krec_s[na + tid] = 0;   // dummies of the middle walk
-                if (tid <= nb) bb_s[tid] = min(max(p3, t.a0), t.a0 + na) - t.a0;
+                if (tid >= T4_G1 && tid < T4_G1 + T4_G2) chunk2_s[tid - T4_G1] = st.hd;
             }
             if (MODE != 1) {
                 if (tid < nb) coff2_s[tid] = (uint32_t)j2 * rowC;
@@ -252,7 +254,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
 
         // ---- the next tile's reads go out now and land while this tile is worked on ----
         Stage sn;
-        if (tile + 1 < lastp1) issue(tn, sn);
+        if (tile + 1 < lastp1) issue(tn, tile + 1, sn);
         // FUSED: the C rows of the tile's f2 fibers are fetched ahead of the consumer (16 lanes per row, rows
         // tid / 16 + 16 r; their offsets are in LDS by now) and are parked in the space of the T1 rows as soon
         // as those are dead.  The consumer then reads both operands of its MFMAs from LDS instead of gathering
@@ -265,24 +267,12 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
             for (int r = 0; r < T4_TR2; ++r) cval[r] = *reinterpret_cast<const float *>(Cl + coff2_s[min(tid / 16 + r * T4_G2, nb - 1)]);
         }
 
-        // ---- marks of both walks ----
-        if (MODE == 0) leaf_mark(rec_s, ba_s, chunk_lr1, tid, NT, na, q1);
-        if (MODE != 2) {
-            for (int i = tid; i < nb; i += NT) {
-                const int lo = bb_s[i], hi = bb_s[i + 1];
-                if (hi <= lo) continue;   // cannot happen: a tile lists only nodes with leaves inside it
-                krec_s[hi - 1] |= 0x80000000u;
-                for (int m = (lo + q2 - 1) / q2; m * q2 < hi; ++m) chunk_lr2[m] = i;
-            }
-            __syncthreads();
-        }
-
         // ---- leaves -> T1 rows ----
         if (MODE == 0) {
             const int g = tid / 2, li = tid % 2;
-            const LeafCarry st = leaf_walk<float, T4_N, U1>(row1_s, carry1_s, rec_s, ba_s, chunk_lr1, a.E, g, li, q1, nchild);
+            const uint32_t done = table_walk<float, T4_N, U1>(row1_s, carry1_s, rec_s, chunk1_s, a.E, g, li, q1, nchild);
             __syncthreads();
-            leaf_combine<float, T4_N>(row1_s, carry1_s, ba_s, chunk_lr1, st, g, li, q1);
+            table_combine<float, T4_N>(row1_s, carry1_s, chunk1_s, done, g, li);
             __syncthreads();
         }
 
@@ -291,14 +281,13 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
             const int g = tid / T4_LG2, li = tid % T4_LG2;
             const int m = li / 2, nq = (li % 2) * 4;
             const char *Db = reinterpret_cast<const char *>(a.D) + m * 4;
-            LeafCarry st{0, false, false};
+            uint32_t done = 0;
             const int gs = g * q2, ge = min(gs + q2, na);
             if (gs < ge) {
-                st.lr0 = chunk_lr2[g];
-                st.head = bb_s[st.lr0] != gs;
-                float *rowp = row2_s + st.lr0 * RS2 + li * 4;
+                const uint32_t entry = chunk2_s[g];
+                float *rowp = row2_s + (entry & kChunkRow) * RS2 + li * 4;
                 float *const row0 = rowp;
-                float *dst = st.head ? carry2_s + g * RS2 + li * 4 : rowp;
+                float *dst = (entry & kChunkHead) ? carry2_s + g * RS2 + li * 4 : rowp;
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
                 for (int c = gs; c < ge; c += U2) {
                     uint32_t kr[U2];
@@ -327,7 +316,8 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                         dst = end ? rowp : dst;
                     }
                 }
-                st.owner = st.head && (rowp != row0 || ge == na);
+                done = entry | (rowp != row0 ? kChunkEnded : 0u);
+                if (li == 0) chunk2_s[g] = done;
             }
             __syncthreads();
             if (c_in_lds) {   // the T1 rows are dead: their space takes the C rows (l >= L padded with zeros)
@@ -338,7 +328,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                     if (f < nb) row1_s[f * 16 + l] = l < L ? cval[r] : 0.f;
                 }
             }
-            leaf_combine<float, T4_W2>(row2_s, carry2_s, bb_s, chunk_lr2, st, g, li, q2);
+            table_combine<float, T4_W2>(row2_s, carry2_s, chunk2_s, done, g, li);
             __syncthreads();
         }
 
@@ -386,37 +376,44 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                     for (int r = 0; r < 4; ++r) atomic_add(dst + r, v[r]);
                 }
             };
-            for (int ls = 0; ls < nc; ++ls) {
-                const int f0 = uni(bc_s[ls]), f1 = uni(bc_s[ls + 1]);
-                t4_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-                constexpr int UB = 4;   // 4-fiber blocks whose operand reads are issued together
-                for (int fb = f0; fb < f1; fb += 4 * UB) {
-                    float cv[UB], tv[UB];
+            // the loop is compiled once per source of the C rows: with a run-time choice inside it the two reads
+            // merge into one generic-address load, whose wait also covers every global read in flight
+            auto slices = [&](auto c_rows_in_lds) {
+                constexpr bool CL = decltype(c_rows_in_lds)::value;
+                for (int ls = 0; ls < nc; ++ls) {
+                    const int f0 = uni(bc_s[ls]), f1 = uni(bc_s[ls + 1]);
+                    t4_floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+                    constexpr int UB = 4;   // 4-fiber blocks whose operand reads are issued together
+                    for (int fb = f0; fb < f1; fb += 4 * UB) {
+                        float cv[UB], tv[UB];
 #pragma unroll
-                    for (int ub = 0; ub < UB; ++ub) {
-                        const int lf = fb + 4 * ub + kk;
-                        const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
-                        const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
-                        float cvr;
-                        if (MODE == 0 && c_in_lds) cvr = row1_s[lfc * 16 + col];
-                        else cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
-                        tv[ub] = lf < f1 ? tvr : 0.f;
-                        cv[ub] = lval ? cvr : 0.f;
+                        for (int ub = 0; ub < UB; ++ub) {
+                            const int lf = fb + 4 * ub + kk;
+                            const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
+                            const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
+                            float cvr;
+                            if (CL) cvr = row1_s[lfc * 16 + col];
+                            else cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
+                            tv[ub] = lf < f1 ? tvr : 0.f;
+                            cv[ub] = lval ? cvr : 0.f;
+                        }
+#pragma unroll
+                        for (int ub = 0; ub < UB; ++ub)
+                            if (fb + 4 * ub < f1) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(tv[ub], cv[ub], acc, 0, 0, 0);
                     }
-#pragma unroll
-                    for (int ub = 0; ub < UB; ++ub)
-                        if (fb + 4 * ub < f1) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(tv[ub], cv[ub], acc, 0, 0, 0);
+                    const bool incoming = ls == 0 && in_f, outgoing = ls == nc - 1 && out_f;
+                    if (incoming) acc += carry;
+                    if (outgoing) {
+                        if (last_tile) emit(acc, ls, true);   // continues in another workgroup's run
+                        else carry = acc;
+                    } else {
+                        emit(acc, ls, incoming && chain_shared);
+                        if (incoming) chain_shared = false;
+                    }
                 }
-                const bool incoming = ls == 0 && in_f, outgoing = ls == nc - 1 && out_f;
-                if (incoming) acc += carry;
-                if (outgoing) {
-                    if (last_tile) emit(acc, ls, true);   // continues in another workgroup's run
-                    else carry = acc;
-                } else {
-                    emit(acc, ls, incoming && chain_shared);
-                    if (incoming) chain_shared = false;
-                }
-            }
+            };
+            if (MODE == 0 && c_in_lds) slices(std::true_type{});
+            else slices(std::false_type{});
         }
         __syncthreads();
         if (tile + 1 < lastp1) {
@@ -424,6 +421,15 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
             st = sn;
         }
     }  // tiles of the run
+}
+
+WalkShape ttmc4_mfma_walk_shape()
+{
+    WalkShape w;
+    w.levels = 2;
+    w.groups[0] = T4_G1; w.groups[1] = T4_G2;
+    w.batch[0] = T4_U1; w.batch[1] = T4_U2;
+    return w;
 }
 
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p) { return ttmc4_lds_bytes(p->caps.tn, p->caps.ta, p->caps.tb); }
@@ -446,8 +452,11 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * 4 >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
     if ((uint64_t)fac[0].rows * (uint64_t)fac[0].ld * 4 >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
     Ttmc4Args a;
-    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1]; a.pos3 = sp->pos[2]; a.crd3 = sp->crd[2];
-    a.pos4 = sp->pos[3]; a.crd4 = sp->crd[3];
+    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1];
+    // the two walked levels are read from the plan's walk tables
+    if (!p->walk.d_rec[0] || !p->walk.d_rec[1] || !p->walk.d_heads || p->walk.heads_per_tile < T4_G1 + T4_G2) return SC_ERR_SCHED_UNSUPPORTED;
+    a.rec4 = p->walk.d_rec[0]; a.rec3 = p->walk.d_rec[1];
+    a.heads = p->walk.d_heads; a.heads_per_tile = p->walk.heads_per_tile;
     a.vals = static_cast<const float *>(sp->vals);
     a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
     a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;

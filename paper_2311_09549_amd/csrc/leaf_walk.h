@@ -51,7 +51,7 @@ __host__ __device__ constexpr size_t leaf_walk_lds_bytes(int W, int tn, int ta, 
 template <int U>
 __device__ __forceinline__ int leaf_chunk(int nchild, int groups)
 {
-    return max(((nchild + groups - 1) / groups + U - 1) / U * U, U);
+    return walk_chunk(nchild, groups, U);
 }
 
 // Marks fiber ends in the records and notes the fiber at the head of every chunk.  Runs
@@ -141,6 +141,88 @@ __device__ __forceinline__ void leaf_combine(T *row_s, const T *carry_s, const i
         for (int i = 0; i < VEC; ++i) sum.v[i] += c.v[i];
     }
     T *dst = row_s + st.lr0 * RS + li * VEC;
+    const P base = *reinterpret_cast<const P *>(dst);   // the piece written by the chunk in which the fiber starts
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) sum.v[i] += base.v[i];
+    *reinterpret_cast<P *>(dst) = sum;
+}
+
+// ---- the same walk driven by the plan's walk tables ----
+// The records already carry the end-of-fiber bits (the plan's copy of the coordinates has them, and
+// the stage sets the bit of the tile's last nonzero), and chunk_s holds, per lane group, the plan's
+// entry for the tile: row of the fiber at the head of the chunk | bit 15 when that fiber began in an
+// earlier chunk.  No fiber bounds are staged and nothing is marked at run time.  After its walk a
+// group replaces its entry by the same word with bit 16 set when a fiber ended inside the chunk;
+// the combine step reads the entries of the chunks before its own to find the carry rows that
+// belong to its head fiber: those of the chunks that began inside the fiber and saw no end.
+constexpr uint32_t kChunkHead = 0x8000u, kChunkEnded = 0x10000u, kChunkRow = 0x7fffu;
+
+template <typename T, int W, int U>
+__device__ __forceinline__ uint32_t table_walk(T *row_s, T *carry_s, const LeafRec<T> *rec_s, uint32_t *chunk_s, const void *F, int g, int li,
+                                               int q, int nchild)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int RS = leaf_row_stride<T>(W);
+    using P = Pack<T, VEC>;
+    const int gs = g * q, ge = min(gs + q, nchild);
+    if (gs >= ge) return 0;
+    const char *Fb = static_cast<const char *>(F);
+    const uint32_t lo16 = (uint32_t)li * 16u;
+    const uint32_t entry = chunk_s[g];
+    const bool head = (entry & kChunkHead) != 0;
+    T *rowp = row_s + (entry & kChunkRow) * RS + li * VEC;
+    T *const row0 = rowp;
+    T *dst = head ? carry_s + g * RS + li * VEC : rowp;
+    T acc[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; ++i) acc[i] = T(0);
+    for (int c = gs; c < ge; c += U) {
+        LeafRec<T> r[U];
+        P d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) r[u] = rec_s[pidx(c + u)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) d[u] = *reinterpret_cast<const P *>(Fb + ((r[u].koff & 0x7fffffffu) + lo16));
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            P o;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                acc[i] += r[u].v * d[u].v[i];
+                o.v[i] = acc[i];
+            }
+            *reinterpret_cast<P *>(dst) = o;
+            const bool end = (int32_t)r[u].koff < 0;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[i] = end ? T(0) : acc[i];
+            rowp = end ? rowp + RS : rowp;
+            dst = end ? rowp : dst;
+        }
+    }
+    const uint32_t done = entry | (rowp != row0 ? kChunkEnded : 0u);
+    if (li == 0) chunk_s[g] = done;
+    return done;
+}
+
+// After a barrier: the group in which a head fiber ends adds the carry rows of the chunks the fiber
+// passed through to the fiber's row (it is then the row's only writer).
+template <typename T, int W>
+__device__ __forceinline__ void table_combine(T *row_s, const T *carry_s, const uint32_t *chunk_s, uint32_t done, int g, int li)
+{
+    constexpr int VEC = VecWidth<T>::value;
+    constexpr int RS = leaf_row_stride<T>(W);
+    using P = Pack<T, VEC>;
+    if ((done & (kChunkHead | kChunkEnded)) != (kChunkHead | kChunkEnded)) return;
+    P sum = *reinterpret_cast<const P *>(carry_s + g * RS + li * VEC);
+    for (int h = g - 1; h >= 0; --h) {
+        const uint32_t e = chunk_s[h];
+        // a chunk in which a fiber ended, or which began with the fiber, wrote its piece to the row itself
+        if ((e & (kChunkHead | kChunkEnded)) != kChunkHead) break;
+        const P c = *reinterpret_cast<const P *>(carry_s + h * RS + li * VEC);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) sum.v[i] += c.v[i];
+    }
+    T *dst = row_s + (done & kChunkRow) * RS + li * VEC;
     const P base = *reinterpret_cast<const P *>(dst);   // the piece written by the chunk in which the fiber starts
 #pragma unroll
     for (int i = 0; i < VEC; ++i) sum.v[i] += base.v[i];

@@ -86,6 +86,35 @@ struct ProfileState {
     hipEvent_t ev_end[kMaxLaunches];
 };
 
+// Walk tables: what the segmented walks of a tile need to know about the node boundaries, worked out
+// once when the plan is made instead of by every tile of every execution.
+//   rec[0]   one word per stored nonzero: its last coordinate, bit 31 set when it is the last of its fiber
+//   rec[1]   one word per node of level "a": its coordinate, bit 31 set when it is the last child of its parent
+//   heads    per tile (in the order of the device tile table) one 16-bit entry per lane group of the leaf walk,
+//            then one per lane group of the walk one level up: the tile-local index of the node that holds the
+//            first child of the group's chunk (chunks of walk_chunk children), bit 15 set when that node began
+//            in an earlier chunk
+// The lane-group counts and batch sizes are those of the kernel the plan dispatches to.
+struct WalkShape {
+    int32_t levels = 0;          // 0 = the plan's kernels keep no walk tables
+    int32_t groups[2] = {0, 0};  // lane groups of the leaf walk / of the walk over level-a nodes
+    int32_t batch[2] = {1, 1};   // children a lane group takes per step (chunks are multiples of it)
+};
+
+struct WalkTables {
+    WalkShape shape;
+    uint32_t *d_rec[2] = {nullptr, nullptr};
+    uint16_t *d_heads = nullptr;
+    int32_t heads_per_tile = 0;
+};
+
+// Children per lane group for a tile of n children: a multiple of the batch size u.
+__host__ __device__ inline int walk_chunk(int n, int groups, int u)
+{
+    const int q = ((n + groups - 1) / groups + u - 1) / u * u;
+    return q > u ? q : u;
+}
+
 struct Intermediate {
     std::string name;   // e.g. "T(i,j,m)"
     size_t offset = 0;  // byte offset inside the workspace (FISSIONED only)
@@ -134,6 +163,7 @@ struct sc_plan {
                              // numbered the same way from slot_b[tile]
     std::vector<int32_t> slot_b;
     int32_t *d_slot_b = nullptr;   // plan-owned device copy, in the order of the device tile table
+    sck::WalkTables walk;          // plan-owned device tables of the segmented walks (kernels that use them)
     double model_flops = 0, model_bytes = 0;
     std::string text;  // description
 
@@ -189,6 +219,9 @@ bool plan_wants_tensor_order(const sc_plan *plan);
 // True when the kernels of the plan can run without floating-point atomics (FUSED schedules of
 // the kernels that emit one piece per tile and shared row).
 bool plan_supports_deterministic(const sc_plan *plan);
+
+// Lane-group layout of the walks of the kernels the plan dispatches to (levels = 0: no walk tables).
+WalkShape plan_walk_shape(const sc_plan *plan);
 
 // Dynamic LDS bytes the fused / fissioned kernels of a plan need (used for validation).
 size_t lds_bytes_needed(const sc_plan *plan);

@@ -75,6 +75,9 @@ def main() -> int:
     ap.add_argument("--kernel", required=True, help="substring of the profiled kernel's name")
     ap.add_argument("--key", required=True, help='"<config id>:<launch name>" as bench.py reports it')
     ap.add_argument("--out", default=DEFAULT_PATH)
+    ap.add_argument("--mfma-dir", default=None,
+                    help="directory of a third counter run (SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CU_CYCLES SQ_INSTS_MFMA): "
+                         "stores the matrix cores' busy fraction of the kernel")
     a = ap.parse_args()
     kib = 1024.0
     k_fetch = _per_dispatch_mean(a.fetch_dir, "FETCH_SIZE", a.kernel) * kib
@@ -90,6 +93,12 @@ def main() -> int:
         "hbm_bytes": k_fetch / f_fetch + k_write / f_write,
         "source_sha256": source_digest(),
     }
+    if a.mfma_dir:
+        # busy cycles of the matrix pipes summed over the four SIMDs of every CU, over the CUs' busy cycles
+        busy = _per_dispatch_mean(a.mfma_dir, "SQ_VALU_MFMA_BUSY_CYCLES", a.kernel)
+        cu = _per_dispatch_mean(a.mfma_dir, "SQ_BUSY_CU_CYCLES", a.kernel)
+        ent["mfma_busy"] = busy / (4.0 * cu) if cu else None
+        ent["mfma_instructions"] = _per_dispatch_mean(a.mfma_dir, "SQ_INSTS_MFMA", a.kernel)
     rec = {"entries": {}}
     if os.path.exists(a.out):
         with open(a.out) as fh:
