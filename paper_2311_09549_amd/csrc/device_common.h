@@ -207,8 +207,9 @@ inline void launch_output_zero(Launcher &ln, const sc_plan *p, T *out)
 // the temporary it writes.
 size_t leaf_traverse_lds_bytes(const sc_plan *p, int W);
 // `partials`: deterministic schedules only (else null): slots for the pieces of rows that span tiles.
-sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name, void *partials);
+WalkShape leaf_traverse_walk_shape(sc_dtype dtype, int W);
+sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const void *vals, const sc_dense_view &F, void *Tout, int W, const char *name,
+                               void *partials);
 
 // Order-3 TTM chain on matrix cores (fp32, L = M = 16; its own kernel file): the FUSED schedule (T == nullptr)
 // or the consumer kernel of the FISSIONED one.

@@ -756,7 +756,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         return launch_fixup(p, ln, p->det_top, ws, out);
     } else {
         void *partials_a = p->deterministic && ws ? static_cast<char *>(ws) + p->det_a.slot_offset : nullptr;
-        sc_status st = launch_leaf_producer(p, ln, sp->pos[2], sp->crd[2], sp->vals, fac[1], a.T, W, "order3_traverse", partials_a);
+        sc_status st = launch_leaf_producer(p, ln, sp->vals, fac[1], a.T, W, "order3_traverse", partials_a);
         if (st != SC_OK) return st;
         st = launch_fixup(p, ln, p->det_a, ws, a.T);   // deterministic: the rows of T that span tiles
         if (st != SC_OK) return st;
@@ -896,7 +896,12 @@ bool plan_wants_tensor_order(const sc_plan *p)
 
 WalkShape plan_walk_shape(const sc_plan *p)
 {
-    if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_walk_shape();
+    if (p->sched == SC_SCHED_LINEAR) return WalkShape{};
+    if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_walk_shape();   // its leaf level also serves the traversal kernel
+    // FISSIONED, order >= 3: the leaf traversal, whose rows are as wide as the last factor
+    if (p->sched == SC_SCHED_FISSIONED && (p->kind == K_TTMC3 || p->kind == K_MTTKRP3))
+        return leaf_traverse_walk_shape(p->dtype, (int)p->fcols[1]);
+    if (p->sched == SC_SCHED_FISSIONED && p->kind == K_TTMC4) return leaf_traverse_walk_shape(p->dtype, (int)p->fcols[2]);
     return WalkShape{};
 }
 

@@ -258,7 +258,7 @@ sc_status run_order4(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
         // in slots, and a fix-up adds them in tile order before the next kernel reads the rows
         const bool det = p->deterministic && ws && mfma;
         char *wsb = static_cast<char *>(ws);
-        sc_status st = launch_leaf_producer(p, ln, sp->pos[3], sp->crd[3], sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse",
+        sc_status st = launch_leaf_producer(p, ln, sp->vals, fac[2], a.T1, (int)N, "ttmc4_traverse",
                                             det ? wsb + p->det_a.slot_offset : nullptr);
         if (st != SC_OK) return st;
         if (det) {

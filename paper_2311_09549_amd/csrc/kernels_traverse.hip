@@ -9,9 +9,10 @@
 // fiber ends issues one mostly-masked store per step.  The kernel therefore collects the
 // rows of a tile in LDS and writes them out at the end with full-width stores:
 //
-//   stage 1  tile-local fiber bounds; one LDS record per nonzero {factor row offset, value}
-//   stage 2  fiber ends marked in the records (top bit of the offset); first fiber of every
-//            lane-group chunk
+//   stage    one LDS record per nonzero {factor row offset | end-of-fiber bit, value}: the
+//            coordinates come from the plan's walk tables with the end bits in them, and so does
+//            the fiber at the head of every lane group's chunk; no fiber bounds are read and
+//            nothing is marked at run time
 //   walk     the shared branch-free leaf walk: a lane group of LG = W / VEC lanes owns a
 //            contiguous chunk of nonzeros, keeps U gathers in flight and writes the running
 //            sum to the current fiber's row of the LDS tile after every nonzero; chunk heads
@@ -34,7 +35,9 @@ __device__ __forceinline__ void nt_store16(T *dst, const PK &v)
 }
 
 struct LeafArgs {
-    const int32_t *pos, *crd;
+    const uint32_t *rec;     // the plan's walk table: last coordinate of every nonzero | end-of-fiber bit 31
+    const uint16_t *heads;   // ... and per tile the chunk heads of the lane groups
+    int32_t heads_per_tile;
     const void *vals;
     const void *F;
     int64_t ldF;
@@ -47,34 +50,33 @@ struct LeafArgs {
 template <typename T>
 __host__ __device__ constexpr size_t leaf_lds_bytes(int W, int tn, int ta)
 {
-    return leaf_walk_lds_bytes<T>(W, tn, ta, LNT) + 64;
+    const int groups = LNT / (W / (16 / (int)sizeof(T)));
+    return (size_t)(ta + 1 + groups) * leaf_row_stride<T>(W) * sizeof(T) + (size_t)padded(tn + 8) * sizeof(LeafRec<T>) + (size_t)groups * 4 + 64;
 }
 
 // Global reads of one tile's staging, held in registers until the tile's turn.
 template <typename T>
 struct LeafStage {
     static constexpr int MAXR = 4;   // tn <= MAXR * LNT
-    static constexpr int MAXB = 3;   // ta + 1 <= MAXB * LNT
     uint32_t kk[MAXR];
     T vv[MAXR];
-    int bb[MAXB];
+    uint32_t hd;
 };
 
 // Issues every global read of a tile's staging at once (clamped indices keep the redundant
 // ones in bounds), so the staging costs one memory latency, not one per loop trip.
 template <typename T>
-__device__ __forceinline__ void leaf_issue(const LeafArgs &a, const TileRec &t, int tid, LeafStage<T> &s)
+__device__ __forceinline__ void leaf_issue(const LeafArgs &a, const TileRec &t, int tile, int groups, int tid, LeafStage<T> &s)
 {
     const T *vals = static_cast<const T *>(a.vals);
     const int nchild = t.n1 - t.n0;
 #pragma unroll
     for (int r = 0; r < LeafStage<T>::MAXR; ++r) {
         const int c = t.n0 + min(tid + r * LNT, nchild - 1);
-        s.kk[r] = (uint32_t)a.crd[c];
+        s.kk[r] = a.rec[c];
         s.vv[r] = vals[c];
     }
-#pragma unroll
-    for (int r = 0; r < LeafStage<T>::MAXB; ++r) s.bb[r] = a.pos[t.a0 + min(tid + r * LNT, t.na)];
+    s.hd = a.heads[(int64_t)tile * a.heads_per_tile + min(tid, groups - 1)];
 }
 
 // Workgroup b handles tiles b, b + gridDim.x, ... (the launch is persistent for wide rows and
@@ -90,7 +92,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
     constexpr int VEC = VecWidth<T>::value;
     constexpr int LG = W / VEC;
     constexpr int G = LNT / LG;
-    constexpr int U = 4;
+    constexpr int U = 4;   // as in leaf_traverse_walk_shape
     static_assert(W % VEC == 0 && (LG & (LG - 1)) == 0 && LG <= 64, "row width");
     using P = Pack<T, VEC>;
     using Rec = LeafRec<T>;
@@ -101,8 +103,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
     T *row_s = reinterpret_cast<T *>(smem);                                    // (ta + 1) rows of RS
     T *carry_s = row_s + (size_t)(a.ta + 1) * RS;                              // G rows of RS
     Rec *rec_s = reinterpret_cast<Rec *>(carry_s + (size_t)G * RS);            // padded(tn + 8)
-    int *ba_s = reinterpret_cast<int *>(rec_s + padded(a.tn + 8));             // ta + 2: first nonzero of each fiber (tile-local)
-    int *chunk_lr = ba_s + a.ta + 2;                                           // G: fiber holding the first nonzero of each chunk
+    uint32_t *chunk_s = reinterpret_cast<uint32_t *>(rec_s + padded(a.tn + 8));   // G: chunk heads
 
     const int tid = threadIdx.x;
     const int g = tid / LG, li = tid % LG;
@@ -113,7 +114,7 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
     TileRec t = tiles[blockIdx.x];
     TileRec t1 = tiles[min(nx, last)];
     Stage st;
-    leaf_issue(a, t, tid, st);
+    leaf_issue(a, t, (int)blockIdx.x, G, tid, st);
     // First tile: wait here, so that the loop body itself never waits on staging registers
     // (a wait there would also wait for the previous tile's row stores): vmcnt(0).
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -123,22 +124,19 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
         const int na = t.na;
         const int q = leaf_chunk<U>(nchild, G);   // nonzeros per lane group, multiple of U
 
-        // ---- stage 1: registers -> LDS ----
+        // ---- stage: registers -> LDS ----
 #pragma unroll
         for (int r = 0; r < Stage::MAXR; ++r) {
             const int c = tid + r * LNT;
             if (c < nchild) {
                 Rec rec;
-                rec.koff = st.kk[r] * rowF;
+                // the tile's last nonzero closes the fiber it is in as far as this tile goes
+                rec.koff = (st.kk[r] & 0x7fffffffu) * rowF | (st.kk[r] & 0x80000000u) | (c == nchild - 1 ? 0x80000000u : 0u);
                 rec.v = st.vv[r];
                 rec_s[pidx(c)] = rec;
             }
         }
-#pragma unroll
-        for (int r = 0; r < Stage::MAXB; ++r) {
-            const int i = tid + r * LNT;
-            if (i <= na) ba_s[i] = min(max(st.bb[r], t.n0), t.n1) - t.n0;
-        }
+        if (tid < G) chunk_s[tid] = st.hd;
         if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
             Rec rec;
             rec.koff = 0;
@@ -147,23 +145,19 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
         }
         __syncthreads();
 
-        // ---- stage 2 ----
-        leaf_mark(rec_s, ba_s, chunk_lr, tid, LNT, na, q);
-        __syncthreads();
-
         // ---- reads of the next tile (and the record of the one after) go out now ----
         const bool more = nx < a.ntiles;
         Stage sn;
-        if (more) leaf_issue(a, t1, tid, sn);
+        if (more) leaf_issue(a, t1, nx, G, tid, sn);
         const TileRec t2 = tiles[min(nx + stride, last)];
 
         // ---- walk ----
-        const LeafCarry cst = leaf_walk<T, W, U>(row_s, carry_s, rec_s, ba_s, chunk_lr, a.F, g, li, q, nchild);
+        const uint32_t done = table_walk<T, W, U>(row_s, carry_s, rec_s, chunk_s, a.F, g, li, q, nchild);
         // The prefetched registers are complete here, before any store is queued behind
         // them (waits count loads and stores in issue order): vmcnt(0), other counters free.
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __syncthreads();
-        leaf_combine<T, W>(row_s, carry_s, ba_s, chunk_lr, cst, g, li, q);
+        table_combine<T, W>(row_s, carry_s, chunk_s, done, g, li);
         __syncthreads();
 
         // ---- flush ----
@@ -217,16 +211,19 @@ __global__ void __launch_bounds__(LNT) leaf_traverse_kernel(LeafArgs a, const Ti
 
 namespace {
 template <typename T, int W>
-sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                        const sc_dense_view &F, void *Tout, void *partials, const char *name)
+sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const void *vals, const sc_dense_view &F, void *Tout, void *partials, const char *name)
 {
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return SC_OK;
     // factor rows are addressed with 31-bit byte offsets (bit 31 marks fiber ends)
     if ((uint64_t)F.rows * (uint64_t)F.ld * sizeof(T) >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
-    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta + 1 > LeafStage<float>::MAXB * LNT) return SC_ERR_SCHED_UNSUPPORTED;   // staging registers
+    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta > (int)kChunkRow) return SC_ERR_SCHED_UNSUPPORTED;   // staging registers, row numbers of the chunk heads
+    // the plan's walk tables must have been made for this kernel's lane groups
+    const WalkShape want = leaf_traverse_walk_shape(p->dtype, W);
+    const WalkTables &wt = p->walk;
+    if (!wt.d_rec[0] || !wt.d_heads || wt.shape.groups[0] != want.groups[0] || wt.shape.batch[0] != want.batch[0]) return SC_ERR_SCHED_UNSUPPORTED;
     LeafArgs a = {};
-    a.pos = pos_leaf; a.crd = crd_leaf;
+    a.rec = wt.d_rec[0]; a.heads = wt.d_heads; a.heads_per_tile = wt.heads_per_tile;
     a.vals = vals;
     a.F = F.data;
     a.ldF = F.ld;
@@ -260,18 +257,29 @@ sc_status leaf_traverse(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf,
 
 size_t leaf_traverse_lds_bytes(const sc_plan *p, int W)
 {
-    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta + 1 > LeafStage<float>::MAXB * LNT) return SIZE_MAX;   // staging registers
+    if (p->caps.tn > LeafStage<float>::MAXR * LNT || p->caps.ta > (int)kChunkRow) return SIZE_MAX;   // staging registers, row numbers of the chunk heads
     return p->dtype == SC_F64 ? leaf_lds_bytes<double>(W, p->caps.tn, p->caps.ta) : leaf_lds_bytes<float>(W, p->caps.tn, p->caps.ta);
 }
 
-sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const int32_t *pos_leaf, const int32_t *crd_leaf, const void *vals,
-                               const sc_dense_view &F, void *Tout, int W, const char *name, void *partials)
+WalkShape leaf_traverse_walk_shape(sc_dtype dtype, int W)
+{
+    WalkShape w;
+    const int vec = dtype == SC_F64 ? 2 : 4;   // elements per 16-byte lane
+    if (W < vec || W % vec) return w;
+    w.levels = 1;
+    w.groups[0] = LNT / (W / vec);
+    w.batch[0] = 4;   // U of the kernel
+    return w;
+}
+
+sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const void *vals, const sc_dense_view &F, void *Tout, int W, const char *name,
+                               void *partials)
 {
     const bool f64 = p->dtype == SC_F64;
 #define SC_LEAF(WW)                                                                                   \
     case WW:                                                                                          \
-        return f64 ? leaf_traverse<double, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, partials, name) \
-                   : leaf_traverse<float, WW>(p, ln, pos_leaf, crd_leaf, vals, F, Tout, partials, name);
+        return f64 ? leaf_traverse<double, WW>(p, ln, vals, F, Tout, partials, name) \
+                   : leaf_traverse<float, WW>(p, ln, vals, F, Tout, partials, name);
     switch (W) {
         SC_LEAF(8)
         SC_LEAF(16)

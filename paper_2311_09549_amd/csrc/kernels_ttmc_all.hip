@@ -249,7 +249,7 @@ sc_status run_ttmc_all(const sc_plan *p, const sc_csf_view *sp, const sc_dense_v
         Launcher li{in, stream};
         void *T1 = wsb + p->k5_inner_ws_offset + in->inter[0].offset;
         void *partials_a = in->deterministic ? wsb + p->k5_inner_ws_offset + in->det_a.slot_offset : nullptr;
-        sc_status st = launch_leaf_producer(in, li, sp->pos[2], sp->crd[2], sp->vals, fac[2], T1, N, "ttmc_all_traverse", partials_a);
+        sc_status st = launch_leaf_producer(in, li, sp->vals, fac[2], T1, N, "ttmc_all_traverse", partials_a);
         if (st != SC_OK) return st;
         st = launch_fixup(in, li, in->det_a, wsb + p->k5_inner_ws_offset, T1);
         if (st != SC_OK) return st;
