@@ -214,6 +214,7 @@ sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const void *vals,
 // Order-3 TTM chain on matrix cores (fp32, L = M = 16; its own kernel file): the FUSED schedule (T == nullptr)
 // or the consumer kernel of the FISSIONED one.
 size_t ttmc3_mfma_lds_bytes(const sc_plan *p);
+WalkShape ttmc3_mfma_walk_shape();
 bool ttmc3_mfma_caps_ok(const sc_plan *p);
 // `partials`: deterministic schedules only (else null): slots for the pieces of rows that span tiles.
 sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,

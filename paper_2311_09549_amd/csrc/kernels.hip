@@ -837,10 +837,10 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
                 c.tb = c.ta;
             }
             if (dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {
-                // matrix-core kernel: measured best on the 30 M-nonzero workload; 216 rows keep the
-                // workgroup's LDS just below the size at which five fit a compute unit
+                // matrix-core kernel: measured best on the 30 M-nonzero workload; 224 rows keep the
+                // workgroup's LDS (31,328 bytes) just below the size at which five fit a compute unit
                 c.tn = 768;
-                c.ta = 216;
+                c.ta = 224;
                 c.tb = 64;
             }
         }
@@ -898,6 +898,7 @@ WalkShape plan_walk_shape(const sc_plan *p)
 {
     if (p->sched == SC_SCHED_LINEAR) return WalkShape{};
     if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_walk_shape();   // its leaf level also serves the traversal kernel
+    if (p->kind == K_TTMC3 && p->sched == SC_SCHED_FUSED && plan_wants_tensor_order(p)) return ttmc3_mfma_walk_shape();
     // FISSIONED, order >= 3: the leaf traversal, whose rows are as wide as the last factor
     if (p->sched == SC_SCHED_FISSIONED && (p->kind == K_TTMC3 || p->kind == K_MTTKRP3))
         return leaf_traverse_walk_shape(p->dtype, (int)p->fcols[1]);

@@ -6,10 +6,10 @@
 // The temporary of the `where` nest lives in LDS for the fibers of one tile; the consumer is a
 // (16 x Kf) * (Kf x 16) product per slice, Kf = fibers of the slice, on v_mfma_f32_16x16x4_f32.
 //
-//   stage 1  every global read of the tile is issued before the first is used; records
-//            {D row offset, value} per nonzero, fiber bounds, C row offset per fiber, slice
-//            bounds and output rows go to LDS
-//   stage 2  fiber ends marked in the records; first fiber of every lane-group chunk
+//   stage    every global read of the tile is issued before the first is used; records
+//            {D row offset | end-of-fiber bit, value} per nonzero (the coordinates come from the
+//            plan's walk tables with the end bits in them, as do the fibers at the heads of the
+//            lane groups' chunks), C row offset per fiber, slice bounds and output rows go to LDS
 //   walk     the shared branch-free leaf walk (a group of 4 lanes per nonzero chunk, U gathers
 //            in flight, running sums written to the fibers' LDS rows, chunk heads combined
 //            after a barrier without atomics)
@@ -31,7 +31,10 @@
 namespace sck {
 
 struct Ttmc3Args {
-    const int32_t *crd1, *pos2, *crd2, *pos3, *crd3;
+    const int32_t *crd1, *pos2, *crd2;
+    const uint32_t *rec3;    // FUSED: the plan's walk table, last coordinate of every nonzero | end-of-fiber bit 31
+    const uint16_t *heads;   // ... and per tile the chunk heads of the T3_G lane groups
+    int32_t heads_per_tile;
     const float *vals;
     const float *C, *D;
     int64_t ldC, ldD;
@@ -50,7 +53,7 @@ constexpr int T3_LG = 4;            // lanes per row
 constexpr int T3_G = NT / T3_LG;    // lane groups per workgroup
 constexpr int T3_WAVES = NT / 64;
 constexpr int T3_MAXR = 4;          // tn <= T3_MAXR * NT
-constexpr int T3_MAXB = 2;          // ta + 1 <= T3_MAXB * NT, tb + 1 <= NT
+constexpr int T3_U = 8;             // nonzeros a lane group of the leaf walk takes per step
 
 // The carry rows and the nonzero records are dead once the T rows of a tile are complete;
 // the pieces that the consumer parks (WAVES x {head, tail} x 256 floats) reuse their space.
@@ -65,7 +68,7 @@ __host__ __device__ constexpr size_t ttmc3_scratch_bytes(int tn)
 
 __host__ __device__ constexpr size_t ttmc3_lds_bytes(int tn, int ta, int tb)
 {
-    return (size_t)(ta + 1) * T3_RS * 4 + ttmc3_scratch_bytes(tn) + (size_t)(ta + 2 + T3_G + ta + 2 * tb + 2) * 4 + T3_WAVES * 16 + 64;
+    return (size_t)(ta + 1) * T3_RS * 4 + ttmc3_scratch_bytes(tn) + (size_t)(T3_G + ta + 2 * tb + 2) * 4 + T3_WAVES * 16 + 64;
 }
 
 typedef float t3_floatx4 __attribute__((ext_vector_type(4)));
@@ -75,7 +78,7 @@ typedef float t3_floatx4 __attribute__((ext_vector_type(4)));
 template <bool FUSED, bool DET>
 __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const TileRec *__restrict__ tiles)
 {
-    constexpr int U = 8;
+    constexpr int U = T3_U;
     constexpr int RS = T3_RS;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -83,9 +86,8 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     float *carry_s = row_s + (size_t)(a.ta + 1) * RS;                                    // G rows of RS
     Ttmc3Rec *rec_s = reinterpret_cast<Ttmc3Rec *>(carry_s + (size_t)T3_G * RS);         // padded(tn + 8)
     float *part_s = carry_s;                                                             // WAVES x {head, tail} x 256, once carry_s and rec_s are dead
-    int *ba_s = reinterpret_cast<int *>(reinterpret_cast<unsigned char *>(carry_s) + ttmc3_scratch_bytes(a.tn));   // ta + 2
-    int *chunk_lr = ba_s + a.ta + 2;                                                     // G
-    uint32_t *coff_s = reinterpret_cast<uint32_t *>(chunk_lr + T3_G);                    // ta: byte offset of C(j,:)
+    uint32_t *chunk_s = reinterpret_cast<uint32_t *>(reinterpret_cast<unsigned char *>(carry_s) + ttmc3_scratch_bytes(a.tn));   // G: chunk heads of the leaf walk
+    uint32_t *coff_s = chunk_s + T3_G;                                                   // ta: byte offset of C(j,:)
     int *bb_s = reinterpret_cast<int *>(coff_s + a.ta);                                  // tb + 2: first fiber of each slice
     int *crdb_s = bb_s + a.tb + 2;                                                       // tb: output row of each slice
     int *meta_s = crdb_s + a.tb;                                                         // WAVES x 4: head slice, head ends, tail slice
@@ -99,22 +101,21 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     struct Stage {
         uint32_t kk[T3_MAXR];
         float vv[T3_MAXR];
-        int pb[T3_MAXB];
+        uint32_t hd;
         Pack<float, 4> trow[FUSED ? 1 : TR];
         int cj, ps, ci;
     };
-    auto issue = [&](const TileRec &t, Stage &s) {
+    auto issue = [&](const TileRec &t, int tile, Stage &s) {
         const int nchild = t.n1 - t.n0;
         const int na = t.na, nb = t.nb;
         if (FUSED) {
 #pragma unroll
             for (int r = 0; r < T3_MAXR; ++r) {
                 const int c = t.n0 + min(tid + r * NT, nchild - 1);
-                s.kk[r] = (uint32_t)a.crd3[c];
+                s.kk[r] = a.rec3[c];
                 s.vv[r] = a.vals[c];
             }
-#pragma unroll
-            for (int r = 0; r < T3_MAXB; ++r) s.pb[r] = a.pos3[t.a0 + min(tid + r * NT, na)];
+            s.hd = a.heads[(int64_t)tile * a.heads_per_tile + min(tid, T3_G - 1)];
         } else {
 #pragma unroll
             for (int r = 0; r < TR; ++r) {
@@ -128,7 +129,7 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     };
     TileRec t = tiles[first];   // a launched workgroup has at least one tile
     Stage st;
-    issue(t, st);
+    issue(t, first, st);
 
     for (int tile = first; tile < lastp1; ++tile) {
     const TileRec tn = tiles[min(tile + 1, lastp1 - 1)];
@@ -143,7 +144,6 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     {
         const uint32_t(&kk)[T3_MAXR] = st.kk;
         const float(&vv)[T3_MAXR] = st.vv;
-        const int(&pb)[T3_MAXB] = st.pb;
         const auto &trow = st.trow;
         const int cj = st.cj, ps = st.ps, ci = st.ci;
         if (FUSED) {
@@ -152,7 +152,8 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
                 const int c = tid + r * NT;
                 if (c < nchild) {
                     Ttmc3Rec rec;
-                    rec.koff = kk[r] * rowD;
+                    // the tile's last nonzero closes the fiber it is in as far as this tile goes
+                    rec.koff = (kk[r] & 0x7fffffffu) * rowD | (kk[r] & 0x80000000u) | (c == nchild - 1 ? 0x80000000u : 0u);
                     rec.v = vv[r];
                     rec_s[pidx(c)] = rec;
                 }
@@ -163,11 +164,7 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
                 rec.v = 0.f;
                 rec_s[pidx(nchild + tid)] = rec;
             }
-#pragma unroll
-            for (int r = 0; r < T3_MAXB; ++r) {
-                const int i = tid + r * NT;
-                if (i <= na) ba_s[i] = min(max(pb[r], t.n0), t.n1) - t.n0;
-            }
+            if (tid < T3_G) chunk_s[tid] = st.hd;
         } else {
             // A fiber cut by a tile boundary has one complete row in the workspace; the tile in
             // which it starts consumes it, the tiles it continues into see a zero row.
@@ -190,16 +187,14 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     // ---- consumer kernel: the next tile's reads go out now and land while this tile is worked on
     // (the fused kernel has no registers to spare for that: it measured slower with spills) ----
     Stage sn;
-    if (!FUSED && tile + 1 < lastp1) issue(tn, sn);
+    if (!FUSED && tile + 1 < lastp1) issue(tn, tile + 1, sn);
 
-    // ---- stage 2, walk (leaves -> T rows in LDS), combine ----
+    // ---- walk (leaves -> T rows in LDS), combine ----
     if (FUSED) {
-        leaf_mark(rec_s, ba_s, chunk_lr, tid, NT, na, q);
-        __syncthreads();
         const int g = tid / T3_LG, li = tid % T3_LG;
-        const LeafCarry st = leaf_walk<float, T3_W, U>(row_s, carry_s, rec_s, ba_s, chunk_lr, a.D, g, li, q, nchild);
+        const uint32_t done = table_walk<float, T3_W, U>(row_s, carry_s, rec_s, chunk_s, a.D, g, li, q, nchild);
         __syncthreads();
-        leaf_combine<float, T3_W>(row_s, carry_s, ba_s, chunk_lr, st, g, li, q);
+        table_combine<float, T3_W>(row_s, carry_s, chunk_s, done, g, li);
         __syncthreads();
     }
 
@@ -298,18 +293,27 @@ __global__ void __launch_bounds__(NT, 5) ttmc3_mfma_kernel(Ttmc3Args a, const Ti
     }
     __syncthreads();
     if (tile + 1 < lastp1) {
-        if (FUSED) issue(tn, sn);
+        if (FUSED) issue(tn, tile + 1, sn);
         t = tn;
         st = sn;
     }
     }  // tiles of the run
 }
 
+WalkShape ttmc3_mfma_walk_shape()
+{
+    WalkShape w;
+    w.levels = 1;
+    w.groups[0] = T3_G;
+    w.batch[0] = T3_U;
+    return w;
+}
+
 size_t ttmc3_mfma_lds_bytes(const sc_plan *p) { return ttmc3_lds_bytes(p->caps.tn, p->caps.ta, p->caps.tb); }
 
 bool ttmc3_mfma_caps_ok(const sc_plan *p)
 {
-    return p->caps.tn <= T3_MAXR * NT && p->caps.ta + 1 <= T3_MAXB * NT && p->caps.ta <= NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
+    return p->caps.tn <= T3_MAXR * NT && p->caps.ta <= NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
 }
 
 sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
@@ -323,7 +327,13 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * 4 >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
     if ((uint64_t)fac[0].rows * (uint64_t)fac[0].ld * 4 >= (1ull << 32)) return SC_ERR_SHAPE_MISMATCH;
     Ttmc3Args a;
-    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1]; a.pos3 = sp->pos[2]; a.crd3 = sp->crd[2];
+    a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1];
+    a.rec3 = nullptr; a.heads = nullptr; a.heads_per_tile = 0;
+    if (T == nullptr) {   // the leaf level is read from the plan's walk tables
+        const WalkTables &wt = p->walk;
+        if (!wt.d_rec[0] || !wt.d_heads || wt.shape.groups[0] != T3_G || wt.shape.batch[0] != T3_U) return SC_ERR_SCHED_UNSUPPORTED;
+        a.rec3 = wt.d_rec[0]; a.heads = wt.d_heads; a.heads_per_tile = wt.heads_per_tile;
+    }
     a.vals = static_cast<const float *>(sp->vals);
     a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
     a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;
