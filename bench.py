@@ -301,10 +301,11 @@ def main() -> int:
             con = Contraction(cfg["expr"], data0["coords"], data0["vals"], cfg["dims"], factors, sc.schedule("auto"),
                               synth.output_shape(cfg))
             flops, nbytes = sc.plan_model(con.plan)
-            ms, _ = timed(con, 5, 1)
+            mean_ms, st = timed(con, 7, 2)
+            ms = st["median"]   # a point is a handful of launches: the median keeps one slow launch out of it
             text = sc.plan_describe(con.plan)
             chosen = [ln for ln in text.splitlines() if "<- chosen" in ln]
-            rows.append({"L": L, "M": MN, "N": MN, "ms": ms, "gflops": flops / (ms * 1e-3) / 1e9, "chosen": list(sc.plan_chosen(con.plan)),
+            rows.append({"L": L, "M": MN, "N": MN, "ms": ms, "mean_ms": mean_ms, "gflops": flops / (ms * 1e-3) / 1e9, "chosen": list(sc.plan_chosen(con.plan)),
                          "evaluator": chosen[0].strip() if chosen else None, "workspace_bytes": con.ws_bytes})
             del con
             torch.cuda.empty_cache()

@@ -3,18 +3,23 @@
  * executed under the fused / fissioned loop nests of "SparseAuto: An Auto-Scheduler for
  * Sparse Tensor Computations Using Recursive Loop Nest Restructuring" (arXiv 2311.09549).
  *
- * The library executes a schedule; it does not search for one (the auto-scheduler of
- * Section 5 is not part of it).  The caller names the expression and the schedule:
+ * The library executes a schedule; it does not search the space of schedules (the
+ * compile-time stages of the auto-scheduler of Section 5 are not part of it).  The caller
+ * names the expression and the schedule class, or lets the library's run-time stage pick
+ * among the schedules it has kernels for (SC_SCHED_AUTO):
  *
- *   kernel 6 of Table 2   A(i,l,m)   = B(i,j,k) * C(j,l) * D(k,m)             ("ttmc3")
- *   MTTKRP (Section 6)    A(i,r)     = B(i,j,k) * C(j,r) * D(k,r)             ("mttkrp3")
- *   kernel 1 of Table 2   A(i,l)     = S(i,j) * X(i,k) * Y(j,k) * Z(j,l)      ("sddmm_spmm")
- *   order-4 TTM chain     A(i,l,m,n) = B(i,j,k,p) * C(j,l) * D(k,m) * E(p,n)  ("ttmc4")
+ *   kernel 6 of Table 2   A(i,l,m)   = B(i,j,k) * C(j,l) * D(k,m)                    ("ttmc3")
+ *   MTTKRP (Section 6)    A(i,r)     = B(i,j,k) * C(j,r) * D(k,r)                    ("mttkrp3")
+ *   kernel 1 of Table 2   A(i,l)     = S(i,j) * X(i,k) * Y(j,k) * Z(j,l)             ("sddmm_spmm")
+ *   order-4 TTM chain     A(i,l,m,n) = B(i,j,k,p) * C(j,l) * D(k,m) * E(p,n)         ("ttmc4")
+ *   kernel 5 of Table 2   A(l,m,n)   = B(i,j,k) * C(i,l) * D(j,m) * E(k,n)           ("ttmc_all")
+ *   kernel 8 of Table 2   A(i,m)     = B(i,j,k) * C(j,r) * D(k,r) * E(r,m)           ("mttkrp_gemm")
+ *   kernel 2 of Table 2   A(i,m)     = S(i,j) * X(i,k) * Y(j,k) * Z(j,l) * E(l,m)    ("sddmm_spmm_gemm")
  *
  * Index names are free; the FIRST operand on the right-hand side is the sparse one, its
- * first index must be the first output index, and the remaining operands are dense
- * row-major matrices passed in expression order.  Anything outside this family is
- * rejected with SC_ERR_EXPR_UNSUPPORTED.
+ * first index must be the first output index (except in kernel 5, whose output has no
+ * sparse index), and the remaining operands are dense row-major matrices passed in
+ * expression order.  Anything outside this family is rejected with SC_ERR_EXPR_UNSUPPORTED.
  *
  * Conventions
  *   - Every function returns an sc_status (0 = SC_OK), never throws, never aborts,
@@ -27,7 +32,9 @@
  *     index fastest, and is fully overwritten (rows of empty slices become +0).
  *   - `on_device` says whether the pointers of a view are host (0) or device (1) memory.
  *   - sc_execute allocates nothing, never synchronises and launches only on the stream
- *     it is given.  sc_plan_create may allocate a few small plan-owned device tables.
+ *     it is given.  sc_plan_create allocates the plan-owned device tables: tile records and,
+ *     for the kernels that use them, walk tables (4 bytes per stored nonzero and per node of
+ *     the level above, see sc_plan_create).
  */
 #ifndef SPARSECONTRACT_H
 #define SPARSECONTRACT_H
@@ -171,8 +178,14 @@ sc_status sc_coo_to_csf(const sc_coo_view *coo, sc_csf_view *out);
  * "A(i,l,m)=B(i,j,k)*C(j,l)*D(k,m)".  `sparse` may be a host or a device view: its pos
  * arrays (and, for host views, its crd arrays) are checked and the equal-work tile tables
  * are built from them.  Of `factors` only rows / cols / dtype are read.  If a GPU is
- * present the tile tables are uploaded into plan-owned device memory; without one the plan
- * is still created (for validation, sizing and description) but cannot execute. */
+ * present the tile tables are uploaded into plan-owned device memory, together with the
+ * walk tables of the kernels that use them (the leaf traversal of the FISSIONED schedules,
+ * the matrix-core kernels of the TTM chains): a copy of the coordinates of the walked levels
+ * with the end-of-node bit folded into bit 31 (4 bytes per stored nonzero, and per node of
+ * the level above for the order-4 chain) and 2 bytes per tile and lane group.  Those kernels
+ * read the copy instead of the view's arrays of these levels, which is why an execution
+ * must be given the view the plan was made from.  Without a GPU the plan is still created
+ * (for validation, sizing and description) but cannot execute. */
 sc_status sc_plan_create(sc_plan **out, const char *expr, const sc_csf_view *sparse,
                          const sc_dense_view *factors, int32_t nfactors, const sc_schedule *sched);
 

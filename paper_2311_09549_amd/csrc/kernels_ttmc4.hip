@@ -259,7 +259,7 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
         // tid / 16 + 16 r; their offsets are in LDS by now) and are parked in the space of the T1 rows as soon
         // as those are dead.  The consumer then reads both operands of its MFMAs from LDS instead of gathering
         // C in its inner loop, where the gather's latency was paid once per block of fibers.
-        const bool c_in_lds = MODE == 0 && a.tb * 16 <= (a.ta + 1) * RS1;
+        const bool c_in_lds = MODE == 0 && (a.tb + 15) * 16 <= (a.ta + 1) * RS1;   // 15 rows of slack: the consumer reads past a slice's last fiber
         float cval[T4_TR2];
         if (c_in_lds) {
             const char *Cl = reinterpret_cast<const char *>(a.C) + min(tid % 16, L - 1) * 4;
@@ -386,16 +386,28 @@ __global__ void __launch_bounds__(NT) ttmc4_mfma_kernel(Ttmc4Args a, const TileR
                     constexpr int UB = 4;   // 4-fiber blocks whose operand reads are issued together
                     for (int fb = f0; fb < f1; fb += 4 * UB) {
                         float cv[UB], tv[UB];
+                        if (CL) {
+                            // both operands at fixed distances from one address per lane: lanes past the slice read
+                            // rows of the next slice or unused rows of the same arrays, and both values are dropped
+                            const float *t2p = row2_s + (fb + kk) * RS2 + wave * 16 + col;
+                            const float *c1p = row1_s + (fb + kk) * 16 + col;
 #pragma unroll
-                        for (int ub = 0; ub < UB; ++ub) {
-                            const int lf = fb + 4 * ub + kk;
-                            const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
-                            const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
-                            float cvr;
-                            if (CL) cvr = row1_s[lfc * 16 + col];
-                            else cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
-                            tv[ub] = lf < f1 ? tvr : 0.f;
-                            cv[ub] = lval ? cvr : 0.f;
+                            for (int ub = 0; ub < UB; ++ub) {
+                                const bool in_slice = fb + 4 * ub + kk < f1;
+                                const float tvr = t2p[ub * 4 * RS2], cvr = c1p[ub * 64];
+                                tv[ub] = in_slice ? tvr : 0.f;
+                                cv[ub] = in_slice ? cvr : 0.f;   // rows l >= L of C are zeros in LDS
+                            }
+                        } else {
+#pragma unroll
+                            for (int ub = 0; ub < UB; ++ub) {
+                                const int lf = fb + 4 * ub + kk;
+                                const int lfc = min(lf, f1 - 1);   // lanes past the slice read a valid fiber and are zeroed
+                                const float tvr = row2_s[lfc * RS2 + wave * 16 + col];
+                                const float cvr = *reinterpret_cast<const float *>(Cb + coff2_s[lfc]);
+                                tv[ub] = lf < f1 ? tvr : 0.f;
+                                cv[ub] = lval ? cvr : 0.f;
+                            }
                         }
 #pragma unroll
                         for (int ub = 0; ub < UB; ++ub)
