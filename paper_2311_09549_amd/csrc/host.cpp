@@ -462,6 +462,8 @@ void build_tiles(const sc_csf_view *v, const HostCsf &h, const TileCaps &caps, s
     }
 }
 
+void appendf(std::string &s, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // Walk tables of a plan (see WalkTables): the coordinate arrays of the two lowest levels with the
 // end-of-node bits folded in, and per tile the node at the head of every lane group's chunk.  `order`
 // is the device tile table.
@@ -470,6 +472,8 @@ sc_status build_walk_tables(sc_plan *p, const sc_csf_view *v, const HostCsf &h, 
     WalkTables &w = p->walk;
     const int d = v->order;
     if (w.shape.levels <= 0 || !h.have_crd || order.empty()) return SC_OK;
+    if (p->caps.ta > 0x7fff || p->caps.tb > 0x7fff) return SC_ERR_SCHED_UNSUPPORTED;   // a chunk head holds a tile-local node number in 15 bits
+    size_t table_bytes = 0;
     try {
         for (int lv = 0; lv < w.shape.levels; ++lv) {
             const int m = d - 1 - lv;                 // CSF level of the children
@@ -479,6 +483,7 @@ sc_status build_walk_tables(sc_plan *p, const sc_csf_view *v, const HostCsf &h, 
             for (int64_t f = 0; f < nparent; ++f) rec[(size_t)h.pos[m][f + 1] - 1] |= 0x80000000u;
             if (hipMalloc((void **)&w.d_rec[lv], sizeof(uint32_t) * (size_t)n) != hipSuccess) return SC_ERR_DEVICE;
             if (hipMemcpy(w.d_rec[lv], rec.data(), sizeof(uint32_t) * (size_t)n, hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
+            table_bytes += sizeof(uint32_t) * (size_t)n;
         }
         const int g0 = w.shape.groups[0], g1 = w.shape.levels > 1 ? w.shape.groups[1] : 0;
         w.heads_per_tile = (g0 + g1 + 1) / 2 * 2;
@@ -512,6 +517,9 @@ sc_status build_walk_tables(sc_plan *p, const sc_csf_view *v, const HostCsf &h, 
         }
         if (hipMalloc((void **)&w.d_heads, sizeof(uint16_t) * heads.size()) != hipSuccess) return SC_ERR_DEVICE;
         if (hipMemcpy(w.d_heads, heads.data(), sizeof(uint16_t) * heads.size(), hipMemcpyHostToDevice) != hipSuccess) return SC_ERR_DEVICE;
+        table_bytes += sizeof(uint16_t) * heads.size();
+        appendf(p->text, "walk tables: %zu bytes of plan-owned device memory (coordinates of the walked levels with the end-of-node bits, chunk heads per tile)\n",
+                table_bytes);
     } catch (const std::bad_alloc &) { return SC_ERR_ALLOC; }
     return SC_OK;
 }
