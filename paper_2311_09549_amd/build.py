@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libsparsecontract.so")
-SOURCES = ["host.cpp", "kernels.hip", "kernels_linear.hip", "kernels_order2.hip", "kernels_order4.hip", "kernels_traverse.hip", "kernels_ttmc3.hip", "kernels_ttmc4.hip", "kernels_ttmc_all.hip", "kernels_gemm.hip", "static_scratch.hip"]
+SOURCES = ["host.cpp", "kernels.hip", "kernels_linear.hip", "kernels_order2.hip", "kernels_order4.hip", "kernels_traverse.hip", "kernels_ttmc3.hip", "kernels_ttmc3w.hip", "kernels_ttmc4.hip", "kernels_ttmc_all.hip", "kernels_gemm.hip", "static_scratch.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

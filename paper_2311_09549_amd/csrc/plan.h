@@ -216,6 +216,9 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 // table in tensor order rather than interleaved.
 bool plan_wants_tensor_order(const sc_plan *plan);
 
+// True for the FUSED order-3 chains that run the matrix-core kernel for rank pairs beyond 16 x 16 (kernels_ttmc3w.hip).
+bool plan_uses_wide_ttmc3(const sc_plan *plan);
+
 // True when the kernels of the plan can run without floating-point atomics (FUSED schedules of
 // the kernels that emit one piece per tile and shared row).
 bool plan_supports_deterministic(const sc_plan *plan);
