@@ -226,11 +226,12 @@ sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void 
 
 // Order-4 TTM chain on matrix cores (fp32, M = N = 8, L <= 16; its own kernel file): mode 0 the FUSED schedule,
 // modes 1 and 2 the second and third kernel of the FISSIONED one.
-// kernels_ttmc3w.hip: FUSED order-3 chain on matrix cores for rank pairs that are multiples of 16 (other than 16 x 16)
+// kernels_ttmc3w.hip: order-3 chain on matrix cores for rank pairs that are multiples of 16 (other than 16 x 16), fused and
+// the consumer kernel of the FISSIONED schedule
 bool ttmc3_wide_ranks(int64_t L, int64_t W);
 WalkShape ttmc3_wide_walk_shape(int W);
 size_t ttmc3_wide_lds_bytes(const sc_plan *p);
-sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out);
+sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out);
 
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p);
 WalkShape ttmc4_mfma_walk_shape();

@@ -742,7 +742,7 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             return launch_fixup(p, ln, p->det_top, ws, out);
         } else if (plan_uses_wide_ttmc3(p)) {
             if constexpr (sizeof(T) == 4) {
-                ln.status = launch_ttmc3_wide(p, ln, sp, fac, out);
+                ln.status = launch_ttmc3_wide(p, ln, sp, fac, nullptr, out);
                 return ln.status;
             }
         } else {
@@ -776,6 +776,11 @@ sc_status run_order3(const sc_plan *p, const sc_csf_view *sp, const sc_dense_vie
             ln.status = launch_ttmc3_mfma(p, ln, sp, fac, a.T, out, a.partials);
             if (ln.status != SC_OK) return ln.status;
             return launch_fixup(p, ln, p->det_top, ws, out);
+        } else if (plan_uses_wide_ttmc3(p)) {
+            if constexpr (sizeof(T) == 4) {
+                ln.status = launch_ttmc3_wide(p, ln, sp, fac, a.T, out);
+                return ln.status;
+            }
         } else {
             if constexpr (can_mf) {
                 if (mf) {
@@ -892,12 +897,13 @@ sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void 
     return ln.status;
 }
 
-// FUSED order-3 chains whose ranks are multiples of the MFMA tile (other than 16 x 16) run the kernel that keeps a
-// slice's output tiles in registers across the work tiles of a run; deterministic plans stay with the general kernel.
+// Order-3 chains whose ranks are multiples of the MFMA tile (other than 16 x 16) run the kernel that keeps a slice's
+// output tiles in registers across the work tiles of a run (FUSED, and as the consumer behind the leaf traversal);
+// deterministic plans stay with the general kernel.
 bool plan_uses_wide_ttmc3(const sc_plan *p)
 {
-    return p->kind == K_TTMC3 && p->dtype == SC_F32 && p->sched == SC_SCHED_FUSED && !p->deterministic &&
-           ttmc3_wide_ranks(p->fcols[0], p->fcols[1]);
+    return p->kind == K_TTMC3 && p->dtype == SC_F32 && (p->sched == SC_SCHED_FUSED || p->sched == SC_SCHED_FISSIONED) &&
+           !p->deterministic && ttmc3_wide_ranks(p->fcols[0], p->fcols[1]);
 }
 
 bool plan_wants_tensor_order(const sc_plan *p)
@@ -912,7 +918,7 @@ WalkShape plan_walk_shape(const sc_plan *p)
 {
     if (p->sched == SC_SCHED_LINEAR) return WalkShape{};
     if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_walk_shape();   // its leaf level also serves the traversal kernel
-    if (plan_uses_wide_ttmc3(p)) return ttmc3_wide_walk_shape((int)p->fcols[1]);
+    if (plan_uses_wide_ttmc3(p) && p->sched == SC_SCHED_FUSED) return ttmc3_wide_walk_shape((int)p->fcols[1]);
     if (p->kind == K_TTMC3 && p->sched == SC_SCHED_FUSED && plan_wants_tensor_order(p)) return ttmc3_mfma_walk_shape();
     // FISSIONED, order >= 3: the leaf traversal, whose rows are as wide as the last factor
     if (p->sched == SC_SCHED_FISSIONED && (p->kind == K_TTMC3 || p->kind == K_MTTKRP3))
@@ -934,7 +940,9 @@ size_t lds_bytes_needed(const sc_plan *p)
             return p->dtype == SC_F64 ? mttkrp_lds_bytes<double>(w, p->caps.tn, p->caps.ta, p->caps.tb)
                                       : mttkrp_lds_bytes<float>(w, p->caps.tn, p->caps.ta, p->caps.tb);
         }
-        if (plan_uses_wide_ttmc3(p)) return ttmc3_wide_lds_bytes(p);
+        if (plan_uses_wide_ttmc3(p))
+            return p->sched == SC_SCHED_FUSED ? ttmc3_wide_lds_bytes(p)
+                                              : std::max(ttmc3_wide_lds_bytes(p), leaf_traverse_lds_bytes(p, (int)producer_width(p)));
         if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) {
             if (!ttmc3_mfma_caps_ok(p)) return SIZE_MAX;
             if (p->sched != SC_SCHED_FISSIONED) return ttmc3_mfma_lds_bytes(p);

@@ -1,5 +1,6 @@
 // TTM chain of order 3 on matrix cores for fp32 ranks that are multiples of the 16 x 16 MFMA tile (Table 2,
-// kernel 6 <SpTTM, TTM>; also the sparse part of kernel 5's second schedule), FUSED schedule:
+// kernel 6 <SpTTM, TTM>; also the sparse part of kernel 5's second schedule): the FUSED schedule in one kernel and,
+// with FUSED = false, the consumer half of the FISSIONED schedule (the rows of T then come from the workspace):
 //     T(f,:)    = sum_{k' in fiber f} B * D(k,:)                       (producer, leaf walk; W = 16 MT columns)
 //     A(i,:,:) += C(j,:)^T (x) T(f,:)   over the fibers of slice i     (consumer; L = 16 LT rows of C)
 // The consumer of a slice is an (L x Kf) * (Kf x W) product, Kf = fibers of the slice.  Its LT x MT output tiles
@@ -27,6 +28,7 @@ struct Ttmc3wArgs {
     const float *vals;
     const float *C, *D;
     int64_t ldC, ldD;
+    const float *T;   // FISSIONED consumer: the materialised temporary, one W-wide row per fiber
     float *A;
     int32_t tn, ta, tb;
     int32_t ntiles, run;   // tiles in the plan; tiles per workgroup
@@ -46,7 +48,7 @@ __host__ __device__ constexpr size_t ttmc3w_lds_bytes(int L, int W, int tn, int 
 
 typedef float t3w_floatx4 __attribute__((ext_vector_type(4)));
 
-template <int LT, int MT>
+template <int LT, int MT, bool FUSED>
 __global__ void __launch_bounds__(NT) ttmc3_wide_kernel(Ttmc3wArgs a, const TileRec *__restrict__ tiles)
 {
     constexpr int L = 16 * LT, W = 16 * MT;
@@ -93,13 +95,15 @@ __global__ void __launch_bounds__(NT) ttmc3_wide_kernel(Ttmc3wArgs a, const Tile
     };
     auto issue = [&](const TileRec &t, int tile, Stage &s) {
         const int nchild = t.n1 - t.n0;
+        if (FUSED) {
 #pragma unroll
-        for (int r = 0; r < T3W_MAXR; ++r) {
-            const int c = t.n0 + min(tid + r * NT, nchild - 1);
-            s.kk[r] = a.rec3[c];
-            s.vv[r] = a.vals[c];
+            for (int r = 0; r < T3W_MAXR; ++r) {
+                const int c = t.n0 + min(tid + r * NT, nchild - 1);
+                s.kk[r] = a.rec3[c];
+                s.vv[r] = a.vals[c];
+            }
+            s.hd = a.heads[(int64_t)tile * a.heads_per_tile + min(tid, G - 1)];
         }
-        s.hd = a.heads[(int64_t)tile * a.heads_per_tile + min(tid, G - 1)];
         s.cj = a.crd2[t.a0 + min(tid, t.na - 1)];
         s.ps = a.pos2[t.b0 + min(tid, t.nb)];
         s.ci = a.crd1[t.b0 + min(tid, t.nb - 1)];
@@ -117,24 +121,26 @@ __global__ void __launch_bounds__(NT) ttmc3_wide_kernel(Ttmc3wArgs a, const Tile
         const int q = leaf_chunk<U>(nchild, G);
 
         // ---- stage: registers -> LDS ----
+        if (FUSED) {
 #pragma unroll
-        for (int r = 0; r < T3W_MAXR; ++r) {
-            const int c = tid + r * NT;
-            if (c < nchild) {
-                Rec rec;
-                // the tile's last nonzero closes the fiber it is in as far as this tile goes
-                rec.koff = (st.kk[r] & 0x7fffffffu) * rowD | (st.kk[r] & 0x80000000u) | (c == nchild - 1 ? 0x80000000u : 0u);
-                rec.v = st.vv[r];
-                rec_s[pidx(c)] = rec;
+            for (int r = 0; r < T3W_MAXR; ++r) {
+                const int c = tid + r * NT;
+                if (c < nchild) {
+                    Rec rec;
+                    // the tile's last nonzero closes the fiber it is in as far as this tile goes
+                    rec.koff = (st.kk[r] & 0x7fffffffu) * rowD | (st.kk[r] & 0x80000000u) | (c == nchild - 1 ? 0x80000000u : 0u);
+                    rec.v = st.vv[r];
+                    rec_s[pidx(c)] = rec;
+                }
             }
+            if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
+                Rec rec;
+                rec.koff = 0;
+                rec.v = 0.f;
+                rec_s[pidx(nchild + tid)] = rec;
+            }
+            if (tid < G) chunk_s[tid] = st.hd;
         }
-        if (tid < U) {  // dummies completing the last batch: value 0, row 0, no mark
-            Rec rec;
-            rec.koff = 0;
-            rec.v = 0.f;
-            rec_s[pidx(nchild + tid)] = rec;
-        }
-        if (tid < G) chunk_s[tid] = st.hd;
         if (tid < na) cj_s[tid] = st.cj;
         if (tid <= nb) bb_s[tid] = min(max(st.ps, t.a0), t.a0 + na) - t.a0;
         if (tid < nb) crdb_s[tid] = st.ci;
@@ -155,8 +161,21 @@ __global__ void __launch_bounds__(NT) ttmc3_wide_kernel(Ttmc3wArgs a, const Tile
             }
         }
 
-        // ---- walk (leaves -> T rows in LDS), combine ----
-        {
+        // ---- T rows of the tile's fibers: the leaf walk (FUSED), or the rows the traversal kernel left in the workspace.  A fiber
+        // cut by a tile boundary has one complete row there; the tile in which it starts consumes it, the tiles it continues
+        // into see a zero row. ----
+        if (!FUSED) {
+            constexpr int VPR = W / 4;
+            const float *Tg = a.T + (int64_t)t.a0 * W;
+#pragma unroll 4
+            for (int idx = tid; idx < na * VPR; idx += NT) {
+                const int f = idx / VPR, q4 = (idx % VPR) * 4;
+                t3w_floatx4 v = *reinterpret_cast<const t3w_floatx4 *>(Tg + (int64_t)f * W + q4);
+                if (f == 0 && (t.flags & 1)) v = t3w_floatx4{0.f, 0.f, 0.f, 0.f};
+                *reinterpret_cast<t3w_floatx4 *>(row_s + f * RS + q4) = v;
+            }
+            __syncthreads();
+        } else {
             const int g = tid / LG, li = tid % LG;
             const uint32_t done = table_walk<float, W, U>(row_s, carry_s, rec_s, chunk_s, a.D, g, li, q, nchild);
             __syncthreads();
@@ -227,7 +246,10 @@ namespace {
 template <int LT, int MT>
 void launch_wide(const Ttmc3wArgs &a, const TileRec *tiles, int blocks, size_t lds, hipStream_t stream)
 {
-    ttmc3_wide_kernel<LT, MT><<<blocks, NT, lds, stream>>>(a, tiles);
+    if (a.T)
+        ttmc3_wide_kernel<LT, MT, false><<<blocks, NT, lds, stream>>>(a, tiles);
+    else
+        ttmc3_wide_kernel<LT, MT, true><<<blocks, NT, lds, stream>>>(a, tiles);
 }
 
 template <int LT>
@@ -266,20 +288,25 @@ size_t ttmc3_wide_lds_bytes(const sc_plan *p)
     return ttmc3w_lds_bytes((int)p->fcols[0], (int)p->fcols[1], p->caps.tn, p->caps.ta, p->caps.tb);
 }
 
-sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, void *out)
+sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out)
 {
+    // T == nullptr: FUSED schedule; otherwise the consumer kernel of the FISSIONED schedule
     const int ntiles = (int)p->tiles.size();
     if (ntiles == 0) return SC_OK;
     const int L = (int)p->fcols[0], W = (int)p->fcols[1];
     if (!ttmc3_wide_ranks(L, W) || ttmc3_wide_lds_bytes(p) == SIZE_MAX) return SC_ERR_SCHED_UNSUPPORTED;
     // D rows are addressed with 31-bit byte offsets (bit 31 marks fiber ends)
     if ((uint64_t)fac[1].rows * (uint64_t)fac[1].ld * 4 >= (1ull << 31)) return SC_ERR_SHAPE_MISMATCH;
-    const WalkTables &wt = p->walk;
-    const WalkShape want = ttmc3_wide_walk_shape(W);
-    if (!wt.d_rec[0] || !wt.d_heads || wt.shape.groups[0] != want.groups[0] || wt.shape.batch[0] != want.batch[0]) return SC_ERR_SCHED_UNSUPPORTED;
     Ttmc3wArgs a;
     a.crd1 = sp->crd[0]; a.pos2 = sp->pos[1]; a.crd2 = sp->crd[1];
-    a.rec3 = wt.d_rec[0]; a.heads = wt.d_heads; a.heads_per_tile = wt.heads_per_tile;
+    a.rec3 = nullptr; a.heads = nullptr; a.heads_per_tile = 0;
+    if (T == nullptr) {   // the leaf level is read from the plan's walk tables
+        const WalkTables &wt = p->walk;
+        const WalkShape want = ttmc3_wide_walk_shape(W);
+        if (!wt.d_rec[0] || !wt.d_heads || wt.shape.groups[0] != want.groups[0] || wt.shape.batch[0] != want.batch[0]) return SC_ERR_SCHED_UNSUPPORTED;
+        a.rec3 = wt.d_rec[0]; a.heads = wt.d_heads; a.heads_per_tile = wt.heads_per_tile;
+    }
+    a.T = static_cast<const float *>(T);
     a.vals = static_cast<const float *>(sp->vals);
     a.C = static_cast<const float *>(fac[0].data); a.ldC = fac[0].ld;
     a.D = static_cast<const float *>(fac[1].data); a.ldD = fac[1].ld;
@@ -293,7 +320,7 @@ sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.ntiles = ntiles;
     a.run = (ntiles + want_blocks - 1) / want_blocks;
     const int blocks = (ntiles + a.run - 1) / a.run;
-    ln.begin("ttmc3_fused_mfma_wide");
+    ln.begin(T ? "ttmc3_consume_mfma_wide" : "ttmc3_fused_mfma_wide");
     bool ok = false;
     switch (L / 16) {
     case 1: ok = dispatch_m<1>(W / 16, a, p->d_tiles, blocks, lds, ln.stream); break;
