@@ -17,9 +17,10 @@
 //
 // Both reductions are deterministic: a workgroup sums a contiguous chunk of slices (fibers) into an
 // L x (M N) tile in registers and stores it in its own slot of the workspace; sum_partials adds the
-// slots in chunk order.  The reduction over i is a dense (L x I) * (I x MN) product with I large
-// and L small: 2 L flops per 4-byte element of S read, bound by memory traffic at the ranks of
-// Table 7 up to about L = 64, so it runs on the vector ALUs.
+// slots in chunk order.  The reduction over i is a dense (L x I) * (I x MN) product with I large:
+// 2 L flops per 4-byte element of S read.  At L = 16 it is bound by reading S and runs on the vector
+// ALUs (a thread per column, 16 values of l in registers); from L = 32 up it runs on the matrix cores
+// with all of L per workgroup, so that S is still read once.
 #include "device_common.h"
 
 namespace sck {
@@ -78,6 +79,51 @@ __global__ void __launch_bounds__(NT) mode0_reduce_kernel(K5Args a)
         T *P = static_cast<T *>(a.partials) + (int64_t)blockIdx.x * a.L * a.MN;
         for (int l = 0; l < nl; ++l) P[(int64_t)(l0 + l) * a.MN + c] = acc[l];
     }
+}
+
+// The same partial sums on the matrix cores, fp32, L = 16 LT from 32 up, M N a multiple of 64: a workgroup takes all of L
+// for 64 columns (a wavefront for 16 of them), so S is read once instead of once per 16 values of l; four slices per
+// v_mfma_f32_16x16x4_f32 with C^T as operand A (l along the rows) and S as operand B, both straight from global memory
+// (a lane's 16 neighbours read 64 contiguous bytes of a row).
+typedef float k5_floatx4 __attribute__((ext_vector_type(4)));
+template <int LT>
+__global__ void __launch_bounds__(NT) mode0_reduce_mfma_kernel(K5Args a)
+{
+    constexpr int UK = 4;   // steps of four slices whose operand reads are issued together
+    const int tid = threadIdx.x;
+    const int wave = tid / 64, lane = tid % 64, kk = lane / 16, col = lane % 16;
+    const int c = blockIdx.y * 64 + wave * 16 + col;   // < M N: the launch has M N / 64 workgroups along y
+    const int64_t r0 = (int64_t)blockIdx.x * a.chunk, r1 = min(r0 + a.chunk, a.rows);
+    const float *C = static_cast<const float *>(a.C) + col;
+    const float *S = static_cast<const float *>(a.S) + c;
+    k5_floatx4 acc[LT];
+#pragma unroll
+    for (int lt = 0; lt < LT; ++lt) acc[lt] = k5_floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int64_t rb = r0; rb < r1; rb += 4 * UK) {
+        float sv[UK], cv[UK][LT];
+#pragma unroll
+        for (int u = 0; u < UK; ++u) {
+            const int64_t row = rb + 4 * u + kk, rc = min(row, r1 - 1);   // lanes past the chunk read its last slice and are zeroed
+            const bool ok = row < r1;
+            const float s = S[rc * (int64_t)a.MN];
+            sv[u] = ok ? s : 0.f;
+#pragma unroll
+            for (int lt = 0; lt < LT; ++lt) {
+                const float v = C[rc * a.ldC + lt * 16];
+                cv[u][lt] = ok ? v : 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UK; ++u)
+#pragma unroll
+            for (int lt = 0; lt < LT; ++lt) acc[lt] = __builtin_amdgcn_mfma_f32_16x16x4f32(cv[u][lt], sv[u], acc[lt], 0, 0, 0);
+    }
+    // acc[lt][r] = partial(l = 16 lt + 4 kk + r, column c)
+    float *P = static_cast<float *>(a.partials) + (int64_t)blockIdx.x * a.L * a.MN + c;
+#pragma unroll
+    for (int lt = 0; lt < LT; ++lt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) P[(int64_t)(lt * 16 + 4 * kk + r) * a.MN] = acc[lt][r];
 }
 
 // partial(b, l, (m,n)) = sum_{fibers f in chunk b} C(i_f,l) * D(j_f,m) * t(f,n); thread = (m,n)
@@ -266,9 +312,24 @@ sc_status run_ttmc_all(const sc_plan *p, const sc_csf_view *sp, const sc_dense_v
         if (st != SC_OK) return st;
         a.S = S;
         a.rows = p->dims[0];
-        ln.begin("ttmc_all_mode0_reduce");
-        mode0_reduce_kernel<T><<<grid, NT, 0, stream>>>(a);
-        ln.end();
+        if (p->k5_mfma_reduce) {
+            if constexpr (sizeof(T) == 4) {
+                if (MN % 64 != 0) return SC_ERR_SCHED_UNSUPPORTED;
+                const dim3 mgrid((unsigned)p->k5_nchunks, (unsigned)(MN / 64), 1);
+                ln.begin("ttmc_all_mode0_reduce_mfma");
+                if (L == 32) mode0_reduce_mfma_kernel<2><<<mgrid, NT, 0, stream>>>(a);
+                else if (L == 64) mode0_reduce_mfma_kernel<4><<<mgrid, NT, 0, stream>>>(a);
+                else if (L == 128) mode0_reduce_mfma_kernel<8><<<mgrid, NT, 0, stream>>>(a);
+                else return SC_ERR_SCHED_UNSUPPORTED;
+                ln.end();
+            } else {
+                return SC_ERR_SCHED_UNSUPPORTED;
+            }
+        } else {
+            ln.begin("ttmc_all_mode0_reduce");
+            mode0_reduce_kernel<T><<<grid, NT, 0, stream>>>(a);
+            ln.end();
+        }
     }
     ln.begin("ttmc_all_sum_partials");
     sum_partials_kernel<T><<<(unsigned)((elems + 63) / 64), NT, 0, stream>>>(static_cast<const T *>(a.partials), (int)p->k5_nchunks, elems,
