@@ -842,8 +842,11 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
             c.ta = (int32_t)std::max<int64_t>(32, std::min<int64_t>(512, (16 * 1024) / (w * e)));
             c.tb = c.ta;
             if (dtype == SC_F32 && order3_mfma_ranks((int)fcols[0], (int)w)) {
-                // matrix-core consumer of the general kernel: T rows and C rows of a tile share about 28 KB
-                c.ta = (int32_t)std::max<int64_t>(16, std::min<int64_t>(256, (28 * 1024) / ((w + 4 + fcols[0] + 4) * 4)));
+                // matrix-core consumers (the kernel for rank pairs beyond 16 x 16, and the general kernel under a
+                // deterministic schedule): T rows and C rows of a tile share about 26 KB; 768 nonzeros and 112 fibers
+                // measured best on the uniform 11.5 M-nonzero case at 16 x 32
+                c.tn = 768;
+                c.ta = (int32_t)std::max<int64_t>(16, std::min<int64_t>(256, (26 * 1024) / ((w + 4 + fcols[0] + 4) * 4)));
                 c.tb = c.ta;
             }
             if (dtype == SC_F32 && fcols[0] == 16 && fcols[1] == 16) {

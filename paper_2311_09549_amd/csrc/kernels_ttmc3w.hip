@@ -35,7 +35,7 @@ struct Ttmc3wArgs {
 };
 
 constexpr int T3W_U = 4;      // nonzeros a lane group of the leaf walk takes per step
-constexpr int T3W_MAXR = 2;   // tn <= T3W_MAXR * NT; ta, tb + 1 <= NT
+constexpr int T3W_MAXR = 4;   // tn <= T3W_MAXR * NT; ta, tb + 1 <= NT
 
 __host__ __device__ constexpr int t3w_groups(int W) { return NT / (W / 4); }
 
