@@ -216,6 +216,7 @@ sc_status launch_leaf_producer(const sc_plan *p, Launcher &ln, const void *vals,
 size_t ttmc3_mfma_lds_bytes(const sc_plan *p);
 WalkShape ttmc3_mfma_walk_shape();
 bool ttmc3_mfma_caps_ok(const sc_plan *p);
+int ttmc3_mfma_run(const sc_plan *p, bool one_tile_per_workgroup);
 // `partials`: deterministic schedules only (else null): slots for the pieces of rows that span tiles.
 sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
                             void *partials);
@@ -231,11 +232,13 @@ sc_status launch_fixup(const sc_plan *p, Launcher &ln, const FixLevel &lv, void 
 bool ttmc3_wide_ranks(int64_t L, int64_t W);
 WalkShape ttmc3_wide_walk_shape(int W);
 size_t ttmc3_wide_lds_bytes(const sc_plan *p);
+int ttmc3_wide_run(const sc_plan *p);
 sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out);
 
 size_t ttmc4_mfma_lds_bytes(const sc_plan *p);
 WalkShape ttmc4_mfma_walk_shape();
 bool ttmc4_mfma_caps_ok(const sc_plan *p);
+int ttmc4_mfma_run(const sc_plan *p, int mode, bool one_tile_per_workgroup);
 sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
                             void *T2, void *out, void *partials);
 

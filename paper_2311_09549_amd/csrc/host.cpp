@@ -552,11 +552,26 @@ void list_rows_to_zero(sc_plan *p, const HostCsf &h)
     p->zero_rows.clear();
     for (int64_t r = 0; r < rows; ++r)
         if (!stored[(size_t)r]) p->zero_rows.push_back((int32_t)r);
-    if (!p->deterministic)
-        for (const TileRec &t : p->tiles) {
+    if (!p->deterministic) {
+        // Kernels that take one tile per workgroup add every piece of a spanning slice atomically.  The persistent
+        // kernels keep such a slice in registers from tile to tile of a run and add only what crosses a run's end.
+        const int run = plan_output_run(p);
+        int32_t last_listed = -1;
+        for (size_t n = 0; n < p->tiles.size(); ++n) {
+            const TileRec &t = p->tiles[n];
             const TopLevel tl = top_level(p->order, t);
-            if (tl.out && !(tl.in && tl.ntop == 1)) p->zero_rows.push_back(h.crd[0][tl.top0 + tl.ntop - 1]);   // a spanning slice, listed where it starts
+            if (!tl.out) continue;
+            const int32_t row = h.crd[0][tl.top0 + tl.ntop - 1];
+            if (run > 0) {
+                if ((n + 1) % (size_t)run != 0) continue;        // continues inside the run
+                if (row == last_listed) continue;                // a slice crossing several runs' ends is listed once
+            } else if (tl.in && tl.ntop == 1) {
+                continue;                                        // listed where the slice starts
+            }
+            p->zero_rows.push_back(row);
+            last_listed = row;
         }
+    }
     p->zero_selective = (int64_t)p->zero_rows.size() * 2 <= rows;
     if (!p->zero_selective) {
         p->zero_rows.clear();

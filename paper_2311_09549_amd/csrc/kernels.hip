@@ -917,6 +917,17 @@ bool plan_wants_tensor_order(const sc_plan *p)
     return p->kind == K_TTMC4 && p->fcols[0] <= 16 && p->fcols[1] == 8 && p->fcols[2] == 8;   // the matrix-core kernels of the order-4 chain
 }
 
+int plan_output_run(const sc_plan *p)
+{
+    if (p->sched != SC_SCHED_FUSED && p->sched != SC_SCHED_FISSIONED) return 0;
+    if (p->deterministic) return 0;   // one tile per workgroup, pieces in slots: no row is added to
+    const bool fused = p->sched == SC_SCHED_FUSED;
+    if (plan_uses_wide_ttmc3(p)) return ttmc3_wide_run(p);
+    if (p->kind == K_TTMC3 && plan_wants_tensor_order(p)) return ttmc3_mfma_run(p, false);
+    if (p->kind == K_TTMC4 && plan_wants_tensor_order(p)) return ttmc4_mfma_run(p, fused ? 0 : 2, false);
+    return 0;
+}
+
 WalkShape plan_walk_shape(const sc_plan *p)
 {
     if (p->sched == SC_SCHED_LINEAR) return WalkShape{};

@@ -316,6 +316,18 @@ bool ttmc3_mfma_caps_ok(const sc_plan *p)
     return p->caps.tn <= T3_MAXR * NT && p->caps.ta <= NT && p->caps.tb + 1 <= NT && p->caps.tb >= 1;
 }
 
+// Tiles per workgroup: four runs per resident workgroup slot (shorter runs even out the tiles' different costs); a
+// deterministic schedule takes one tile per workgroup, so that the pieces are the ones the plan numbered.
+int ttmc3_mfma_run(const sc_plan *p, bool one_tile_per_workgroup)
+{
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0 || one_tile_per_workgroup) return 1;
+    const int fit = lds_workgroups_per_cu(ttmc3_lds_bytes(p->caps.tn, p->caps.ta, p->caps.tb), p->lds_per_cu);
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : 4 * fit;
+    const int want = std::min(ntiles, p->n_cu * per_cu);
+    return (ntiles + want - 1) / want;
+}
+
 sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out,
                             void *partials)
 {
@@ -342,14 +354,9 @@ sc_status launch_ttmc3_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc3_lds_bytes(a.tn, a.ta, a.tb);
-    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
-    // four runs per resident workgroup slot: shorter runs even out the tiles' different costs
-    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : 4 * fit;
-    // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
-    const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);
     a.ntiles = ntiles;
-    a.run = (ntiles + want - 1) / want;
+    a.run = ttmc3_mfma_run(p, partials != nullptr);
     const int blocks = (ntiles + a.run - 1) / a.run;
     if (T == nullptr) {
         ln.begin("ttmc3_fused_mfma");

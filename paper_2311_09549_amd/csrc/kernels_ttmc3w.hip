@@ -288,6 +288,18 @@ size_t ttmc3_wide_lds_bytes(const sc_plan *p)
     return ttmc3w_lds_bytes((int)p->fcols[0], (int)p->fcols[1], p->caps.tn, p->caps.ta, p->caps.tb);
 }
 
+// Tiles per workgroup: four runs per resident workgroup slot.
+int ttmc3_wide_run(const sc_plan *p)
+{
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0) return 1;
+    const size_t lds = ttmc3w_lds_bytes((int)p->fcols[0], (int)p->fcols[1], p->caps.tn, p->caps.ta, p->caps.tb);
+    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : 4 * fit;
+    const int want = std::min(ntiles, p->n_cu * per_cu);
+    return (ntiles + want - 1) / want;
+}
+
 sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, const void *T, void *out)
 {
     // T == nullptr: FUSED schedule; otherwise the consumer kernel of the FISSIONED schedule
@@ -314,11 +326,8 @@ sc_status launch_ttmc3_wide(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc3w_lds_bytes(L, W, a.tn, a.ta, a.tb);
-    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
-    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : 4 * fit;
-    const int want_blocks = std::min(ntiles, p->n_cu * per_cu);
     a.ntiles = ntiles;
-    a.run = (ntiles + want_blocks - 1) / want_blocks;
+    a.run = ttmc3_wide_run(p);
     const int blocks = (ntiles + a.run - 1) / a.run;
     ln.begin(T ? "ttmc3_consume_mfma_wide" : "ttmc3_fused_mfma_wide");
     bool ok = false;

@@ -452,6 +452,20 @@ bool ttmc4_mfma_caps_ok(const sc_plan *p)
            p->caps.tb >= 1;
 }
 
+// Tiles per workgroup.  Several runs per resident workgroup slot: shorter runs even out the tiles' different costs,
+// longer ones save row updates; six per slot measured best for the fused kernel (24 per compute unit), 32 per compute
+// unit for the two kernels of the FISSIONED schedule.  A deterministic schedule takes one tile per workgroup, so that
+// the pieces are the ones the plan numbered.
+int ttmc4_mfma_run(const sc_plan *p, int mode, bool one_tile_per_workgroup)
+{
+    const int ntiles = (int)p->tiles.size();
+    if (ntiles == 0 || one_tile_per_workgroup) return 1;
+    const int fit = lds_workgroups_per_cu(ttmc4_lds_bytes(p->caps.tn, p->caps.ta, p->caps.tb, mode), p->lds_per_cu);
+    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : (mode == 0 ? 6 * fit : 32);
+    const int want = std::min(ntiles, p->n_cu * per_cu);
+    return (ntiles + want - 1) / want;
+}
+
 sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *sp, const sc_dense_view *fac, int mode, const void *T1,
                             void *T2, void *out, void *partials)
 {
@@ -480,18 +494,11 @@ sc_status launch_ttmc4_mfma(const sc_plan *p, Launcher &ln, const sc_csf_view *s
     a.tn = p->caps.tn; a.ta = p->caps.ta; a.tb = p->caps.tb;
     // persistent launch over contiguous runs of tiles (the tile table of such a plan is in tensor order)
     const size_t lds = ttmc4_lds_bytes(a.tn, a.ta, a.tb, mode);
-    const int fit = lds_workgroups_per_cu(lds, p->lds_per_cu);
-    // several runs per resident workgroup slot: shorter runs even out the tiles' different costs, longer
-    // ones save row updates; six per slot measured best for the fused kernel (24 per compute unit), 32 per
-    // compute unit for the two kernels of the FISSIONED schedule
-    const int per_cu = p->tune.per_cu > 0 ? std::min(p->tune.per_cu, 64) : (mode == 0 ? 6 * fit : 32);
-    // deterministic: one tile per workgroup, so that the pieces are the ones the plan numbered
-    const int want = partials ? ntiles : std::min(ntiles, p->n_cu * per_cu);
     a.partials = static_cast<float *>(partials);
     a.slot_b = p->d_slot_b;
     if (partials && mode == 1 && !p->d_slot_b) return SC_ERR_SCHED_UNSUPPORTED;
     a.ntiles = ntiles;
-    a.run = (ntiles + want - 1) / want;
+    a.run = ttmc4_mfma_run(p, mode, partials != nullptr);
     const int blocks = (ntiles + a.run - 1) / a.run;
     if (mode == 0) {
         ln.begin("ttmc4_fused_mfma");

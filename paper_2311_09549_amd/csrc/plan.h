@@ -217,6 +217,12 @@ TileCaps default_caps(Kind kind, sc_dtype dtype, sc_sched_kind sched, const int6
 // table in tensor order rather than interleaved.
 bool plan_wants_tensor_order(const sc_plan *plan);
 
+// Tiles per workgroup of the kernel that writes the plan's output rows when that kernel is persistent over contiguous
+// runs of tiles (the matrix-core kernels); 0 for the kernels that take one tile per workgroup.  Within a run a slice that
+// continues from tile to tile stays in registers and is stored once; only a slice that crosses a run's end is added
+// atomically, so only those rows have to start from zero.  The launchers use the same number.
+int plan_output_run(const sc_plan *plan);
+
 // True for the FUSED order-3 chains that run the matrix-core kernel for rank pairs beyond 16 x 16 (kernels_ttmc3w.hip).
 bool plan_uses_wide_ttmc3(const sc_plan *plan);
 
