@@ -55,3 +55,27 @@ def test_parity_schedule_picked_by_the_cost_evaluator(oracle, cid, scale):
         assert sc.plan_chosen(con.plan) == ("linear", 0)
         con.run()
         assert_parity(oracle, cfg, data, con.result())
+
+
+@pytest.mark.parametrize("which", ["fused", "fissioned"])
+@pytest.mark.parametrize("ranks", [(16, 32), (64, 64), (128, 16)])
+def test_parity_wide_ranks_with_padded_leading_dimension(oracle, ranks, which):
+    """The matrix-core kernel for rank pairs beyond 16 x 16 with factor rows longer than the rank (ld > cols): the padding
+    holds NaN, so a read outside the first `cols` elements of a row, or a row offset taken from cols instead of ld, shows."""
+    import torch
+    from paper_2311_09549_amd import binding as sc
+    from paper_2311_09549_amd.driver import Contraction
+
+    cfg = dict(synth.config(3, 0.002), ranks=ranks)
+    data = synth.generate(cfg)
+    con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"], sc.schedule(which),
+                      synth.output_shape(cfg))
+    padded = []
+    for n, f in enumerate(con.factors):
+        big = torch.full((f.shape[0], f.shape[1] + 4 * (n + 1)), float("nan"), dtype=f.dtype, device=f.device)
+        big[:, : f.shape[1]] = f
+        padded.append(big[:, : f.shape[1]])
+        assert sc.dense_view(padded[-1]).ld == f.shape[1] + 4 * (n + 1)
+    con.factors = padded
+    con.run()
+    assert_parity(oracle, cfg, data, con.result())
