@@ -15,7 +15,7 @@ from helpers import assert_parity
 pytestmark = pytest.mark.gpu
 
 KIND_CFG = {"mttkrp3": 2, "ttmc3": 3, "sddmm_spmm": 4, "ttmc4": 5}
-RANKS = {"mttkrp3": [(8,), (16,), (32,), (64,)], "ttmc3": [(16, 16), (8, 16), (4, 32), (16, 8), (32, 64)],
+RANKS = {"mttkrp3": [(8,), (16,), (32,), (64,)], "ttmc3": [(16, 16), (8, 16), (4, 32), (16, 8), (32, 64), (16, 32), (64, 16), (128, 32)],
          "sddmm_spmm": [(16, 16), (32, 32), (64, 64), (128, 128)], "ttmc4": [(8, 8, 8), (4, 8, 8), (16, 8, 8), (12, 8, 8)]}
 KNOBS = ("tile_leaves", "tile_nodes_a", "tile_nodes_b")
 
