@@ -95,3 +95,68 @@ def test_parity_random_valid_inputs(oracle, first):
             for k in KNOBS:
                 sc.tuning_set(k, 0)
     assert ran >= 30
+
+
+# ---- kernels 5, 8 and 2 of Table 2: the all-mode TTMC under its schedules, the trailing dense products ----
+NEXT_KIND_CFG = {"ttmc_all": 6, "mttkrp_gemm": 7, "sddmm_spmm_gemm": 8}
+K5_SCHEDULES = [("fused", ()), ("fissioned", ("T1(i,j,n)", "T2(i,m,n)")), ("fissioned", ("T(i,j,n)",)), ("fused", ("T(i,m,n)",)), ("linear", ())]
+
+
+def _random_next_case(seed):
+    rng = np.random.default_rng([777, seed])
+    kind = list(NEXT_KIND_CFG)[rng.integers(0, 3)]
+    base = synth.config(NEXT_KIND_CFG[kind], 0.001)
+    order = len(base["dims"])
+    dims = tuple(int(x) for x in rng.integers(3, 200, order))
+    if order == 2:
+        dims = (max(dims), max(dims))
+    total = int(np.prod([float(d) for d in dims]))
+    nnz = int(min(rng.integers(1, 20000), total // 2))
+    if rng.integers(0, 2):
+        flat = np.unique(rng.integers(0, total, nnz))
+    else:   # most entries in the leading slices
+        flat = np.unique((rng.pareto(0.7, nnz) * 50).astype(np.int64) % total)
+    coords = [np.ascontiguousarray(c.astype(np.int32)) for c in np.unravel_index(np.sort(flat), dims)]
+    nnz = len(coords[0])
+    dtype = "f64" if rng.integers(0, 5) == 0 else "f32"
+    if kind == "ttmc_all":
+        ranks = (int(rng.choice([8, 16, 32, 64, 128])), int(rng.choice([8, 16, 32, 64])), int(rng.choice([8, 16, 32, 64])))
+        which, names = K5_SCHEDULES[rng.integers(0, 5)]
+    elif kind == "mttkrp_gemm":
+        ranks = (int(rng.choice([8, 16, 32, 64])), int(rng.choice([8, 16, 24, 64, 128])))
+        which, names = ["fused", "fissioned", "linear"][rng.integers(0, 3)], ()
+    else:
+        r = int(rng.choice([16, 32, 64]))
+        ranks = (r, r, int(rng.choice([8, 16, 48, 64])))
+        which, names = ["fused", "fissioned", "linear"][rng.integers(0, 3)], ()
+    det = bool(rng.integers(0, 2)) and which != "linear" and names != ("T(i,m,n)",)
+    cfg = dict(base, dims=dims, nnz=nnz, dtype=dtype, ranks=ranks)
+    dt = np.float64 if dtype == "f64" else np.float32
+    data = dict(cfg=cfg, coords=coords, vals=rng.uniform(-1, 1, nnz).astype(dt),
+                factors=[rng.standard_normal(s).astype(dt) for s in synth.factor_shapes(cfg)])
+    return cfg, data, which, names, det
+
+
+@pytest.mark.parametrize("first", [0, 50, 100])
+def test_parity_random_valid_inputs_of_the_composed_kernels(oracle, first):
+    ran = 0
+    for seed in range(first, first + 50):
+        cfg, data, which, names, det = _random_next_case(seed)
+        print(f"case {seed}: {cfg['kind']} {which} {names} det={det} {cfg['dtype']} ranks={cfg['ranks']} dims={cfg['dims']} nnz={cfg['nnz']}", flush=True)
+        try:
+            con = Contraction(cfg["expr"], data["coords"], data["vals"], cfg["dims"], data["factors"],
+                              sc.schedule(which, list(names), [0] * len(names), deterministic=det), synth.output_shape(cfg))
+        except sc.ScError as ex:
+            assert "SC_ERR_SCHED_UNSUPPORTED" in str(ex), ex
+            continue
+        con.out.fill_(float("nan"))
+        con.run()
+        got = con.result().copy()
+        assert_parity(oracle, cfg, data, got)   # the first failing case ends the loop
+        if det:
+            con.out.fill_(float("nan"))
+            con.run()
+            assert con.result().tobytes() == got.tobytes(), f"case {seed}: second execution differs"
+        ran += 1
+        del con
+    assert ran >= 40
