@@ -1076,11 +1076,11 @@ static sc_status plan_ttmc_all(sc_plan *p, const char *expr, const Term &lhs, co
     const int64_t units = variant <= 1 ? p->nfib[1] : p->dims[0];
     const int64_t per = variant == 1 ? 1024 : variant == 0 ? 256 : 64;
     p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>((units + per - 1) / per, (int64_t)p->n_cu * 2));
-    // From L = 32 up the contraction over the first mode is a GEMM worth the matrix cores (a workgroup takes all of L for
+    // In fp32 at L = 16, 32, 64, 128 the contraction over the first mode runs on the matrix cores (a workgroup takes all of L for
     // 64 columns of (m,n), so S is read once); its grid has M N / 64 workgroups per chunk of slices, and fewer chunks
     // keep the slots small when the output is large.
     const int64_t mn = p->fcols[1] * p->fcols[2];
-    p->k5_mfma_reduce = variant >= 2 && p->dtype == SC_F32 && (p->fcols[0] == 32 || p->fcols[0] == 64 || p->fcols[0] == 128) && mn % 64 == 0;
+    p->k5_mfma_reduce = variant >= 2 && p->dtype == SC_F32 && (p->fcols[0] == 16 || p->fcols[0] == 32 || p->fcols[0] == 64 || p->fcols[0] == 128) && mn % 64 == 0;
     if (p->k5_mfma_reduce) {
         const int64_t per_chunk = mn / 64, want = (int64_t)p->n_cu * 8;
         p->k5_nchunks = std::max<int64_t>(1, std::min<int64_t>(p->k5_nchunks, (want + per_chunk - 1) / per_chunk));

@@ -18,9 +18,9 @@
 // Both reductions are deterministic: a workgroup sums a contiguous chunk of slices (fibers) into an
 // L x (M N) tile in registers and stores it in its own slot of the workspace; sum_partials adds the
 // slots in chunk order.  The reduction over i is a dense (L x I) * (I x MN) product with I large:
-// 2 L flops per 4-byte element of S read.  At L = 16 it is bound by reading S and runs on the vector
-// ALUs (a thread per column, 16 values of l in registers); from L = 32 up it runs on the matrix cores
-// with all of L per workgroup, so that S is still read once.
+// 2 L flops per 4-byte element of S read.  In fp32 with L in {16, 32, 64, 128} and M N a multiple of 64 it runs
+// on the matrix cores with all of L per workgroup, so that S is read once whatever L is; the other cases
+// (fp64, other ranks) run on the vector ALUs, a thread per column with 16 values of l in registers.
 #include "device_common.h"
 
 namespace sck {
@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(NT) mode0_reduce_kernel(K5Args a)
     }
 }
 
-// The same partial sums on the matrix cores, fp32, L = 16 LT from 32 up, M N a multiple of 64: a workgroup takes all of L
+// The same partial sums on the matrix cores, fp32, L = 16 LT in {16, 32, 64, 128}, M N a multiple of 64: a workgroup takes all of L
 // for 64 columns (a wavefront for 16 of them), so S is read once instead of once per 16 values of l; four slices per
 // v_mfma_f32_16x16x4_f32 with C^T as operand A (l along the rows) and S as operand B, both straight from global memory
 // (a lane's 16 neighbours read 64 contiguous bytes of a row).
@@ -317,7 +317,8 @@ sc_status run_ttmc_all(const sc_plan *p, const sc_csf_view *sp, const sc_dense_v
                 if (MN % 64 != 0) return SC_ERR_SCHED_UNSUPPORTED;
                 const dim3 mgrid((unsigned)p->k5_nchunks, (unsigned)(MN / 64), 1);
                 ln.begin("ttmc_all_mode0_reduce_mfma");
-                if (L == 32) mode0_reduce_mfma_kernel<2><<<mgrid, NT, 0, stream>>>(a);
+                if (L == 16) mode0_reduce_mfma_kernel<1><<<mgrid, NT, 0, stream>>>(a);
+                else if (L == 32) mode0_reduce_mfma_kernel<2><<<mgrid, NT, 0, stream>>>(a);
                 else if (L == 64) mode0_reduce_mfma_kernel<4><<<mgrid, NT, 0, stream>>>(a);
                 else if (L == 128) mode0_reduce_mfma_kernel<8><<<mgrid, NT, 0, stream>>>(a);
                 else return SC_ERR_SCHED_UNSUPPORTED;

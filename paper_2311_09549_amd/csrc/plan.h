@@ -176,7 +176,7 @@ struct sc_plan {
     size_t k5_inner_ws_offset = 0;     // workspace of the inner plan
     size_t k5_partials_offset = 0;     // k5_nchunks x L x (M N)
     int64_t k5_nchunks = 0, k5_chunk = 0;
-    bool k5_mfma_reduce = false;       // the contraction over the first mode runs on the matrix cores (fp32, L a multiple of 16 from 32 up)
+    bool k5_mfma_reduce = false;       // the contraction over the first mode runs on the matrix cores (fp32, L in {16, 32, 64, 128}, M N a multiple of 64)
 
     // Trailing dense product (kernels 8 and 2 of Table 2): the sparse part runs as an inner plan (MTTKRP, or kernel 1)
     // whose rows, one per coordinate of the first mode, pass through the workspace.
